@@ -1,0 +1,32 @@
+"""ORACLE (test infrastructure): one-step-stale form of the lock-free update.
+
+Follows Alg. 2 reduced to one GPU with no SSD and no forward/backward: the updating actor applies
+the *buffered* gradient g' ("Update p32, m32, v32 via g'16"), then the buffer is cleared and the
+16-bit parameters are refreshed by the cast; a newly produced gradient is accumulated into the
+cleared buffer (0 + g = g exactly, one gradient per update).  Each call applies the gradient handed
+over by the previous call; a call without a gradient flushes the buffer.
+"""
+from __future__ import annotations
+
+from typing import Optional, Sequence
+
+import numpy as np
+
+from .adamw import Hyper, PagedAdamWState
+
+
+class DelayedStepper:
+    def __init__(self, state: PagedAdamWState):
+        self.state = state
+        self.buffered: Optional[np.ndarray] = None   # g' (bf16 bits), None = empty
+        self.applied = 0                              # number of updates applied so far
+
+    def step(self, new_g16_pages: Optional[np.ndarray], h: Hyper,
+             pages: Optional[Sequence[int]] = None):
+        """Returns (norms, skips) of the update applied by this call, or None if none was."""
+        out = None
+        if self.buffered is not None:
+            self.applied += 1
+            out = self.state.step(self.buffered, self.applied, h, pages)
+        self.buffered = None if new_g16_pages is None else new_g16_pages.copy()
+        return out

@@ -1,0 +1,65 @@
+"""One-step-stale stepping: N delayed calls plus a flush equal N synchronous steps bit for bit,
+and before the flush the state equals N-1 synchronous steps."""
+import numpy as np
+
+import oracle
+
+
+def make(seed, n_pages=3, Ep=32):
+    rng = np.random.default_rng(seed)
+    p32 = (rng.standard_normal((n_pages, Ep)) * 0.02).astype(np.float32)
+    used = [Ep, 20, 5]
+    return p32, used
+
+
+def grads(seed, T, shape):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(T):
+        a = (rng.standard_normal(shape) * 1e-3).astype(np.float32)
+        out.append((a.view(np.uint32) >> 16).astype(np.uint16))
+    out[2][1, :] = 0     # a page without gradient at one step
+    return out
+
+
+def state_bytes(st):
+    return b"".join(a.tobytes() for a in (st.p, st.m, st.v, st.p16))
+
+
+def test_delayed_plus_flush_equals_sync():
+    T = 6
+    h = oracle.Hyper(max_grad_norm=0.004, skip_mode=1)
+    p32, used = make(0)
+    gs = grads(1, T, p32.shape)
+
+    sync = oracle.PagedAdamWState(p32, used)
+    snaps = [state_bytes(sync)]
+    for t in range(T):
+        sync.step(gs[t], t + 1, h)
+        snaps.append(state_bytes(sync))
+
+    st = oracle.PagedAdamWState(p32, used)
+    d = oracle.DelayedStepper(st)
+    for t in range(T):
+        out = d.step(gs[t], h)
+        assert (out is None) == (t == 0)
+        assert state_bytes(st) == snaps[t]          # one step behind the synchronous run
+        assert d.applied == t
+    d.step(None, h)                                  # flush
+    assert state_bytes(st) == snaps[T] and d.applied == T
+    assert d.step(None, h) is None                   # nothing left to flush
+    assert state_bytes(st) == snaps[T]
+
+
+def test_buffered_gradient_is_a_copy():
+    p32, used = make(2)
+    st = oracle.PagedAdamWState(p32, used)
+    d = oracle.DelayedStepper(st)
+    g = grads(3, 3, p32.shape)[0]
+    d.step(g, oracle.Hyper())
+    keep = g.copy()
+    g[:] = 0                                         # the producer reuses its buffer
+    d.step(None, oracle.Hyper())
+    ref = oracle.PagedAdamWState(p32, used)
+    ref.step(keep, 1, oracle.Hyper())
+    assert state_bytes(st) == state_bytes(ref)
