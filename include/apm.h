@@ -1,0 +1,280 @@
+/*
+ * apm — page-granular mixed-precision AdamW for MI355X (gfx950).  C ABI.
+ *
+ * The library implements, on one GPU, the optimizer-update hot path of Angel-PTM
+ * (arXiv 2303.02868): model states live in fixed-size pages (Sec. 4.1), the update of the FP32
+ * master parameter / momentum / variance from 16-bit gradients and the cast back to 16-bit
+ * parameters run page by page (Alg. 2; Sec. 4.3, last paragraph), pages move between pinned host
+ * memory and HBM asynchronously (Sec. 5 "Allocator") overlapped with the update (Sec. 4.2), and a
+ * one-step-stale variant decouples gradient production from the update (Sec. 4.3, Alg. 2).
+ *
+ * Conventions
+ *   - Every function returns an apm_status (0 = ok, negative = error) unless stated; nothing
+ *     throws or aborts.  On error, outputs are untouched and apm_last_error() describes the cause.
+ *   - "device pointer" = HBM or pinned-host memory the GPU can address; "host pointer" = ordinary
+ *     host memory read or written by the CPU during the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  GPU work is enqueued
+ *     on it and the call returns without waiting; only argument and capacity errors are reported
+ *     synchronously.
+ *   - A pool and everything it owns belong to one HIP device.  Calls on one pool must be issued
+ *     from one thread at a time and, unless stated, be ordered by the caller's streams: the pool's
+ *     internal scratch is shared by its calls.
+ *   - Element counts are in elements, never bytes, unless the name says bytes.
+ */
+#ifndef APM_H
+#define APM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct apm_pool apm_pool;
+typedef struct apm_streamer apm_streamer;
+
+enum apm_status {
+    APM_OK = 0,
+    APM_EINVAL = -1,  /* bad argument */
+    APM_ENOMEM = -2,  /* allocation failed or pool capacity exceeded */
+    APM_ERANGE = -3,  /* page / state index out of range */
+    APM_EDEVICE = -4, /* HIP runtime error or wrong device kind */
+    APM_ESTATE = -5   /* call not valid in the pool's current state */
+};
+
+/* Where a pool's pages live.  The paper's device map is {0: GPU, 1: CPU, 2: SSD} (Page listing,
+ * Sec. 4.1); the SSD tier is not built. */
+enum apm_device { APM_DEV_GPU = 0, APM_DEV_HOST = 1 };
+
+enum apm_dtype { APM_F32 = 0, APM_BF16 = 1 };
+
+/* The five state classes of a page group (Alg. 2 inputs): FP32 master parameter, momentum,
+ * variance; 16-bit gradient; 16-bit (buffered) parameter.  16-bit means bf16 (Sec. 6.1). */
+enum apm_state { APM_P32 = 0, APM_M32 = 1, APM_V32 = 2, APM_G16 = 3, APM_P16 = 4, APM_N_STATES = 5 };
+
+enum apm_skip_mode {
+    APM_SKIP_NONE = 0,     /* every listed page is updated; zero gradients are ordinary gradients */
+    APM_SKIP_UNTOUCHED = 1 /* a page whose used gradient elements are all +-0 is left bit-identical */
+};
+
+enum apm_pool_flags {
+    APM_POOL_NO_ZERO = 1u /* do not zero-fill at creation; the caller guarantees that unused page
+                             elements (padding, alignment gaps) are zero in every state class */
+};
+
+/*
+ * Pool description.  Page group k of a pool is the element range [k*E, (k+1)*E) of each state
+ * class the pool stores; class s is one contiguous region of n_pages*E elements (fp32 classes
+ * 4 B/element, bf16 classes 2 B/element), so consecutive pages are contiguous in memory.
+ * With E = 1048576 an fp32 page is the paper's 4 MB page (Sec. 4.1 "Optimal Page Size").
+ */
+typedef struct {
+    int32_t device;     /* apm_device */
+    int32_t hip_device; /* HIP device ordinal that owns / addresses the pool */
+    int64_t page_elems; /* E > 0, a multiple of 8 */
+    int64_t n_pages;    /* capacity in page groups, > 0 */
+    uint32_t state_mask; /* bit s set = the pool stores state class s */
+    uint32_t flags;      /* apm_pool_flags */
+    /* base[s] != NULL: caller-owned region for class s (n_pages*E elements, 16-byte aligned,
+     * HBM for a GPU pool, pinned host memory for a HOST pool); it must outlive the pool.
+     * base[s] == NULL: the library allocates (hipMalloc / hipHostMalloc) and frees it. */
+    void* base[APM_N_STATES];
+} apm_pool_desc;
+
+/* A caller-owned contiguous tensor.  `data` is a device pointer (see Conventions) of `numel`
+ * elements of `dtype`, or NULL where a call only needs the size.  `id` is the caller's tensor id,
+ * recorded in the page table (Tensor listing, Sec. 4.1). */
+typedef struct {
+    int64_t id;
+    int32_t dtype; /* apm_dtype */
+    int32_t reserved;
+    int64_t numel;
+    void* data;
+} apm_tensor;
+
+/* One contiguous piece of a tensor inside one page: elements [tensor_off, tensor_off+n) of tensor
+ * number `tensor` (its index in the list) sit at [page_off, page_off+n) of page `page`. */
+typedef struct {
+    int64_t tensor, tensor_off, page, page_off, n;
+} apm_segment;
+
+/* Page-table entry, after the Page listing of Sec. 4.1 (sizes in elements of the page group). */
+typedef struct {
+    int64_t total_elems;     /* E */
+    int64_t used_elems;      /* end offset of the last occupied element */
+    int64_t available_elems; /* E - used_elems */
+    int32_t device;          /* apm_device of the pool */
+    int32_t n_tensors;       /* 0, 1 or 2 */
+    int64_t tensor_id[2];    /* caller ids of the tenants (-1 = none) */
+    int64_t tensor_elems[2]; /* elements each tenant occupies in this page */
+} apm_page_info;
+
+/* Optimizer hyper-parameters, as doubles; the library derives every step-dependent scalar in
+ * double and rounds it to fp32 once.  max_grad_norm <= 0 switches per-page clipping off. */
+typedef struct {
+    double lr, beta1, beta2, eps, weight_decay, max_grad_norm;
+    int32_t skip_mode; /* apm_skip_mode */
+    int32_t reserved;
+} apm_hyper;
+
+/* ---- errors ------------------------------------------------------------------------------ */
+
+/* Message of the calling thread's last failed call (library-owned, valid until the thread's next
+ * failing call); "" if none. */
+const char* apm_last_error(void);
+
+/* ---- packing plan (host only; no GPU is touched) ------------------------------------------- */
+
+/*
+ * Deterministic layout of a ragged tensor list in pages of E elements (Sec. 4.1: at most two
+ * tensors per page; a tensor smaller than a page takes a page of its own).  Tensors are placed in
+ * list order; numel == 0 takes no page; 0 < numel < E takes a fresh page at offset 0 that admits
+ * no second tenant; numel >= E starts in the open page if there is one (a page with one tenant and
+ * room left after rounding its used extent up to 8 elements), else in a fresh page, continues
+ * through fresh pages, and leaves its partly filled last page open.
+ *
+ * numels: host pointer, n entries >= 0.  segs: host pointer, capacity *n_segs on entry, count on
+ * return (NULL with *n_segs == 0 to query the count only).  n_pages, fragmentation
+ * (= 1 - sum(numel) / (n_pages*E)) : host pointers, nullable.
+ * Errors: APM_EINVAL (bad E, negative numel, NULL n_segs), APM_ENOMEM (*n_segs too small; the
+ * needed count is still returned in *n_segs).
+ */
+int apm_pack_plan(int64_t page_elems, const int64_t* numels, int64_t n, apm_segment* segs,
+                  int64_t* n_segs, int64_t* n_pages, double* fragmentation);
+
+/* ---- pool and page table (Sec. 4.1 Page; Sec. 5 "Allocator": pre-allocated memory cut into
+ *      fixed-size pages) --------------------------------------------------------------------- */
+
+/* Creates a pool.  *out is written only on success.  Library-allocated regions, and caller regions
+ * unless APM_POOL_NO_ZERO, are zero-filled (synchronously).  Errors: APM_EINVAL, APM_ENOMEM,
+ * APM_EDEVICE. */
+int apm_pool_create(apm_pool** out, const apm_pool_desc* desc);
+
+/* Waits for the pool's internal streams, frees what the library allocated.  NULL is accepted. */
+int apm_pool_destroy(apm_pool* pool);
+
+/* Number of pages the installed layout occupies (0 before any layout). */
+int64_t apm_pool_pages_in_use(const apm_pool* pool);
+
+/* Page-table entry of `page` (host pointer out).  APM_ERANGE if page >= capacity. */
+int apm_pool_page_info(const apm_pool* pool, int64_t page, apm_page_info* out);
+
+/* Device pointer of the first element of `page` in class `state`, or NULL (class not stored, page
+ * out of range). */
+void* apm_pool_state_ptr(const apm_pool* pool, int state, int64_t page);
+
+/*
+ * Installs the layout of a tensor list (apm_pack_plan's rule) in the pool's page table without
+ * copying data — tensors are then "born" in pages.  Only id and numel of each tensor are read.
+ * Re-installing a different layout zero-fills every class the pool stores first (on `stream`).
+ * Outputs as in apm_pack_plan.  Errors: APM_ENOMEM if the layout needs more pages than the pool
+ * has.
+ */
+int apm_pool_set_layout(apm_pool* pool, const apm_tensor* tensors, int64_t n, apm_segment* segs,
+                        int64_t* n_segs, int64_t* n_pages, double* fragmentation, void* stream);
+
+/* ---- pack / unpack (gather / scatter kernels; the Tensor listing's merge is apm_unpack) ---- */
+
+/*
+ * Copies the tensors' elements, bit for bit, into class `state` of the pool's pages.  If the pool
+ * has no layout yet the list's layout is installed first; otherwise the list must have the same
+ * numels as the installed layout (APM_ESTATE if not).  tensors[i].dtype must match the class
+ * (APM_F32 for P32/M32/V32, APM_BF16 for G16/P16) and tensors[i].data must be a device pointer
+ * (any alignment; 16-byte alignment takes the fast path).  Padding is not written: it stays zero.
+ * Outputs as in apm_pack_plan.  Asynchronous on `stream`.
+ */
+int apm_pack_tensors(apm_pool* pool, int state, const apm_tensor* tensors, int64_t n,
+                     apm_segment* segs, int64_t* n_segs, int64_t* n_pages, double* fragmentation,
+                     void* stream);
+
+/* Inverse of apm_pack_tensors: scatters class `state` of the pages back into the contiguous
+ * tensors dst[i].data.  The list must match the installed layout.  Asynchronous on `stream`. */
+int apm_unpack(apm_pool* pool, int state, const apm_tensor* dst, int64_t n, void* stream);
+
+/* ---- the update (Alg. 2 "Update p32, m32, v32 via g16", "p'16 <- cast(p32)") -------------- */
+
+/*
+ * One AdamW step on the listed pages of a GPU pool that stores all five classes.
+ * For each listed page k with used extent n_k, with t = step (1-based, global):
+ *   nz = any used gradient element with non-zero magnitude bits; if skip_mode is
+ *   APM_SKIP_UNTOUCHED and !nz: skip_mask = 1, grad_norm = 0, page untouched.  Otherwise
+ *   norm = sqrt(sum g^2) over the used elements (fp64 accumulation, fixed order),
+ *   s = max_grad_norm > 0 ? min(1, max_grad_norm / (norm + 1e-6)) : 1,  g^ = s*g,
+ *   m' = b1 m + (1-b1) g^;  v' = b2 v + (1-b2) g^2;
+ *   p' = p (1 - lr wd) - lr (m'/(1-b1^t)) / (sqrt(v'/(1-b2^t)) + eps);   p16' = bf16_rne(p').
+ * Arithmetic is fp32 with correctly rounded divide and square root.
+ *
+ * pages: host pointer to n_pages distinct page indices, or NULL = pages [0, n_pages).
+ * grad_norm (float[n_pages]) and skip_mask (uint8_t[n_pages]): device pointers, nullable,
+ * indexed like `pages`, written by the kernel.
+ * Errors: APM_EINVAL (step < 1, bad hyper-parameters, NULL hyper), APM_ERANGE (page index),
+ * APM_ESTATE (pool lacks a class), APM_EDEVICE.
+ */
+int apm_page_adamw_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
+                        const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,
+                        void* stream);
+
+/* ---- page movement (Page listing: move; Sec. 5 "Allocator": asynchronous GPU-CPU copies) --- */
+
+/*
+ * Copies class `state` of n_pages consecutive pages, src_page.. of `src` to dst_page.. of `dst`
+ * (one asynchronous copy; H2D, D2H, D2D or H2H according to the pools' devices).  Both pools
+ * must have the same page_elems and store the class.  Page-table entries are not copied.
+ */
+int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_page,
+                        int64_t n_pages, int state, void* stream);
+
+/* ---- streamed update: FP32 states in pinned host pages, double-buffered through HBM
+ *      (Sec. 4.2: overlap movement with computation, scheduled per page) -------------------- */
+
+/*
+ * host:   HOST pool storing P32, M32, V32 (the layout is taken from `dev`).
+ * dev:    GPU pool storing G16 and P16 for the same pages, with an installed layout.
+ * batch_pages: pages moved and updated per pipeline stage (>= 1).
+ * n_slots: staging slots in HBM (>= 2); each holds batch_pages pages of the three fp32 classes.
+ * The streamer owns three streams (copy-in, compute, copy-out), its staging memory and events.
+ */
+int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool* dev, int64_t batch_pages,
+                        int n_slots);
+int apm_streamer_destroy(apm_streamer* s);
+
+/*
+ * One AdamW step over all pages in use: for batch b, H2D(b+1) on the copy-in stream runs beside
+ * update(b) on the compute stream and D2H(b-1) on the copy-out stream, ordered by events.
+ * The work starts after everything enqueued on `stream` so far, and `stream` is made to wait for
+ * the step's completion; the host does not block.  grad_norm / skip_mask as in
+ * apm_page_adamw_step (device pointers, one entry per page in use, nullable).
+ */
+int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, float* grad_norm,
+                      uint8_t* skip_mask, void* stream);
+
+/* ---- one-step-stale update (Alg. 2 reduced to one GPU: apply the buffered gradient while the
+ *      next one is being staged) -------------------------------------------------------------- */
+
+/*
+ * new_g16 != NULL: device pointer to a gradient for the whole pool in page layout (capacity
+ * n_pool_pages*E bf16 elements; only the used extents of the listed pages are read).  The call
+ *   (1) if a gradient is buffered, increments the pool's applied-update counter c and enqueues the
+ *       AdamW step with t = c on the buffered gradient on the pool's internal update stream;
+ *   (2) enqueues, on `stream`, the staging of new_g16 into the other half of the pool's ping-pong
+ *       gradient buffer; the caller may reuse new_g16 once `stream` has passed this point.
+ * new_g16 == NULL flushes: applies the buffered gradient if any and makes `stream` wait for the
+ * update stream.  The page list (as in apm_page_adamw_step) must be the same on every call
+ * between two flushes.  P16 is rewritten asynchronously by the update stream: a reader that does
+ * not flush may see parameters one step stale, which is the mechanism's stated trade-off.
+ */
+int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
+                     const apm_hyper* hyper, void* stream);
+
+/* Number of updates apm_step_delayed has applied (enqueued) on this pool so far. */
+int64_t apm_delayed_applied(const apm_pool* pool);
+
+/* Per-page outputs of the delayed path: device pointers (float[n] / uint8_t[n], nullable) the
+ * update kernels of later apm_step_delayed calls write, indexed like their page list. */
+int apm_delayed_set_outputs(apm_pool* pool, float* grad_norm, uint8_t* skip_mask);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APM_H */

@@ -113,17 +113,25 @@ class PagedAdamWState:
         self.p16 = (np.zeros(p32_pages.shape, dtype=np.uint16) if p16_pages is None
                     else p16_pages.copy())
 
-    def step(self, g16_pages: np.ndarray, t: int, h: Hyper, pages: Optional[Sequence[int]] = None):
+    def step(self, g16_pages: np.ndarray, t: int, h: Hyper, pages: Optional[Sequence[int]] = None,
+             threads: int = 1):
         """Apply one step to the listed pages (default all).  Returns (norms fp32, skip uint8),
-        indexed like `pages`."""
+        indexed like `pages`.  Pages are independent, so `threads` > 1 only spreads whole pages
+        over host threads; the per-page arithmetic is unchanged."""
         assert g16_pages.dtype == np.uint16 and g16_pages.shape == self.p.shape
-        idx = range(self.n_pages) if pages is None else pages
-        norms: List[np.float32] = []
-        skips: List[int] = []
-        for k in idx:
+        idx = list(range(self.n_pages) if pages is None else pages)
+
+        def one(k):
             n = int(self.used[k])
-            nrm, sk = page_adamw(self.p[k, :n], self.m[k, :n], self.v[k, :n], self.p16[k, :n],
-                                 g16_pages[k, :n], t, h)
-            norms.append(nrm)
-            skips.append(int(sk))
-        return np.array(norms, dtype=np.float32), np.array(skips, dtype=np.uint8)
+            return page_adamw(self.p[k, :n], self.m[k, :n], self.v[k, :n], self.p16[k, :n],
+                              g16_pages[k, :n], t, h)
+
+        if threads > 1 and len(idx) > 1:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=threads) as ex:
+                res = list(ex.map(one, idx))
+        else:
+            res = [one(k) for k in idx]
+        norms = np.array([r[0] for r in res], dtype=np.float32)
+        skips = np.array([int(r[1]) for r in res], dtype=np.uint8)
+        return norms, skips

@@ -1,0 +1,290 @@
+// Page AdamW kernels for gfx950: per-slice gradient reduction and the fused update.
+//
+// Both kernels are HBM-bandwidth bound (no reuse, ~20 fp32 operations per element), so the design
+// is about memory access only: every wavefront instruction touches one fully contiguous span
+// (1 KiB for the 128-bit fp32 accesses, 512 B for the 64-bit bf16 accesses), each lane keeps
+// several independent loads in flight, and a workgroup never straddles a page.
+//
+// Work decomposition: grid.y walks the listed pages, grid.x the fixed-size slices of a page;
+// slices that start beyond the page's used extent exit at once.  The page table (`used`) is read
+// on the device, so a call needs no host-side knowledge of extents.
+#include "apm_internal.h"
+
+namespace apm {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kWave = 64;
+
+__device__ __forceinline__ double shfl_xor_f64(double x, int off) {
+    int lo = __double2loint(x), hi = __double2hiint(x);
+    lo = __shfl_xor(lo, off, kWave);
+    hi = __shfl_xor(hi, off, kWave);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the wavefront in a fixed butterfly order; every lane ends with the same value.
+__device__ __forceinline__ double wave_sum_f64(double x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += shfl_xor_f64(x, off);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x |= (uint32_t)__shfl_xor((int)x, off, kWave);
+    return x;
+}
+
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Round-to-nearest-even of an fp32 value to bf16 bits, on the integer representation.
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+struct ReduceArgs {
+    const uint16_t* g16;
+    const int32_t* used;
+    const int64_t* grad_pages;
+    int64_t grad_first;
+    int64_t list_offset;
+    int64_t E;
+    double* partials;
+    uint32_t* nzflags;
+    int32_t S;
+};
+
+// Per (page, slice): sum of squares in fp64 and OR of the magnitude bits of the slice's used
+// gradient elements.  Slice 0 always writes (a zero for an empty page); other slices only when
+// they hold used elements.  The fixed order (lane-sequential, wavefront butterfly, wave 0..3)
+// makes the result independent of scheduling.
+__global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a) {
+    const int64_t i = a.list_offset + blockIdx.y;
+    const int64_t page = a.grad_pages ? a.grad_pages[i] : a.grad_first + i;
+    const int used = a.used[page];
+    const int start = blockIdx.x * kReduceTile;
+    if (start >= used && blockIdx.x != 0) return;
+    const int end = min(start + kReduceTile, used);
+    const uint16_t* g = a.g16 + page * a.E;
+
+    double acc = 0.0;
+    uint32_t nz = 0;
+    constexpr int kIters = kReduceTile / (kThreads * 8);
+    u32x4 w[kIters];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int e = start + (it * kThreads + (int)threadIdx.x) * 8;
+        w[it] = u32x4{0u, 0u, 0u, 0u};
+        if (e < end) w[it] = *reinterpret_cast<const u32x4*>(g + e);
+    }
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int e = start + (it * kThreads + (int)threadIdx.x) * 8;
+        if (e + 8 > end) {  // boundary vector: drop the elements at or beyond the used extent
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t x = w[it][j];
+                if (e + 2 * j >= end) x = 0u;
+                else if (e + 2 * j + 1 >= end) x &= 0x0000FFFFu;
+                w[it][j] = x;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t x = w[it][j];
+            nz |= x & 0x7FFF7FFFu;
+            const double lo = (double)bf16lo(x), hi = (double)bf16hi(x);
+            acc = fma(lo, lo, acc);
+            acc = fma(hi, hi, acc);
+        }
+    }
+    acc = wave_sum_f64(acc);
+    nz = wave_or_u32(nz);
+    __shared__ double s_acc[kThreads / kWave];
+    __shared__ uint32_t s_nz[kThreads / kWave];
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        s_acc[wave] = acc;
+        s_nz[wave] = nz;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = s_acc[0];
+        uint32_t z = s_nz[0];
+#pragma unroll
+        for (int k = 1; k < kThreads / kWave; ++k) {
+            t += s_acc[k];
+            z |= s_nz[k];
+        }
+        a.partials[i * a.S + blockIdx.x] = t;
+        a.nzflags[i * a.S + blockIdx.x] = z;
+    }
+}
+
+struct UpdateArgs {
+    float* p32;
+    float* m32;
+    float* v32;
+    const uint16_t* g16;
+    uint16_t* p16;
+    const int32_t* used;
+    const int64_t* state_pages;
+    const int64_t* grad_pages;
+    int64_t state_first;
+    int64_t grad_first;
+    int64_t list_offset;
+    int64_t E;
+    const double* partials;
+    const uint32_t* nzflags;
+    int32_t S;
+    int32_t skip_mode;
+    float* grad_norm;
+    uint8_t* skip_mask;
+    double max_norm;
+    float b1, omb1, b2, omb2, inv_sqrt_bc2, eps, step_size, lr_wd;
+};
+
+__device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g, const UpdateArgs& a,
+                                           float scale) {
+    const float gs = g * scale;
+    m = fmaf(a.b1, m, a.omb1 * gs);
+    v = fmaf(a.b2, v, a.omb2 * (gs * gs));
+    const float denom = fmaf(sqrtf(v), a.inv_sqrt_bc2, a.eps);
+    // p' = p - (lr wd p + (lr/bc1) m'/denom): the two small terms are summed first, so the only
+    // rounding at the magnitude of p is the final subtraction (half an ulp per step).
+    const float delta = fmaf(a.step_size, m / denom, a.lr_wd * p);
+    p = p - delta;
+}
+
+// Fused update of one slice of one page: 12 B + 2 B read and 12 B + 2 B written per element.
+// U = 128-bit vectors per lane and state class kept in flight.
+template <int U>
+__global__ __launch_bounds__(kThreads) void apm_adamw_kernel(UpdateArgs a) {
+    const int64_t i = a.list_offset + blockIdx.y;
+    const int64_t gpage = a.grad_pages ? a.grad_pages[i] : a.grad_first + i;
+    const int used = a.used[gpage];
+    const int used8 = (used + 7) & ~7;
+    const int start = blockIdx.x * (kThreads * 4 * U);
+    const bool lead = blockIdx.x == 0;
+    if (start >= used8 && !lead) return;
+
+    float scale = 1.0f;
+    if (a.partials) {
+        // Combine the page's slice partials in a fixed order (same in every wavefront).
+        const int n_slices = max(1, (used + kReduceTile - 1) / kReduceTile);
+        const int lane = threadIdx.x & (kWave - 1);
+        double s = 0.0;
+        uint32_t nz = 0;
+        for (int k = lane; k < n_slices; k += kWave) {
+            s += a.partials[i * a.S + k];
+            nz |= a.nzflags[i * a.S + k];
+        }
+        s = wave_sum_f64(s);
+        nz = wave_or_u32(nz);
+        const bool skip = a.skip_mode == APM_SKIP_UNTOUCHED && nz == 0u;
+        const double norm = sqrt(s);
+        if (lead && threadIdx.x == 0) {
+            if (a.grad_norm) a.grad_norm[i] = skip ? 0.0f : (float)norm;
+            if (a.skip_mask) a.skip_mask[i] = skip ? 1 : 0;
+        }
+        if (skip) return;
+        if (a.max_norm > 0.0) {
+            const double sc = a.max_norm / (norm + 1e-6);
+            scale = sc < 1.0 ? (float)sc : 1.0f;
+        }
+    }
+    if (start >= used8) return;
+
+    const int64_t spage = a.state_pages ? a.state_pages[i] : a.state_first + i;
+    f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
+    f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
+    f32x4* __restrict__ V = reinterpret_cast<f32x4*>(a.v32 + spage * a.E);
+    const u32x2* __restrict__ G = reinterpret_cast<const u32x2*>(a.g16 + gpage * a.E);
+    u32x2* __restrict__ P16 = reinterpret_cast<u32x2*>(a.p16 + gpage * a.E);
+
+    const int nvec = used8 >> 2;
+    const int v0 = (start >> 2) + (int)threadIdx.x;
+    f32x4 p[U], m[U], v[U];
+    u32x2 g[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int vi = v0 + u * kThreads;
+        if (vi < nvec) {
+            g[u] = __builtin_nontemporal_load(G + vi);
+            p[u] = __builtin_nontemporal_load(P + vi);
+            m[u] = __builtin_nontemporal_load(M + vi);
+            v[u] = __builtin_nontemporal_load(V + vi);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int vi = v0 + u * kThreads;
+        if (vi < nvec) {
+            const float gf[4] = {bf16lo(g[u][0]), bf16hi(g[u][0]), bf16lo(g[u][1]), bf16hi(g[u][1])};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float pj = p[u][j], mj = m[u][j], vj = v[u][j];
+                adamw_elem(pj, mj, vj, gf[j], a, scale);
+                p[u][j] = pj;
+                m[u][j] = mj;
+                v[u][j] = vj;
+            }
+            u32x2 o;
+            o[0] = f32_to_bf16_rne(p[u][0]) | (f32_to_bf16_rne(p[u][1]) << 16);
+            o[1] = f32_to_bf16_rne(p[u][2]) | (f32_to_bf16_rne(p[u][3]) << 16);
+            __builtin_nontemporal_store(p[u], P + vi);
+            __builtin_nontemporal_store(m[u], M + vi);
+            __builtin_nontemporal_store(v[u], V + vi);
+            __builtin_nontemporal_store(o, P16 + vi);
+        }
+    }
+}
+
+constexpr int kUpdateU = 4;
+constexpr int kMaxGridY = 65535;
+
+}  // namespace
+
+hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
+    ReduceArgs a{L.g16, L.used, L.grad_pages, L.grad_first, 0, L.E, L.partials, L.nzflags, L.S};
+    for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
+        const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
+        a.list_offset = off;
+        hipLaunchKernelGGL(apm_grad_reduce_kernel, dim3((unsigned)L.S, (unsigned)ny), dim3(kThreads), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
+    UpdateArgs a{};
+    a.p32 = L.p32; a.m32 = L.m32; a.v32 = L.v32; a.g16 = L.g16; a.p16 = L.p16;
+    a.used = L.used; a.state_pages = L.state_pages; a.grad_pages = L.grad_pages;
+    a.state_first = L.state_first; a.grad_first = L.grad_first; a.E = L.E;
+    a.partials = L.partials; a.nzflags = L.nzflags; a.S = L.S; a.skip_mode = L.skip_mode;
+    a.grad_norm = L.grad_norm; a.skip_mask = L.skip_mask; a.max_norm = L.max_norm;
+    a.b1 = L.b1; a.omb1 = L.omb1; a.b2 = L.b2; a.omb2 = L.omb2;
+    a.inv_sqrt_bc2 = L.inv_sqrt_bc2; a.eps = L.eps; a.step_size = L.step_size; a.lr_wd = L.lr_wd;
+    constexpr int64_t tile = kThreads * 4 * kUpdateU;
+    const unsigned nx = (unsigned)((L.E + tile - 1) / tile);
+    for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
+        const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
+        a.list_offset = off;
+        hipLaunchKernelGGL(apm_adamw_kernel<kUpdateU>, dim3(nx, (unsigned)ny), dim3(kThreads), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace apm

@@ -1,0 +1,142 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "apm.h"
+
+namespace apm {
+
+// ---- errors -------------------------------------------------------------------------------
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define APM_HIP(expr)                                                                   \
+    do {                                                                                \
+        hipError_t apm_e_ = (expr);                                                     \
+        if (apm_e_ != hipSuccess)                                                       \
+            return ::apm::fail(APM_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(apm_e_)); \
+    } while (0)
+
+// ---- packing plan -------------------------------------------------------------------------
+constexpr int64_t kAlign = 8;  // elements; keeps 128-bit accesses aligned for both widths
+
+struct PageEntry {
+    int64_t used = 0;
+    int32_t n_tensors = 0;
+    int64_t tensor[2] = {-1, -1};  // index in the tensor list
+    int64_t tensor_elems[2] = {0, 0};
+};
+
+struct Plan {
+    int64_t E = 0;
+    int64_t total = 0;
+    std::vector<apm_segment> segs;
+    std::vector<PageEntry> pages;
+};
+
+int make_plan(int64_t E, const int64_t* numels, int64_t n, Plan* out);
+int emit_plan(const Plan& plan, apm_segment* segs, int64_t* n_segs, int64_t* n_pages,
+              double* fragmentation);
+
+inline int elem_bytes(int state) { return state <= APM_V32 ? 4 : 2; }
+
+// ---- pinned staging ring: small host arrays (page lists, copy descriptors) to the device ----
+struct StageRing {
+    static constexpr int K = 8;
+    void* h[K] = {};
+    void* d[K] = {};
+    size_t cap[K] = {};
+    hipEvent_t ev[K] = {};
+    bool busy[K] = {};
+    int next = 0;
+    // Returns a slot whose previous use has completed, with at least `bytes` capacity.
+    int acquire(size_t bytes, int* slot);
+    // Copies the first `bytes` of the slot's host buffer to its device buffer on `s`.
+    int commit(int slot, size_t bytes, hipStream_t s);
+    void destroy();
+};
+
+// ---- kernels ------------------------------------------------------------------------------
+constexpr int kReduceTile = 16384;  // gradient elements per workgroup of the reduce kernel
+
+struct AdamwLaunch {
+    float* p32;
+    float* m32;
+    float* v32;
+    const uint16_t* g16;
+    uint16_t* p16;
+    const int32_t* used;          // device, indexed by grad page id
+    const int64_t* state_pages;   // device list or nullptr (then state_first + i)
+    const int64_t* grad_pages;    // device list or nullptr (then grad_first + i)
+    int64_t state_first;
+    int64_t grad_first;
+    int64_t n_listed;
+    int64_t E;
+    double* partials;             // [n_listed][S] per-slice sums of squares; nullptr = no reduce pass
+    uint32_t* nzflags;            // [n_listed][S] per-slice OR of magnitude bits
+    int32_t S;                    // slices per page = ceil(E / kReduceTile)
+    float* grad_norm;             // device, nullable
+    uint8_t* skip_mask;           // device, nullable
+    float b1, omb1, b2, omb2, inv_sqrt_bc2, eps, step_size, lr_wd;
+    double max_norm;
+    int32_t skip_mode;
+};
+
+hipError_t launch_grad_reduce(const AdamwLaunch& a, hipStream_t s);
+hipError_t launch_adamw(const AdamwLaunch& a, hipStream_t s);
+
+struct SegDesc {
+    const void* src;
+    void* dst;
+    int64_t nbytes;
+};
+hipError_t launch_seg_copy(const SegDesc* d_descs, int64_t n, int64_t max_bytes, hipStream_t s);
+
+// Fills the scalar fields of `a` from the hyper-parameters (all derived in double, rounded once).
+int prepare_hyper(const apm_hyper* h, int64_t step, AdamwLaunch* a);
+
+}  // namespace apm
+
+struct apm_pool {
+    apm_pool_desc desc{};
+    void* base[APM_N_STATES] = {};
+    bool owned[APM_N_STATES] = {};
+
+    bool has_layout = false;
+    std::vector<int64_t> layout_numels;
+    std::vector<int64_t> layout_ids;
+    apm::Plan plan;
+
+    int32_t* d_used = nullptr;      // device page table: used extent per page
+    double* d_partials = nullptr;   // reduce scratch, n_pages * S
+    uint32_t* d_nzflags = nullptr;
+    int32_t S = 0;
+    apm::StageRing ring;
+
+    // one-step-stale update state
+    hipStream_t upd_stream = nullptr;
+    uint16_t* gbuf[2] = {nullptr, nullptr};
+    hipEvent_t ev_staged[2] = {};
+    hipEvent_t ev_applied[2] = {};
+    bool applied_valid[2] = {false, false};
+    hipEvent_t ev_flush = nullptr;
+    int cur = 0;
+    bool buffered = false;
+    int64_t applied = 0;
+    float* delayed_norm = nullptr;
+    uint8_t* delayed_skip = nullptr;
+
+    bool stores(int s) const { return s >= 0 && s < APM_N_STATES && (desc.state_mask >> s) & 1u; }
+};
+
+namespace apm {
+// Validates a page list and enqueues the two kernels of one step.  g16_override != nullptr
+// replaces the pool's G16 region as the gradient source.
+int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
+                 const apm_hyper* hyper, const uint16_t* g16_override, float* grad_norm,
+                 uint8_t* skip_mask, hipStream_t stream);
+int ensure_scratch(apm_pool* pool);
+}  // namespace apm

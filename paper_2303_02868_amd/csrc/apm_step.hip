@@ -1,0 +1,199 @@
+// Host side of the update: scalar preparation, page-list handling, the synchronous step and the
+// one-step-stale (delayed) step.
+#include <cmath>
+
+#include "apm_internal.h"
+
+namespace apm {
+
+int prepare_hyper(const apm_hyper* h, int64_t step, AdamwLaunch* a) {
+    if (!h) return fail(APM_EINVAL, "NULL hyper");
+    if (step < 1) return fail(APM_EINVAL, "step must be >= 1 (got %lld): bias correction divides by 1 - beta^step", (long long)step);
+    if (!(h->beta1 >= 0.0 && h->beta1 < 1.0) || !(h->beta2 >= 0.0 && h->beta2 < 1.0)) return fail(APM_EINVAL, "betas must lie in [0, 1)");
+    if (!(h->eps >= 0.0) || !std::isfinite(h->lr) || !std::isfinite(h->weight_decay) || std::isnan(h->max_grad_norm)) return fail(APM_EINVAL, "bad hyper-parameter");
+    if (h->skip_mode != APM_SKIP_NONE && h->skip_mode != APM_SKIP_UNTOUCHED) return fail(APM_EINVAL, "unknown skip_mode %d", h->skip_mode);
+    // Every scalar is formed in double and rounded to fp32 exactly once: 1 - 0.999f evaluated in
+    // fp32 would already be off by 1e-5 relative.
+    const double bc1 = 1.0 - std::pow(h->beta1, (double)step);
+    const double bc2 = 1.0 - std::pow(h->beta2, (double)step);
+    a->b1 = (float)h->beta1;
+    a->omb1 = (float)(1.0 - h->beta1);
+    a->b2 = (float)h->beta2;
+    a->omb2 = (float)(1.0 - h->beta2);
+    a->inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    a->eps = (float)h->eps;
+    a->step_size = (float)(h->lr / bc1);
+    a->lr_wd = (float)(h->lr * h->weight_decay);
+    a->max_norm = h->max_grad_norm > 0.0 ? h->max_grad_norm : 0.0;
+    a->skip_mode = h->skip_mode;
+    return APM_OK;
+}
+
+int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
+                 const apm_hyper* hyper, const uint16_t* g16_override, float* grad_norm,
+                 uint8_t* skip_mask, hipStream_t stream) {
+    if (!pool) return fail(APM_EINVAL, "NULL pool");
+    if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the update runs on GPU pools only");
+    for (int st = 0; st < APM_N_STATES; ++st) {
+        if (st == APM_G16 && g16_override) continue;
+        if (!pool->stores(st)) return fail(APM_ESTATE, "pool does not store state class %d", st);
+    }
+    if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
+    AdamwLaunch L{};
+    int rc = prepare_hyper(hyper, step, &L);
+    if (rc != APM_OK) return rc;
+    if (n_pages == 0) return APM_OK;
+    APM_HIP(hipSetDevice(pool->desc.hip_device));
+
+    // A list that is an ascending run needs no indirection; anything else is staged to the device.
+    int64_t first = 0;
+    bool run = true;
+    if (pages) {
+        first = pages[0];
+        for (int64_t k = 0; k < n_pages; ++k) {
+            if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] = %lld out of range [0, %lld)", (long long)k, (long long)pages[k], (long long)pool->desc.n_pages);
+            if (pages[k] != first + k) run = false;
+        }
+    }
+    const int64_t* d_list = nullptr;
+    if (!run) {
+        int slot;
+        rc = pool->ring.acquire((size_t)n_pages * sizeof(int64_t), &slot);
+        if (rc != APM_OK) return rc;
+        int64_t* h = static_cast<int64_t*>(pool->ring.h[slot]);
+        for (int64_t k = 0; k < n_pages; ++k) h[k] = pages[k];
+        rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(int64_t), stream);
+        if (rc != APM_OK) return rc;
+        d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
+    }
+
+    L.p32 = static_cast<float*>(pool->base[APM_P32]);
+    L.m32 = static_cast<float*>(pool->base[APM_M32]);
+    L.v32 = static_cast<float*>(pool->base[APM_V32]);
+    L.g16 = g16_override ? g16_override : static_cast<const uint16_t*>(pool->base[APM_G16]);
+    L.p16 = static_cast<uint16_t*>(pool->base[APM_P16]);
+    L.used = pool->d_used;
+    L.state_pages = L.grad_pages = d_list;
+    L.state_first = L.grad_first = first;
+    L.n_listed = n_pages;
+    L.E = pool->desc.page_elems;
+    L.S = pool->S;
+    L.grad_norm = grad_norm;
+    L.skip_mask = skip_mask;
+    const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
+    if (need_reduce) {
+        rc = ensure_scratch(pool);
+        if (rc != APM_OK) return rc;
+        L.partials = pool->d_partials;
+        L.nzflags = pool->d_nzflags;
+        APM_HIP(launch_grad_reduce(L, stream));
+    }
+    APM_HIP(launch_adamw(L, stream));
+    return APM_OK;
+}
+
+namespace {
+
+int ensure_delayed(apm_pool* pool) {
+    if (pool->upd_stream) return APM_OK;
+    const size_t bytes = (size_t)pool->desc.n_pages * (size_t)pool->desc.page_elems * 2u;
+    for (int k = 0; k < 2; ++k) {
+        hipError_t e = hipMalloc((void**)&pool->gbuf[k], bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            for (int j = 0; j < 2; ++j) {
+                if (pool->gbuf[j]) (void)hipFree(pool->gbuf[j]);
+                pool->gbuf[j] = nullptr;
+            }
+            return fail(APM_ENOMEM, "allocating the %zu-byte buffered-gradient halves failed: %s", bytes, hipGetErrorString(e));
+        }
+    }
+    for (int k = 0; k < 2; ++k) {
+        APM_HIP(hipEventCreateWithFlags(&pool->ev_staged[k], hipEventDisableTiming));
+        APM_HIP(hipEventCreateWithFlags(&pool->ev_applied[k], hipEventDisableTiming));
+    }
+    APM_HIP(hipEventCreateWithFlags(&pool->ev_flush, hipEventDisableTiming));
+    APM_HIP(hipStreamCreateWithFlags(&pool->upd_stream, hipStreamNonBlocking));
+    return APM_OK;
+}
+
+// Applies the buffered gradient (half `cur`) on the update stream.
+int apply_buffered(apm_pool* pool, const int64_t* pages, int64_t n_pages, const apm_hyper* hyper) {
+    const int k = pool->cur;
+    APM_HIP(hipStreamWaitEvent(pool->upd_stream, pool->ev_staged[k], 0));
+    int rc = enqueue_step(pool, pages, n_pages, pool->applied + 1, hyper, pool->gbuf[k],
+                          pool->delayed_norm, pool->delayed_skip, pool->upd_stream);
+    if (rc != APM_OK) return rc;
+    pool->applied += 1;
+    APM_HIP(hipEventRecord(pool->ev_applied[k], pool->upd_stream));
+    pool->applied_valid[k] = true;
+    return APM_OK;
+}
+
+}  // namespace
+}  // namespace apm
+
+using namespace apm;
+
+extern "C" int apm_page_adamw_step(apm_pool* pool, const int64_t* pages, int64_t n_pages,
+                                   int64_t step, const apm_hyper* hyper, float* grad_norm,
+                                   uint8_t* skip_mask, void* stream) {
+    return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
+                        static_cast<hipStream_t>(stream));
+}
+
+extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages,
+                                const void* new_g16, const apm_hyper* hyper, void* stream) {
+    if (!pool) return fail(APM_EINVAL, "NULL pool");
+    if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the update runs on GPU pools only");
+    if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
+    AdamwLaunch probe{};
+    int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
+    if (rc != APM_OK) return rc;
+    if (pages)
+        for (int64_t k = 0; k < n_pages; ++k)
+            if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
+    APM_HIP(hipSetDevice(pool->desc.hip_device));
+    rc = ensure_delayed(pool);
+    if (rc != APM_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (pool->buffered) {
+        rc = apply_buffered(pool, pages, n_pages, hyper);
+        if (rc != APM_OK) return rc;
+        pool->buffered = false;
+    }
+    if (!new_g16) {  // flush: the caller's stream joins the update stream
+        APM_HIP(hipEventRecord(pool->ev_flush, pool->upd_stream));
+        APM_HIP(hipStreamWaitEvent(s, pool->ev_flush, 0));
+        return APM_OK;
+    }
+    // Stage the new gradient into the other half; that half was last read by the update enqueued
+    // two calls ago, which must have finished before it is overwritten.
+    const int nxt = pool->cur ^ 1;
+    if (pool->applied_valid[nxt]) APM_HIP(hipStreamWaitEvent(s, pool->ev_applied[nxt], 0));
+    const size_t pb = (size_t)pool->desc.page_elems * 2u;
+    const char* src = static_cast<const char*>(new_g16);
+    char* dst = reinterpret_cast<char*>(pool->gbuf[nxt]);
+    int64_t k = 0;
+    while (k < n_pages) {  // one copy per run of consecutive pages
+        const int64_t p0 = pages ? pages[k] : k;
+        int64_t len = 1;
+        while (k + len < n_pages && (pages ? pages[k + len] : k + len) == p0 + len) ++len;
+        APM_HIP(hipMemcpyAsync(dst + (size_t)p0 * pb, src + (size_t)p0 * pb, pb * (size_t)len, hipMemcpyDeviceToDevice, s));
+        k += len;
+    }
+    APM_HIP(hipEventRecord(pool->ev_staged[nxt], s));
+    pool->cur = nxt;
+    pool->buffered = true;
+    return APM_OK;
+}
+
+extern "C" int64_t apm_delayed_applied(const apm_pool* pool) { return pool ? pool->applied : 0; }
+
+extern "C" int apm_delayed_set_outputs(apm_pool* pool, float* grad_norm, uint8_t* skip_mask) {
+    if (!pool) return fail(APM_EINVAL, "NULL pool");
+    pool->delayed_norm = grad_norm;
+    pool->delayed_skip = skip_mask;
+    return APM_OK;
+}

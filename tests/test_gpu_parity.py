@@ -1,0 +1,234 @@
+"""Parity of the HIP path (through the C ABI) against the oracle on the five configurations and on
+edge cases.  Floating-point gate: |gpu - oracle| <= max(1e-6 |oracle|, 1e-9) for p32, m32, v32
+after the last step; packing, masks, p16-vs-own-master and copies are bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2303_02868_amd as apm
+    from gpu_helpers import (DEV, HOST_THREADS, DevicePool, Model, bf16_bits, check_p16,
+                             check_state_close, run_resident, to_hyper, unpack_all)
+
+
+def specs_of(name):
+    f, E = synth.WORKLOADS[name]
+    return f(), E
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+def test_synth_device_backend_matches_host():
+    a = synth.normal_f32(0, 1, 123456789, 1 << 16, 0.02)
+    b = synth.normal_f32(0, 1, 123456789, 1 << 16, 0.02, device=DEV).cpu().numpy()
+    assert a.tobytes() == b.tobytes()
+    g = synth.normal_bf16(0, 1001, 5, 1 << 16, 1e-3)
+    assert g.tobytes() == bf16_bits(synth.normal_bf16(0, 1001, 5, 1 << 16, 1e-3, device=DEV)).tobytes()
+
+
+def test_cfg1_eight_pages_one_step_and_closed_form():
+    specs, E = specs_of("cfg1_8pages")
+    model = Model(specs, E, seed=0)
+    h = oracle.Hyper()
+    dp, st, worst = run_resident(model, 1, h)
+    log(f"cfg1 worst rel err {worst}")
+    # first-step closed form, element by element: p' = p - lr g/(|g|+eps) - lr wd p
+    p0 = model.p_flat.cpu().numpy().astype(np.float64)
+    g = oracle.bf16_bits_to_f64(bf16_bits(model.grad_flat(1)))
+    want = p0 - h.lr * g / (np.abs(g) + h.eps) - h.lr * h.weight_decay * p0
+    got = dp.reg[apm.APM_P32].cpu().numpy().reshape(-1).astype(np.float64)
+    err = np.abs(got - want)
+    assert np.all(err <= np.maximum(1e-6 * np.abs(want), 1e-9))
+    dp.destroy()
+
+
+def test_cfg2_gpt2_small_ten_steps_full_oracle_and_unpack():
+    specs, E = specs_of("gpt2_small_124m")
+    model = Model(specs, E, seed=0)
+    dp, st, worst = run_resident(model, 10, oracle.Hyper())
+    log(f"cfg2 pages {model.plan.n_pages} frag {model.plan.fragmentation:.4f} worst rel err {worst}")
+    assert worst["v"] < 2e-6
+    # unpack is the inverse of pack: tensor-space result == the pages gathered by the oracle plan
+    for state in (apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16):
+        flat = unpack_all(model, dp, state)
+        if state == apm.APM_P16:
+            pages = bf16_bits(dp.reg[state])
+            host = bf16_bits(flat)
+        else:
+            pages = dp.reg[state].cpu().numpy().view(np.uint32)
+            host = flat.cpu().numpy().view(np.uint32)
+        want = oracle.unpack(model.plan, pages, model.numels)
+        for i, w in enumerate(want):
+            a = int(model.off[i])
+            assert np.array_equal(host[a:a + w.size], w), f"unpack state {state} tensor {i}"
+    dp.destroy()
+
+
+def sampled_pages(plan, every):
+    """Every `every`-th page, the first and last, and every page that is not completely full."""
+    s = set(range(0, plan.n_pages, every)) | {0, plan.n_pages - 1}
+    s |= {k for k, p in enumerate(plan.pages) if p.used < plan.page_elems}
+    return sorted(s)
+
+
+def test_cfg3_gpt_1p3b_clipped_ten_steps_sampled_oracle():
+    specs, E = specs_of("gpt_1p3b")
+    model = Model(specs, E, seed=0)
+    sample = sampled_pages(model.plan, 16)
+    log(f"cfg3 pages {model.plan.n_pages}, oracle on {len(sample)} pages")
+    h = oracle.Hyper(max_grad_norm=1.0)
+    dp, st, worst = run_resident(model, 10, h, sample=sample)
+    log(f"cfg3 worst rel err {worst}")
+    assert worst["v"] < 2e-6
+    dp.destroy()
+
+
+def test_cfg5_moe_skip_sync_and_delayed_sampled_oracle():
+    # 20 steps; per step 8 of 64 experts per layer receive a gradient, every other expert page is
+    # skipped.  A synchronous pool (checked against the oracle on sampled pages) and a delayed pool
+    # run side by side on the same gradients; after the flush they must agree bit for bit.
+    f, E = synth.WORKLOADS["moe_8x64"]
+    specs = f()
+    steps = 20
+    act = lambda t: synth.moe_active_tensors(specs, t, 0, 64, 8)
+    h = oracle.Hyper(skip_mode=1)
+    hy = to_hyper(h)
+    model = Model(specs, E, seed=0, active_fn=act)
+    plan, n_t = model.plan, len(specs)
+    n_pages = plan.n_pages
+    sample = sampled_pages(plan, 64)
+    used = [plan.pages[p].used for p in sample]
+    log(f"cfg5 pages {n_pages}, oracle on {len(sample)} pages")
+    a = DevicePool(n_pages, E)
+    b = DevicePool(n_pages, E, states=(apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16))
+    for dp in (a, b):
+        apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    st = oracle.PagedAdamWState(model.host_pages(model.p_flat, sample).view(np.float32), used)
+    skip_d = torch.zeros(n_pages, dtype=torch.uint8, device=DEV)
+    norm_d = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    n_skipped = 0
+    for t in range(1, steps + 1):
+        g_flat = model.grad_flat(t)
+        apm.apm_pack_tensors(a.pool, apm.APM_G16, model.tensors(g_flat), n_t)
+        apm.apm_page_adamw_step(a.pool, None, n_pages, t, hy, norm_d, skip_d)
+        apm.apm_step_delayed(b.pool, None, n_pages, a.reg[apm.APM_G16], hy)
+        assert apm.apm_delayed_applied(b.pool) == t - 1
+        norms, skips = st.step(model.host_pages(g_flat, sample), t, h, threads=HOST_THREADS)
+        torch.cuda.synchronize()
+        sk = skip_d.cpu().numpy()
+        assert np.array_equal(sk[sample], skips)
+        nrm = norm_d.cpu().numpy()[sample]
+        assert np.all(np.abs(nrm - norms) <= 1e-6 * np.abs(norms))
+        n_skipped += int(sk.sum())
+        del g_flat
+    # 56 of 64 experts x 2 matrices x 4 pages x 8 layers are skipped every step
+    assert n_skipped == steps * 8 * 56 * 2 * 4
+    apm.apm_step_delayed(b.pool, None, n_pages, None, hy)          # flush
+    torch.cuda.synchronize()
+    assert apm.apm_delayed_applied(b.pool) == steps
+    worst = {k: check_state_close(k, a.rows_f32(s_, sample), ref, used)
+             for k, s_, ref in (("p", apm.APM_P32, st.p), ("m", apm.APM_M32, st.m), ("v", apm.APM_V32, st.v))}
+    log(f"cfg5 worst rel err {worst}")
+    check_p16(a.rows_b16(apm.APM_P16, sample), a.rows_f32(apm.APM_P32, sample), st.p16, used)
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16):
+        assert torch.equal(a.reg[s_].view(torch.int16), b.reg[s_].view(torch.int16)), f"state {s_}: delayed != sync"
+    a.destroy()
+    b.destroy()
+
+
+def test_delayed_small_with_page_list_and_outputs():
+    E = 16384
+    numels = [3 * E + 5, 100, 2 * E, 9000]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=9, sigma_g=5e-3)
+    n = model.plan.n_pages
+    listed = [p for p in range(n) if p != 2]
+    dp, st, worst = run_resident(model, 5, oracle.Hyper(max_grad_norm=0.5, skip_mode=1),
+                                 page_list=listed, stepper="delayed")
+    dp.destroy()
+
+
+def test_edge_ragged_lists_page_lists_clip_and_skip():
+    # small pages so that tensors span several tiles with ragged tails; odd numels so that tensor
+    # pointers are not 16-byte aligned; zero-size tensors; exact-page tensors
+    E = 40960
+    numels = [E * 2 + 4097, 1, 7, E - 1, E, E + 1, 0, 3 * E + 12345, 255, 8193, 2 * E]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    zero_grad = {3, 8}                      # tensors without gradient -> their sole pages are skipped
+    act = lambda t: np.array([i not in zero_grad for i in range(len(numels))])
+    model = Model(specs, E, seed=3, sigma_g=2e-3, active_fn=act, pad_elems=1)
+    h = oracle.Hyper(max_grad_norm=0.3, skip_mode=1)
+    dp, st, worst = run_resident(model, 4, h)
+    log(f"edge worst {worst}")
+    dp.destroy()
+    # a permuted, partial page list: unlisted pages must stay untouched
+    model2 = Model(specs, E, seed=4, pad_elems=3)
+    n = model2.plan.n_pages
+    listed = [p for p in reversed(range(n)) if p % 3 != 1]
+    dp, st, worst = run_resident(model2, 3, oracle.Hyper(max_grad_norm=0.05), page_list=listed)
+    unl = [p for p in range(n) if p % 3 == 1]
+    assert not dp.rows_f32(apm.APM_M32, unl).any() and not dp.rows_b16(apm.APM_P16, unl).any()
+    dp.destroy()
+
+
+def test_no_outputs_no_clip_path_matches_path_with_reduce():
+    # without clip/skip/outputs the reduce pass is not launched; results must be identical
+    E = 16384
+    specs = [synth.TensorSpec(0, "a", 5 * E + 100), synth.TensorSpec(1, "b", 77)]
+    model = Model(specs, E, seed=5)
+    a, _, _ = run_resident(model, 2, oracle.Hyper(), want_outputs=False)
+    b, _, _ = run_resident(model, 2, oracle.Hyper(), want_outputs=True)
+    for s in (apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16):
+        assert torch.equal(a.reg[s].view(torch.int16), b.reg[s].view(torch.int16))
+    a.destroy()
+    b.destroy()
+
+
+def test_error_paths_and_page_table():
+    E = 1024
+    dp = DevicePool(6, E)
+    hy = apm.make_hyper()
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_adamw_step(dp.pool, None, 2, 0, hy)
+    assert e.value.code == apm.APM_EINVAL and "step" in str(e.value)
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_adamw_step(dp.pool, [0, 6], 2, 1, hy)
+    assert e.value.code == apm.APM_ERANGE
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_adamw_step(dp.pool, None, 2, 1, apm.make_hyper(beta1=1.0))
+    assert e.value.code == apm.APM_EINVAL
+    apm.apm_page_adamw_step(dp.pool, None, 0, 1, hy)          # empty list: a no-op
+    # layout too large for the pool
+    big = apm.make_tensors([7 * E], apm.APM_F32)
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_pool_set_layout(dp.pool, big, 1)
+    assert e.value.code == apm.APM_ENOMEM
+    numels = [2 * E + 10, 5, E + 1]
+    res = apm.apm_pool_set_layout(dp.pool, apm.make_tensors(numels, apm.APM_F32, ids=[70, 71, 72]), 3)
+    plan = oracle.plan_pack(numels, E)
+    assert res.n_pages == plan.n_pages == apm.apm_pool_pages_in_use(dp.pool)
+    for k, pe in enumerate(plan.pages):
+        info = apm.apm_pool_page_info(dp.pool, k)
+        assert info.total_elems == E and info.used_elems == pe.used
+        assert info.available_elems == E - pe.used and info.device == apm.APM_DEV_GPU
+        ids = [70 + t if t >= 0 else -1 for t in pe.tensor_id]
+        assert list(info.tensor_id) == ids and list(info.tensor_elems) == pe.tensor_elems
+        assert info.n_tensors == pe.n_tenants() <= 2
+    # wrong dtype for the class, mismatching list
+    x = torch.zeros(sum(numels), dtype=torch.float32, device=DEV)
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_pack_tensors(dp.pool, apm.APM_G16, apm.make_tensors(numels, apm.APM_F32, [x] * 3), 3)
+    assert e.value.code == apm.APM_EINVAL
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_pack_tensors(dp.pool, apm.APM_P32, apm.make_tensors([5, 5], apm.APM_F32, [x] * 2), 2)
+    assert e.value.code == apm.APM_ESTATE
+    assert apm.apm_pool_state_ptr(dp.pool, apm.APM_M32, 2) == dp.reg[apm.APM_M32].data_ptr() + 2 * E * 4
+    assert apm.apm_pool_state_ptr(dp.pool, apm.APM_M32, 6) is None
+    dp.destroy()

@@ -1,0 +1,86 @@
+"""Page copies and the streamed (host-resident fp32 state) update: copies are bit-exact, and the
+streamed step is bit-identical to the resident step."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2303_02868_amd as apm
+    from gpu_helpers import DEV, DevicePool, Model, bf16_bits, check_state_close, check_p16, to_hyper
+
+
+def host_view(pool, state, n_pages, E):
+    """numpy view of a library-allocated pinned host region."""
+    ptr = apm.apm_pool_state_ptr(pool, state, 0)
+    buf = (ctypes.c_float * (n_pages * E)).from_address(ptr)
+    return np.frombuffer(buf, dtype=np.float32).reshape(n_pages, E)
+
+
+def test_page_copy_roundtrip_bit_exact():
+    E, n = 8192, 10
+    dp = DevicePool(n, E)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n, state_mask=apm.FP32_STATES)
+    x = synth.normal_f32(1, 5, 0, n * E, 1.0, device=DEV).view(n, E)
+    dp.reg[apm.APM_M32].copy_(x)
+    apm.apm_page_copy_async(host, 2, dp.pool, 3, 5, apm.APM_M32)           # D2H pages 3..7 -> 2..6
+    torch.cuda.synchronize()
+    hv = host_view(host, apm.APM_M32, n, E)
+    assert np.array_equal(hv[2:7].view(np.uint32), x[3:8].cpu().numpy().view(np.uint32))
+    assert not hv[:2].any() and not hv[7:].any()
+    apm.apm_page_copy_async(dp.pool, 0, host, 2, 5, apm.APM_M32)  # H2D back
+    torch.cuda.synchronize()
+    assert torch.equal(dp.reg[apm.APM_M32][0:5], x[3:8])
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_copy_async(dp.pool, 8, host, 0, 3, apm.APM_M32)
+    assert e.value.code == apm.APM_ERANGE
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_copy_async(host, 0, dp.pool, 0, 1, apm.APM_G16)
+    assert e.value.code == apm.APM_ERANGE
+    host.destroy()
+    dp.destroy()
+
+
+@pytest.mark.parametrize("batch,slots,clip", [(4, 2, 0.0), (7, 3, 1.0), (64, 2, 1.0)])
+def test_streamed_equals_resident_bit_exact(batch, slots, clip):
+    # a GPT-2-small-sized model: resident run vs. fp32 state in pinned host pages streamed through
+    # `slots` staging slots of `batch` pages
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=1)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    h = oracle.Hyper(max_grad_norm=clip)
+    hy = to_hyper(h)
+    steps = 3
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    # initial master parameters reach the host pool by page copies from the resident pool
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    st = apm.apm_streamer_create(host, dev.pool, batch, slots)
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, steps + 1):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, None)
+        apm.apm_streamer_step(st, t, hy, norm_s, None)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s)
+    for s in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        hv = host_view(host, s, n_pages, E)
+        assert np.array_equal(hv.view(np.uint32), res.reg[s].cpu().numpy().view(np.uint32)), f"state {s}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    st.destroy()
+    host.destroy()
+    dev.destroy()
+    res.destroy()
