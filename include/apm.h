@@ -174,6 +174,19 @@ void* apm_pool_state_ptr(const apm_pool* pool, int state, int64_t page);
 int apm_pool_set_layout(apm_pool* pool, const apm_tensor* tensors, int64_t n, apm_segment* segs,
                         int64_t* n_segs, int64_t* n_pages, double* fragmentation, void* stream);
 
+/* ---- kernel timing (measurement aid) -------------------------------------------------------- */
+
+enum apm_kernel_class { APM_K_REDUCE = 0, APM_K_UPDATE = 1, APM_K_SEGCOPY = 2, APM_N_KERNEL_CLASSES = 3 };
+
+/* While enabled, every kernel the pool's calls launch (apm_page_adamw_step, apm_pack_tensors,
+ * apm_unpack) is bracketed by a pair of HIP events on the stream it is launched on. */
+int apm_pool_set_timing(apm_pool* pool, int enable);
+
+/* Waits for the recorded events, adds the elapsed milliseconds per kernel class into
+ * ms[APM_N_KERNEL_CLASSES] and the launch counts into launches[APM_N_KERNEL_CLASSES] (host
+ * pointers, overwritten), and forgets the events. */
+int apm_pool_read_timing(apm_pool* pool, double* ms, int64_t* launches);
+
 /* ---- pack / unpack (gather / scatter kernels; the Tensor listing's merge is apm_unpack) ---- */
 
 /*

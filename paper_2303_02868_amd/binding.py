@@ -18,6 +18,7 @@ APM_F32, APM_BF16 = 0, 1
 APM_P32, APM_M32, APM_V32, APM_G16, APM_P16, APM_N_STATES = 0, 1, 2, 3, 4, 5
 APM_SKIP_NONE, APM_SKIP_UNTOUCHED = 0, 1
 APM_POOL_NO_ZERO = 1
+APM_K_REDUCE, APM_K_UPDATE, APM_K_SEGCOPY, APM_N_KERNEL_CLASSES = 0, 1, 2, 3
 ALL_STATES = 0b11111
 FP32_STATES = 0b00111
 B16_STATES = 0b11000
@@ -27,7 +28,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_copy_async",
     "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_step_delayed",
-    "apm_delayed_applied", "apm_delayed_set_outputs",
+    "apm_delayed_applied", "apm_delayed_set_outputs", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
 
@@ -105,6 +106,8 @@ def lib() -> C.CDLL:
     L.apm_delayed_applied.argtypes = [vp]
     L.apm_delayed_applied.restype = i64
     L.apm_delayed_set_outputs.argtypes = [vp, vp, vp]
+    L.apm_pool_set_timing.argtypes = [vp, i32]
+    L.apm_pool_read_timing.argtypes = [vp, P(C.c_double), P(i64)]
     for name in EXPORTS:
         getattr(L, name)              # every declared entry point must be exported
     _lib = L
@@ -316,3 +319,15 @@ def apm_delayed_applied(pool: Pool) -> int:
 
 def apm_delayed_set_outputs(pool: Pool, grad_norm=None, skip_mask=None) -> None:
     _check(lib().apm_delayed_set_outputs(pool.handle, _ptr(grad_norm), _ptr(skip_mask)))
+
+
+def apm_pool_set_timing(pool: Pool, enable: bool) -> None:
+    _check(lib().apm_pool_set_timing(pool.handle, int(enable)))
+
+
+def apm_pool_read_timing(pool: Pool):
+    """({class: total ms}, {class: launches}) since the last read."""
+    ms = (C.c_double * APM_N_KERNEL_CLASSES)()
+    n = (C.c_int64 * APM_N_KERNEL_CLASSES)()
+    _check(lib().apm_pool_read_timing(pool.handle, ms, n))
+    return list(ms), list(n)

@@ -129,6 +129,11 @@ struct apm_pool {
     float* delayed_norm = nullptr;
     uint8_t* delayed_skip = nullptr;
 
+    // kernel timing (measurement aid)
+    bool timing = false;
+    struct TimedLaunch { int cls; hipEvent_t begin, end; };
+    std::vector<TimedLaunch> timed;
+
     bool stores(int s) const { return s >= 0 && s < APM_N_STATES && (desc.state_mask >> s) & 1u; }
 };
 
@@ -139,4 +144,19 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
                  const apm_hyper* hyper, const uint16_t* g16_override, float* grad_norm,
                  uint8_t* skip_mask, hipStream_t stream);
 int ensure_scratch(apm_pool* pool);
+
+// Brackets one kernel launch with events when the pool's timing is on.
+struct ScopedTiming {
+    apm_pool* pool;
+    hipStream_t stream;
+    hipEvent_t end = nullptr;
+    ScopedTiming(apm_pool* p, int cls, hipStream_t s) : pool(p), stream(s) {
+        if (!p->timing) return;
+        hipEvent_t b = nullptr;
+        if (hipEventCreate(&b) != hipSuccess || hipEventCreate(&end) != hipSuccess) { end = nullptr; return; }
+        (void)hipEventRecord(b, s);
+        p->timed.push_back({cls, b, end});
+    }
+    ~ScopedTiming() { if (end) (void)hipEventRecord(end, stream); }
+};
 }  // namespace apm

@@ -88,6 +88,10 @@ void free_pool(apm_pool* pool) {
     if (pool->d_partials) (void)hipFree(pool->d_partials);
     if (pool->d_nzflags) (void)hipFree(pool->d_nzflags);
     pool->ring.destroy();
+    for (auto& t : pool->timed) {
+        (void)hipEventDestroy(t.begin);
+        (void)hipEventDestroy(t.end);
+    }
     for (int k = 0; k < 2; ++k) {
         if (pool->gbuf[k]) (void)hipFree(pool->gbuf[k]);
         if (pool->ev_staged[k]) (void)hipEventDestroy(pool->ev_staged[k]);
@@ -168,7 +172,10 @@ int move_segments(apm_pool* pool, int state, const apm_tensor* tensors, int64_t 
     }
     rc = pool->ring.commit(slot, segs.size() * sizeof(SegDesc), s);
     if (rc != APM_OK) return rc;
-    APM_HIP(launch_seg_copy(static_cast<const SegDesc*>(pool->ring.d[slot]), (int64_t)segs.size(), max_bytes, s));
+    {
+        ScopedTiming t(pool, APM_K_SEGCOPY, s);
+        APM_HIP(launch_seg_copy(static_cast<const SegDesc*>(pool->ring.d[slot]), (int64_t)segs.size(), max_bytes, s));
+    }
     return APM_OK;
 }
 
@@ -336,4 +343,33 @@ extern "C" int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* sr
     APM_HIP(hipSetDevice(dh ? src->desc.hip_device : dst->desc.hip_device));
     APM_HIP(hipMemcpyAsync(d, s, pb * (size_t)n_pages, kind, static_cast<hipStream_t>(stream)));
     return APM_OK;
+}
+
+extern "C" int apm_pool_set_timing(apm_pool* pool, int enable) {
+    if (!pool) return fail(APM_EINVAL, "NULL pool");
+    pool->timing = enable != 0;
+    return APM_OK;
+}
+
+extern "C" int apm_pool_read_timing(apm_pool* pool, double* ms, int64_t* launches) {
+    if (!pool || !ms || !launches) return fail(APM_EINVAL, "NULL argument");
+    for (int k = 0; k < APM_N_KERNEL_CLASSES; ++k) {
+        ms[k] = 0.0;
+        launches[k] = 0;
+    }
+    int rc = APM_OK;
+    for (auto& t : pool->timed) {
+        float dt = 0.0f;
+        hipError_t e = hipEventSynchronize(t.end);
+        if (e == hipSuccess) e = hipEventElapsedTime(&dt, t.begin, t.end);
+        if (e != hipSuccess) rc = fail(APM_EDEVICE, "reading a timing event failed: %s", hipGetErrorString(e));
+        else {
+            ms[t.cls] += (double)dt;
+            launches[t.cls] += 1;
+        }
+        (void)hipEventDestroy(t.begin);
+        (void)hipEventDestroy(t.end);
+    }
+    pool->timed.clear();
+    return rc;
 }
