@@ -10,7 +10,8 @@ import os
 from typing import Optional, Sequence
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libapm.so")
+# APM_LIBRARY selects another build of the same library (e.g. one compiled with different tunables).
+LIB_PATH = os.environ.get("APM_LIBRARY") or os.path.join(_PKG, "libapm.so")
 
 APM_OK, APM_EINVAL, APM_ENOMEM, APM_ERANGE, APM_EDEVICE, APM_ESTATE = 0, -1, -2, -3, -4, -5
 APM_DEV_GPU, APM_DEV_HOST = 0, 1

@@ -51,6 +51,24 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// ---- tunables (defaults measured on MI355X; see the sweep notes next to each) ----------------
+#ifndef APM_REDUCE_U
+#define APM_REDUCE_U 4          // 128-bit loads in flight per lane in the reduce kernel
+#endif
+#ifndef APM_UPDATE_THREADS
+#define APM_UPDATE_THREADS 64   // one wavefront per page slice
+#endif
+#ifndef APM_UPDATE_U
+#define APM_UPDATE_U 4          // 128-bit vectors per lane and fp32 class
+#endif
+#ifndef APM_UPDATE_LDS
+// Dynamic LDS requested per workgroup for no purpose other than capping residency at
+// 160 KiB / 16 KiB = 10 wavefronts per CU: with four read and four write streams per wavefront,
+// more resident wavefronts lower the achieved HBM bandwidth (6.1 TB/s unlimited, 6.4 TB/s at 10,
+// 5.7 TB/s at 6 on the 28 B/element access pattern).
+#define APM_UPDATE_LDS 16384
+#endif
+
 struct ReduceArgs {
     const uint16_t* g16;
     const int32_t* used;
@@ -76,38 +94,45 @@ __global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a)
     const int end = min(start + kReduceTile, used);
     const uint16_t* g = a.g16 + page * a.E;
 
-    double acc = 0.0;
+    double acc0 = 0.0, acc1 = 0.0;
     uint32_t nz = 0;
-    constexpr int kIters = kReduceTile / (kThreads * 8);
-    u32x4 w[kIters];
+    constexpr int U = APM_REDUCE_U;
+    constexpr int kOuter = kReduceTile / (kThreads * 8 * U);
+    static_assert(kOuter * kThreads * 8 * U == kReduceTile, "reduce tile must be a multiple of the unrolled span");
+#pragma unroll 1
+    for (int o = 0; o < kOuter; ++o) {
+        const int e0 = start + o * (kThreads * 8 * U) + (int)threadIdx.x * 8;
+        if (e0 - (int)threadIdx.x * 8 >= end) break;   // uniform: the whole span is beyond the extent
+        u32x4 w[U];
 #pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-        const int e = start + (it * kThreads + (int)threadIdx.x) * 8;
-        w[it] = u32x4{0u, 0u, 0u, 0u};
-        if (e < end) w[it] = *reinterpret_cast<const u32x4*>(g + e);
-    }
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * (kThreads * 8);
+            w[u] = u32x4{0u, 0u, 0u, 0u};
+            if (e < end) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g + e));
+        }
 #pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-        const int e = start + (it * kThreads + (int)threadIdx.x) * 8;
-        if (e + 8 > end) {  // boundary vector: drop the elements at or beyond the used extent
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * (kThreads * 8);
+            if (e + 8 > end && e < end) {  // boundary vector: drop elements at or beyond the extent
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t x = w[u][j];
+                    if (e + 2 * j >= end) x = 0u;
+                    else if (e + 2 * j + 1 >= end) x &= 0x0000FFFFu;
+                    w[u][j] = x;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint32_t x = w[it][j];
-                if (e + 2 * j >= end) x = 0u;
-                else if (e + 2 * j + 1 >= end) x &= 0x0000FFFFu;
-                w[it][j] = x;
+                const uint32_t x = w[u][j];
+                nz |= x & 0x7FFF7FFFu;
+                const double lo = (double)bf16lo(x), hi = (double)bf16hi(x);
+                acc0 = fma(lo, lo, acc0);
+                acc1 = fma(hi, hi, acc1);
             }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t x = w[it][j];
-            nz |= x & 0x7FFF7FFFu;
-            const double lo = (double)bf16lo(x), hi = (double)bf16hi(x);
-            acc = fma(lo, lo, acc);
-            acc = fma(hi, hi, acc);
-        }
     }
-    acc = wave_sum_f64(acc);
+    double acc = wave_sum_f64(acc0 + acc1);
     nz = wave_or_u32(nz);
     __shared__ double s_acc[kThreads / kWave];
     __shared__ uint32_t s_nz[kThreads / kWave];
@@ -130,6 +155,51 @@ __global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a)
     }
 }
 
+struct FinalizeArgs {
+    const int32_t* used;
+    const int64_t* grad_pages;
+    int64_t grad_first;
+    int64_t n_listed;
+    const double* partials;
+    const uint32_t* nzflags;
+    int32_t S;
+    int32_t skip_mode;
+    double max_norm;
+    float* scale;      // [n_listed]: clip scale, or a negative value for a skipped page
+    float* grad_norm;  // nullable
+    uint8_t* skip_mask;  // nullable
+};
+
+// One wavefront per listed page: combines the page's slice partials in a fixed order and turns
+// them into the page's clip scale / skip decision and the optional outputs.
+__global__ __launch_bounds__(kThreads) void apm_grad_finalize_kernel(FinalizeArgs a) {
+    const int64_t i = (int64_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+    if (i >= a.n_listed) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t page = a.grad_pages ? a.grad_pages[i] : a.grad_first + i;
+    const int used = a.used[page];
+    const int n_slices = max(1, (used + kReduceTile - 1) / kReduceTile);
+    double s = 0.0;
+    uint32_t nz = 0;
+    for (int k = lane; k < n_slices; k += kWave) {
+        s += a.partials[i * a.S + k];
+        nz |= a.nzflags[i * a.S + k];
+    }
+    s = wave_sum_f64(s);
+    nz = wave_or_u32(nz);
+    if (lane != 0) return;
+    const bool skip = a.skip_mode == APM_SKIP_UNTOUCHED && nz == 0u;
+    const double norm = sqrt(s);
+    float scale = 1.0f;
+    if (a.max_norm > 0.0) {
+        const double sc = a.max_norm / (norm + 1e-6);
+        if (sc < 1.0) scale = (float)sc;
+    }
+    a.scale[i] = skip ? -1.0f : scale;
+    if (a.grad_norm) a.grad_norm[i] = skip ? 0.0f : (float)norm;
+    if (a.skip_mask) a.skip_mask[i] = skip ? 1 : 0;
+}
+
 struct UpdateArgs {
     float* p32;
     float* m32;
@@ -143,13 +213,7 @@ struct UpdateArgs {
     int64_t grad_first;
     int64_t list_offset;
     int64_t E;
-    const double* partials;
-    const uint32_t* nzflags;
-    int32_t S;
-    int32_t skip_mode;
-    float* grad_norm;
-    uint8_t* skip_mask;
-    double max_norm;
+    const float* scale;  // per listed page, nullable (then 1 and no skipping)
     float b1, omb1, b2, omb2, inv_sqrt_bc2, eps, step_size, lr_wd;
 };
 
@@ -165,45 +229,24 @@ __device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g
     p = p - delta;
 }
 
+constexpr int kUpdThreads = APM_UPDATE_THREADS;
+constexpr int kUpdU = APM_UPDATE_U;
+constexpr int kUpdTile = kUpdThreads * 4 * kUpdU;  // elements per workgroup
+
 // Fused update of one slice of one page: 12 B + 2 B read and 12 B + 2 B written per element.
-// U = 128-bit vectors per lane and state class kept in flight.
-template <int U>
-__global__ __launch_bounds__(kThreads) void apm_adamw_kernel(UpdateArgs a) {
+// Each lane keeps kUpdU 128-bit vectors per fp32 class in flight; every wavefront-wide access is
+// one contiguous 1 KiB (fp32) or 512 B (bf16) span.
+__global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     const int64_t i = a.list_offset + blockIdx.y;
     const int64_t gpage = a.grad_pages ? a.grad_pages[i] : a.grad_first + i;
-    const int used = a.used[gpage];
-    const int used8 = (used + 7) & ~7;
-    const int start = blockIdx.x * (kThreads * 4 * U);
-    const bool lead = blockIdx.x == 0;
-    if (start >= used8 && !lead) return;
-
-    float scale = 1.0f;
-    if (a.partials) {
-        // Combine the page's slice partials in a fixed order (same in every wavefront).
-        const int n_slices = max(1, (used + kReduceTile - 1) / kReduceTile);
-        const int lane = threadIdx.x & (kWave - 1);
-        double s = 0.0;
-        uint32_t nz = 0;
-        for (int k = lane; k < n_slices; k += kWave) {
-            s += a.partials[i * a.S + k];
-            nz |= a.nzflags[i * a.S + k];
-        }
-        s = wave_sum_f64(s);
-        nz = wave_or_u32(nz);
-        const bool skip = a.skip_mode == APM_SKIP_UNTOUCHED && nz == 0u;
-        const double norm = sqrt(s);
-        if (lead && threadIdx.x == 0) {
-            if (a.grad_norm) a.grad_norm[i] = skip ? 0.0f : (float)norm;
-            if (a.skip_mask) a.skip_mask[i] = skip ? 1 : 0;
-        }
-        if (skip) return;
-        if (a.max_norm > 0.0) {
-            const double sc = a.max_norm / (norm + 1e-6);
-            scale = sc < 1.0 ? (float)sc : 1.0f;
-        }
-    }
+    const int used8 = (a.used[gpage] + 7) & ~7;
+    const int start = blockIdx.x * kUpdTile;
     if (start >= used8) return;
-
+    float scale = 1.0f;
+    if (a.scale) {
+        scale = a.scale[i];
+        if (scale < 0.0f) return;  // skipped page: nothing is read or written
+    }
     const int64_t spage = a.state_pages ? a.state_pages[i] : a.state_first + i;
     f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
     f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
@@ -213,11 +256,11 @@ __global__ __launch_bounds__(kThreads) void apm_adamw_kernel(UpdateArgs a) {
 
     const int nvec = used8 >> 2;
     const int v0 = (start >> 2) + (int)threadIdx.x;
-    f32x4 p[U], m[U], v[U];
-    u32x2 g[U];
+    f32x4 p[kUpdU], m[kUpdU], v[kUpdU];
+    u32x2 g[kUpdU];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int vi = v0 + u * kThreads;
+    for (int u = 0; u < kUpdU; ++u) {
+        const int vi = v0 + u * kUpdThreads;
         if (vi < nvec) {
             g[u] = __builtin_nontemporal_load(G + vi);
             p[u] = __builtin_nontemporal_load(P + vi);
@@ -226,8 +269,8 @@ __global__ __launch_bounds__(kThreads) void apm_adamw_kernel(UpdateArgs a) {
         }
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int vi = v0 + u * kThreads;
+    for (int u = 0; u < kUpdU; ++u) {
+        const int vi = v0 + u * kUpdThreads;
         if (vi < nvec) {
             const float gf[4] = {bf16lo(g[u][0]), bf16hi(g[u][0]), bf16lo(g[u][1]), bf16hi(g[u][1])};
 #pragma unroll
@@ -249,7 +292,6 @@ __global__ __launch_bounds__(kThreads) void apm_adamw_kernel(UpdateArgs a) {
     }
 }
 
-constexpr int kUpdateU = 4;
 constexpr int kMaxGridY = 65535;
 
 }  // namespace
@@ -263,7 +305,12 @@ hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    return hipSuccess;
+    FinalizeArgs f{L.used, L.grad_pages, L.grad_first, L.n_listed, L.partials, L.nzflags, L.S,
+                   L.skip_mode, L.max_norm, L.scale, L.grad_norm, L.skip_mask};
+    const int per_wg = kThreads / kWave;
+    hipLaunchKernelGGL(apm_grad_finalize_kernel, dim3((unsigned)((L.n_listed + per_wg - 1) / per_wg)),
+                       dim3(kThreads), 0, s, f);
+    return hipGetLastError();
 }
 
 hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
@@ -271,16 +318,14 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
     a.p32 = L.p32; a.m32 = L.m32; a.v32 = L.v32; a.g16 = L.g16; a.p16 = L.p16;
     a.used = L.used; a.state_pages = L.state_pages; a.grad_pages = L.grad_pages;
     a.state_first = L.state_first; a.grad_first = L.grad_first; a.E = L.E;
-    a.partials = L.partials; a.nzflags = L.nzflags; a.S = L.S; a.skip_mode = L.skip_mode;
-    a.grad_norm = L.grad_norm; a.skip_mask = L.skip_mask; a.max_norm = L.max_norm;
+    a.scale = L.partials ? L.scale : nullptr;
     a.b1 = L.b1; a.omb1 = L.omb1; a.b2 = L.b2; a.omb2 = L.omb2;
     a.inv_sqrt_bc2 = L.inv_sqrt_bc2; a.eps = L.eps; a.step_size = L.step_size; a.lr_wd = L.lr_wd;
-    constexpr int64_t tile = kThreads * 4 * kUpdateU;
-    const unsigned nx = (unsigned)((L.E + tile - 1) / tile);
+    const unsigned nx = (unsigned)((L.E + kUpdTile - 1) / kUpdTile);
     for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
         const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
         a.list_offset = off;
-        hipLaunchKernelGGL(apm_adamw_kernel<kUpdateU>, dim3(nx, (unsigned)ny), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL(apm_adamw_kernel, dim3(nx, (unsigned)ny), dim3(kUpdThreads), APM_UPDATE_LDS, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

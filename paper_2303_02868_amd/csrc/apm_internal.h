@@ -77,6 +77,7 @@ struct AdamwLaunch {
     int64_t E;
     double* partials;             // [n_listed][S] per-slice sums of squares; nullptr = no reduce pass
     uint32_t* nzflags;            // [n_listed][S] per-slice OR of magnitude bits
+    float* scale;                 // [n_listed] per-page clip scale (< 0: skipped), written by the reduce pass
     int32_t S;                    // slices per page = ceil(E / kReduceTile)
     float* grad_norm;             // device, nullable
     uint8_t* skip_mask;           // device, nullable
@@ -113,6 +114,7 @@ struct apm_pool {
     int32_t* d_used = nullptr;      // device page table: used extent per page
     double* d_partials = nullptr;   // reduce scratch, n_pages * S
     uint32_t* d_nzflags = nullptr;
+    float* d_scale = nullptr;
     int32_t S = 0;
     apm::StageRing ring;
 

@@ -86,6 +86,7 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
         if (rc != APM_OK) return rc;
         L.partials = pool->d_partials;
         L.nzflags = pool->d_nzflags;
+        L.scale = pool->d_scale;
         ScopedTiming t(pool, APM_K_REDUCE, stream);
         APM_HIP(launch_grad_reduce(L, stream));
     }

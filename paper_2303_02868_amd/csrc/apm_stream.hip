@@ -121,6 +121,7 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
     if (need_reduce) {
         L.partials = dev->d_partials;
         L.nzflags = dev->d_nzflags;
+        L.scale = dev->d_scale;
     }
     const int states[3] = {APM_P32, APM_M32, APM_V32};
     const int64_t n_batches = (N + s->B - 1) / s->B;
