@@ -1,10 +1,15 @@
 #!/usr/bin/env python3
-"""Benchmark of the page-AdamW hot path on one MI355X.
+"""Benchmark of the page-AdamW hot path on one MI355X.  Prints ONE JSON line.
 
-A step is one pass of the whole path over one batch of synthetic gradients:
-  pack g16 (tensors -> pages)  ->  per-page grad reduce  ->  fused page AdamW  ->  unpack p16
-(the pool and the packing plan are set up once, as the method pre-allocates them).  Inputs are
-resident in HBM before the timed region.  Prints ONE JSON line.
+Resident leg (the headline `value`): a step is one pass of the whole path over one batch of
+synthetic gradients,
+  pack g16 (tensors -> pages) -> per-page grad reduce -> fused page AdamW -> unpack p16,
+with the pool and the packing plan set up once (the method pre-allocates them) and every input
+resident in HBM before the timed region.
+
+Streamed leg (reported under "streamed"): the fp32 master / momentum / variance pages live in
+pinned host memory and pass through HBM staging slots, copy-in, update and copy-out overlapped on
+three streams; the PCIe rate is compared with plain pinned copies measured in the same run.
 """
 from __future__ import annotations
 
@@ -22,6 +27,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 BYTES_UPDATE = 28               # per element: read p,m,v (12) + g (2); write p,m,v (12) + p16 (2)
 BYTES_REDUCE = 2                # per element: read g
 BYTES_SEGCOPY_B16 = 4           # per element: read 2 + write 2
+DEV = "cuda:0"
 
 
 def parse():
@@ -30,84 +36,86 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt_1p3b",
-                    choices=["cfg1_8pages", "gpt2_small_124m", "gpt_1p3b", "moe_8x64"])
-    ap.add_argument("--clip", type=float, default=None, help="per-page max grad norm (default: 1.0 for gpt_1p3b, else off)")
+                    choices=["cfg1_8pages", "gpt2_small_124m", "gpt_1p3b", "moe_8x64", "gpt_13b"])
+    ap.add_argument("--clip", type=float, default=None,
+                    help="per-page max grad norm (default: 1.0 for gpt_1p3b, else off)")
     ap.add_argument("--update-only", action="store_true", help="time reduce+update only (no pack/unpack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pages", type=int, default=192, help="pages of the workload the oracle is timed on")
     ap.add_argument("--cpu-steps", type=int, default=2)
+    ap.add_argument("--no-streamed", action="store_true", help="skip the host-streamed leg")
+    ap.add_argument("--streamed-only", action="store_true", help="run only the host-streamed leg (gpt_13b: always)")
+    ap.add_argument("--stream-steps", type=int, default=3)
+    ap.add_argument("--batch-pages", type=int, default=32)
+    ap.add_argument("--slots", type=int, default=3)
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
+class Workload:
+    def __init__(self, name, layers=None):
+        import synth
+        self.name = name
+        factory, self.E = synth.WORKLOADS[name]
+        self.layers = layers
+        # layers: a reduced depth of the 13 B shape, used when the box cannot pin the full state
+        self.specs = factory() if layers is None else synth.gpt_tensor_list(layers, 5120, 20480, 50257, 2048)
+        self.numels = [t.numel for t in self.specs]
+        self.n_t = len(self.specs)
+        self.off = synth.tensor_offsets(self.specs)
+        self.total = int(self.off[-1])
 
-    import paper_2303_02868_amd as apm
-    import synth
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    factory, E = synth.WORKLOADS[args.workload]
-    specs = factory()
-    numels = [t.numel for t in specs]
-    n_t = len(specs)
-    off = synth.tensor_offsets(specs)
-    total = int(off[-1])
-    clip = args.clip if args.clip is not None else (1.0 if args.workload == "gpt_1p3b" else 0.0)
-    skip = apm.APM_SKIP_UNTOUCHED if args.workload == "moe_8x64" else apm.APM_SKIP_NONE
-    hyper = apm.make_hyper(max_grad_norm=clip, skip_mode=skip)
-
-    plan = apm.apm_pack_plan(E, numels)
-    n_pages = plan.n_pages
-    pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages)
-
-    def gen(stream, bf16, sigma, active=None):
-        out = torch.zeros(total, dtype=torch.bfloat16 if bf16 else torch.float32, device=dev)
+    def gen(self, stream, bf16, sigma, active=None):
+        import torch
+        import synth
+        out = torch.zeros(self.total, dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
         fn = synth.normal_bf16 if bf16 else synth.normal_f32
         chunk = 1 << 26
-        for i in range(n_t):
+        # consecutive active tensors are generated as one range
+        i = 0
+        while i < self.n_t:
             if active is not None and not active[i]:
+                i += 1
                 continue
-            a0, n = int(off[i]), numels[i]
-            for a in range(a0, a0 + n, chunk):
-                m = min(chunk, a0 + n - a)
-                out[a:a + m] = fn(0, stream, a, m, sigma, device=dev)
+            j = i
+            while j + 1 < self.n_t and (active is None or active[j + 1]):
+                j += 1
+            a0, a1 = int(self.off[i]), int(self.off[j + 1])
+            for a in range(a0, a1, chunk):
+                m = min(chunk, a1 - a)
+                out[a:a + m] = fn(0, stream, a, m, sigma, device=DEV)
+            i = j + 1
         return out
 
-    def tensors(flat):
+    def tensors(self, flat):
+        import torch
+        import paper_2303_02868_amd as apm
         dt = apm.APM_BF16 if flat.dtype == torch.bfloat16 else apm.APM_F32
-        return apm.make_tensors(numels, dt, [flat.data_ptr() + int(off[i]) * flat.element_size()
-                                             for i in range(n_t)])
+        return apm.make_tensors(self.numels, dt, [flat.data_ptr() + int(self.off[i]) * flat.element_size()
+                                                  for i in range(self.n_t)])
 
-    p_flat = gen(1, False, 0.02)
-    apm.apm_pack_tensors(pool, apm.APM_P32, tensors(p_flat), n_t)
-    torch.cuda.synchronize()
-    del p_flat
-    # two gradient sets, alternated (values do not affect timing; they keep the state finite)
+
+def resident_leg(args, wl, pool, hyper, n_pages):
+    import torch
+    import paper_2303_02868_amd as apm
+    import synth
+    moe = wl.name == "moe_8x64"
     grads = []
-    for k in range(2):
-        act = synth.moe_active_tensors(specs, k + 1, 0, 64, 8) if args.workload == "moe_8x64" else None
-        grads.append(gen(1001 + k, True, 1e-3, act))
-    g_tensors = [tensors(g) for g in grads]
-    p16_flat = torch.zeros(total, dtype=torch.bfloat16, device=dev)
-    p16_tensors = tensors(p16_flat)
+    for k in range(2):          # two gradient sets, alternated (values do not affect timing)
+        act = synth.moe_active_tensors(wl.specs, k + 1, 0, 64, 8) if moe else None
+        grads.append(wl.gen(1001 + k, True, 1e-3, act))
+    g_tensors = [wl.tensors(g) for g in grads]
+    p16_flat = torch.zeros(wl.total, dtype=torch.bfloat16, device=DEV)
+    p16_tensors = wl.tensors(p16_flat)
     if args.update_only:
-        apm.apm_pack_tensors(pool, apm.APM_G16, g_tensors[0], n_t)
+        apm.apm_pack_tensors(pool, apm.APM_G16, g_tensors[0], wl.n_t)
     stream = torch.cuda.current_stream()
 
     def step(t):
         if not args.update_only:
-            apm.apm_pack_tensors(pool, apm.APM_G16, g_tensors[t & 1], n_t, stream)
+            apm.apm_pack_tensors(pool, apm.APM_G16, g_tensors[t & 1], wl.n_t, stream)
         apm.apm_page_adamw_step(pool, None, n_pages, t, hyper, None, None, stream)
         if not args.update_only:
-            apm.apm_unpack(pool, apm.APM_P16, p16_tensors, n_t, stream)
+            apm.apm_unpack(pool, apm.APM_P16, p16_tensors, wl.n_t, stream)
 
     t_step = 1
     for _ in range(args.warmup):
@@ -123,38 +131,38 @@ def main():
     wall = time.perf_counter() - t0
     ms, launches = apm.apm_pool_read_timing(pool)
     apm.apm_pool_set_timing(pool, False)
+    del grads, p16_flat
 
-    # active elements per step (skipped pages are not credited)
-    if args.workload == "moe_8x64":
-        act_elems = [int(sum(n for n, a in zip(numels, synth.moe_active_tensors(specs, k + 1, 0, 64, 8)) if a))
+    if moe:     # skipped pages are not credited
+        act_elems = [int(sum(n for n, a in zip(wl.numels, synth.moe_active_tensors(wl.specs, k + 1, 0, 64, 8)) if a))
                      for k in range(2)]
         elems_update = sum(act_elems) / 2.0
     else:
-        elems_update = float(total)
-    ms_per_step = wall * 1e3 / args.steps
-    value = elems_update * args.steps / wall
+        elems_update = float(wl.total)
 
     def avg(cls):
         return ms[cls] / launches[cls] if launches[cls] else None
 
-    upd_ms = avg(apm.APM_K_UPDATE)
-    red_ms = avg(apm.APM_K_REDUCE)
-    seg_ms = avg(apm.APM_K_SEGCOPY)
+    upd_ms, red_ms, seg_ms = avg(apm.APM_K_UPDATE), avg(apm.APM_K_REDUCE), avg(apm.APM_K_SEGCOPY)
     achieved = elems_update * BYTES_UPDATE / (upd_ms * 1e-3) / 1e9
     kernels = {"adamw_update": {"avg_ms": upd_ms, "launches": launches[apm.APM_K_UPDATE],
                                 "GBps": achieved, "bytes_per_elem": BYTES_UPDATE}}
     if red_ms:
         kernels["grad_reduce"] = {"avg_ms": red_ms, "launches": launches[apm.APM_K_REDUCE],
-                                  "GBps": total * BYTES_REDUCE / (red_ms * 1e-3) / 1e9,
+                                  "GBps": wl.total * BYTES_REDUCE / (red_ms * 1e-3) / 1e9,
                                   "bytes_per_elem": BYTES_REDUCE}
     if seg_ms:
         kernels["seg_copy_bf16"] = {"avg_ms": seg_ms, "launches": launches[apm.APM_K_SEGCOPY],
-                                    "GBps": total * BYTES_SEGCOPY_B16 / (seg_ms * 1e-3) / 1e9,
+                                    "GBps": wl.total * BYTES_SEGCOPY_B16 / (seg_ms * 1e-3) / 1e9,
                                     "bytes_per_elem": BYTES_SEGCOPY_B16}
+    return {"wall": wall, "elems_update": elems_update, "kernels": kernels, "achieved": achieved,
+            "upd_ms": upd_ms, "next_step": t_step}
 
-    # practical ceiling: a plain device-to-device copy of 2 GiB (read + write counted)
+
+def d2d_copy_ceiling():
+    import torch
     n_copy = 1 << 29
-    src = torch.empty(n_copy, dtype=torch.float32, device=dev)
+    src = torch.empty(n_copy, dtype=torch.float32, device=DEV)
     dst = torch.empty_like(src)
     for _ in range(3):
         dst.copy_(src)
@@ -164,55 +172,241 @@ def main():
         dst.copy_(src)
     e1.record()
     torch.cuda.synchronize()
-    copy_gbps = 10 * 2 * n_copy * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
+    return 10 * 2 * n_copy * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    traffic = None
-    pmc = os.path.join(ROOT, "profiles", f"adamw_update_{args.workload}_pmc.txt")
-    if os.path.exists(pmc):
-        for line in open(pmc):
-            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
-                traffic = float(line.split("=", 1)[1])
 
-    out = {
-        "metric": "page AdamW params/s", "value": value, "unit": "params/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": args.workload, "params": total, "pages": n_pages, "page_elems": E,
-                   "fragmentation": plan.fragmentation, "clip": clip, "skip_mode": skip,
-                   "step": "reduce+update" if args.update_only else "pack_g16+reduce+update+unpack_p16",
-                   "state": "fp32 p/m/v + bf16 g/p16 resident in HBM"},
-        "hbm_GBps_update_kernel": achieved, "hbm_frac_of_peak": achieved / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "apm_adamw_kernel", "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": traffic, "algorithmic_bytes_per_launch": elems_update * BYTES_UPDATE,
-                     "avg_launch_ms": upd_ms},
-        "kernels": kernels,
-        "d2d_copy_GBps": copy_gbps,
-    }
+def pcie_raw(host, devp, n_pages, E, state):
+    """Plain pinned copies through apm_page_copy_async: H2D alone, D2H alone, both at once.
+    Returns GB/s per direction."""
+    import torch
+    import paper_2303_02868_amd as apm
+    run = min(256, n_pages // 2)            # pages per copy (1 GiB at E = 1 Mi)
+    reps = max(2, min(8, (n_pages // 2) // run))
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    nbytes = reps * run * E * 4
+    half = n_pages // 2
+
+    def go(h2d, d2h):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(reps):
+            if h2d:
+                apm.apm_page_copy_async(devp, (r * run) % (half - run + 1), host, (r * run) % (half - run + 1), run, state, s1)
+            if d2h:
+                apm.apm_page_copy_async(host, half + (r * run) % (half - run + 1), devp, half + (r * run) % (half - run + 1), run, state, s2)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    go(True, True)
+    th = go(True, False)
+    td = go(False, True)
+    tb = go(True, True)
+    return {"h2d_GBps": nbytes / th / 1e9, "d2h_GBps": nbytes / td / 1e9,
+            "duplex_each_GBps": nbytes / tb / 1e9, "copy_bytes": run * E * 4}
+
+
+def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
+    """fp32 state in pinned host pages; dev_pool supplies G16/P16 and the layout."""
+    import torch
+    import paper_2303_02868_amd as apm
+    E = wl.E
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    has_fp32 = bool(dev_pool.desc.state_mask & 1)
+    stage_src = dev_pool
+    if has_fp32:
+        for st in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+            apm.apm_page_copy_async(host, 0, dev_pool, 0, n_pages, st)
+        torch.cuda.synchronize()
+    raw = None
+    if has_fp32:
+        raw = pcie_raw(host, dev_pool, n_pages, E, apm.APM_M32)
+        for st in (apm.APM_P32, apm.APM_M32, apm.APM_V32):     # restore what the raw copies overwrote
+            apm.apm_page_copy_async(dev_pool, 0, host, 0, n_pages, st)
+        torch.cuda.synchronize()
+    streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
+    stream = torch.cuda.current_stream()
+    t = first_step
+    apm.apm_streamer_step(streamer, t, hyper, None, None, stream)       # warm-up
+    t += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.stream_steps):
+        apm.apm_streamer_step(streamer, t, hyper, None, None, stream)
+        t += 1
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.stream_steps
+    streamer.destroy()
+    host.destroy()
+    each_way = n_pages * E * 12
+    out = {"ms_per_step": wall * 1e3, "params_per_s": wl.total / wall,
+           "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_each_way": each_way,
+           "batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
+           "host_pinned_GB": n_pages * E * 12 / 1e9}
+    if raw:
+        out["raw_pinned_copy"] = raw
+        out["frac_of_measured_duplex"] = out["pcie_GBps_each_way"] / raw["duplex_each_GBps"]
+        out["update_hidden"] = wall <= 1.02 * each_way / (raw["duplex_each_GBps"] * 1e9)
+    return out
+
+
+def cpu_baseline(args, E, n_pages, clip, skip):
+    import numpy as np
+    import torch
+    import oracle
+    import synth
+    n_cpu = min(args.cpu_pages, n_pages)
+    threads = min(16, os.cpu_count() or 1)
+    used = np.full(n_cpu, E, dtype=np.int64)
+    p_rows = synth.normal_f32(0, 1, 0, n_cpu * E, 0.02, device=DEV).cpu().numpy().reshape(n_cpu, E)
+    g_rows = synth.normal_bf16(0, 1001, 0, n_cpu * E, 1e-3, device=DEV).view(torch.int16).cpu().numpy().view(np.uint16).reshape(n_cpu, E)
+    st = oracle.PagedAdamWState(p_rows, used)
+    h = oracle.Hyper(max_grad_norm=clip, skip_mode=int(skip))
+    st.step(g_rows, 1, h, threads=threads)          # warm the pages
+    c0 = time.perf_counter()
+    for k in range(args.cpu_steps):
+        st.step(g_rows, 2 + k, h, threads=threads)
+    cw = time.perf_counter() - c0
+    return {"value": n_cpu * E * args.cpu_steps / cw, "unit": "params/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"{n_cpu} full pages x {args.cpu_steps} steps of the same update (reduce + AdamW "
+                      f"in double), pages split over {threads} threads, {cw:.2f} s wall"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2303_02868_amd as apm
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = Workload(args.workload)
+    E = wl.E
+    clip = args.clip if args.clip is not None else (1.0 if args.workload == "gpt_1p3b" else 0.0)
+    skip = apm.APM_SKIP_UNTOUCHED if args.workload == "moe_8x64" else apm.APM_SKIP_NONE
+    hyper = apm.make_hyper(max_grad_norm=clip, skip_mode=skip)
+    plan = apm.apm_pack_plan(E, wl.numels)
+    n_pages = plan.n_pages
+    streamed_only = args.streamed_only or args.workload == "gpt_13b"
+
+    out = {"metric": "page AdamW params/s", "value": None, "unit": "params/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": None,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": args.workload, "params": wl.total, "pages": n_pages, "page_elems": E,
+                      "fragmentation": plan.fragmentation, "clip": clip, "skip_mode": skip}}
+
+    if not streamed_only:
+        pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages)
+        p_flat = wl.gen(1, False, 0.02)
+        apm.apm_pack_tensors(pool, apm.APM_P32, wl.tensors(p_flat), wl.n_t)
+        torch.cuda.synchronize()
+        del p_flat
+        r = resident_leg(args, wl, pool, hyper, n_pages)
+        out["value"] = r["elems_update"] * args.steps / r["wall"]
+        out["ms_per_step"] = r["wall"] * 1e3 / args.steps
+        out["config"]["step"] = "reduce+update" if args.update_only else "pack_g16+reduce+update+unpack_p16"
+        out["config"]["state"] = "fp32 p/m/v + bf16 g/p16 resident in HBM"
+        traffic = None
+        pmc = os.path.join(ROOT, "profiles", f"adamw_update_{args.workload}_pmc.txt")
+        if os.path.exists(pmc):
+            for line in open(pmc):
+                if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                    traffic = float(line.split("=", 1)[1])
+        out["hbm_GBps_update_kernel"] = r["achieved"]
+        out["hbm_frac_of_peak"] = r["achieved"] / HBM_PEAK_GBPS
+        out["roofline"] = {"bound": "hbm", "kernel": "apm_adamw_kernel", "achieved": r["achieved"],
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": r["achieved"] / HBM_PEAK_GBPS,
+                           "traffic": traffic,
+                           "algorithmic_bytes_per_launch": r["elems_update"] * BYTES_UPDATE,
+                           "avg_launch_ms": r["upd_ms"]}
+        out["kernels"] = r["kernels"]
+        out["d2d_copy_GBps"] = d2d_copy_ceiling()
+        if not args.no_streamed:
+            apm.apm_pack_tensors(pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+            out["streamed"] = streamed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
+        pool.destroy()
+    else:
+        # fp32 state never resident: the GPU pool holds G16/P16 only.  If the box cannot pin the
+        # whole fp32 state, the depth of the 13 B shape shrinks until it fits (stated in the output).
+        if args.workload == "gpt_13b":
+            for layers in (40, 32, 24, 16, 8, 4):
+                wl = Workload(args.workload, layers)
+                plan = apm.apm_pack_plan(E, wl.numels)
+                n_pages = plan.n_pages
+                try:
+                    probe = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES,
+                                                flags=apm.APM_POOL_NO_ZERO)
+                except apm.ApmError as e:
+                    if e.code != apm.APM_ENOMEM:
+                        raise
+                    continue
+                probe.destroy()
+                break
+            out["config"].update({"params": wl.total, "pages": n_pages, "layers_used": layers,
+                                  "layers_of_full_shape": 40, "fragmentation": plan.fragmentation})
+        dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=apm.B16_STATES)
+        apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+        torch.cuda.synchronize()
+        s = streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages)
+        out["streamed"] = s
+        out["value"] = s["params_per_s"]
+        out["ms_per_step"] = s["ms_per_step"]
+        out["steps"] = args.stream_steps
+        out["warmup"] = 1
+        out["config"]["step"] = "H2D p,m,v -> reduce+update -> D2H p,m,v (3 streams)"
+        out["config"]["state"] = "fp32 p/m/v in pinned host pages, bf16 g/p16 resident in HBM"
+        dev_pool.destroy()
 
     if not args.no_cpu_baseline:
-        import oracle
-        n_cpu = min(args.cpu_pages, n_pages)
-        threads = min(16, os.cpu_count() or 1)
-        used = np.full(n_cpu, E, dtype=np.int64)
-        p_rows = synth.normal_f32(0, 1, 0, n_cpu * E, 0.02, device=dev).cpu().numpy().reshape(n_cpu, E)
-        g_rows = synth.normal_bf16(0, 1001, 0, n_cpu * E, 1e-3, device=dev).view(torch.int16).cpu().numpy().view(np.uint16).reshape(n_cpu, E)
-        st = oracle.PagedAdamWState(p_rows, used)
-        h = oracle.Hyper(max_grad_norm=clip, skip_mode=int(skip))
-        st.step(g_rows, 1, h, threads=threads)          # warm the pages
-        c0 = time.perf_counter()
-        for k in range(args.cpu_steps):
-            st.step(g_rows, 2 + k, h, threads=threads)
-        cw = time.perf_counter() - c0
-        out["cpu_baseline"] = {"value": n_cpu * E * args.cpu_steps / cw, "unit": "params/s",
-                               "cores": threads, "kind": "oracle",
-                               "sample": f"{n_cpu} full pages x {args.cpu_steps} steps of the same update "
-                                         f"(reduce + AdamW in double), pages split over {threads} threads, "
-                                         f"{cw:.2f} s wall"}
-    pool.destroy()
+        out["cpu_baseline"] = cpu_baseline(args, E, n_pages, clip, skip)
     print(json.dumps(out))
+
+
+def streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages):
+    """Streamed leg for a model whose fp32 state is only ever host-resident (13 B parameters)."""
+    import torch
+    import paper_2303_02868_amd as apm
+    E = wl.E
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    # master parameters: pack into a P32-only GPU pool, move the pages to the host, free it
+    tmp = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=1 << apm.APM_P32)
+    p_flat = wl.gen(1, False, 0.02)
+    apm.apm_pack_tensors(tmp, apm.APM_P32, wl.tensors(p_flat), wl.n_t)
+    apm.apm_page_copy_async(host, 0, tmp, 0, n_pages, apm.APM_P32)
+    torch.cuda.synchronize()
+    del p_flat
+    # raw PCIe with the momentum class of the host pool against the temporary pool's memory
+    tmp.destroy()
+    tmp2 = apm.apm_pool_create(apm.APM_DEV_GPU, E, min(n_pages, 2048), state_mask=1 << apm.APM_M32)
+    raw = pcie_raw(host, tmp2, min(n_pages, 2048), E, apm.APM_M32)
+    tmp2.destroy()
+    # the raw copies left arbitrary (zero) data in the first host momentum pages: still zero
+    streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
+    stream = torch.cuda.current_stream()
+    t = 1
+    apm.apm_streamer_step(streamer, t, hyper, None, None, stream)
+    t += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.stream_steps):
+        apm.apm_streamer_step(streamer, t, hyper, None, None, stream)
+        t += 1
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.stream_steps
+    streamer.destroy()
+    host.destroy()
+    each_way = n_pages * E * 12
+    out = {"ms_per_step": wall * 1e3, "params_per_s": wl.total / wall,
+           "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_each_way": each_way,
+           "batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
+           "host_pinned_GB": n_pages * E * 12 / 1e9, "raw_pinned_copy": raw,
+           "frac_of_measured_duplex": each_way / wall / 1e9 / raw["duplex_each_GBps"],
+           "update_hidden": wall <= 1.02 * each_way / (raw["duplex_each_GBps"] * 1e9)}
+    return out
 
 
 if __name__ == "__main__":

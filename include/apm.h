@@ -146,9 +146,8 @@ int apm_pack_plan(int64_t page_elems, const int64_t* numels, int64_t n, apm_segm
 /* ---- pool and page table (Sec. 4.1 Page; Sec. 5 "Allocator": pre-allocated memory cut into
  *      fixed-size pages) --------------------------------------------------------------------- */
 
-/* Creates a pool.  *out is written only on success.  Library-allocated regions, and caller regions
- * unless APM_POOL_NO_ZERO, are zero-filled (synchronously).  Errors: APM_EINVAL, APM_ENOMEM,
- * APM_EDEVICE. */
+/* Creates a pool.  *out is written only on success.  Every region is zero-filled (synchronously)
+ * unless APM_POOL_NO_ZERO is set.  Errors: APM_EINVAL, APM_ENOMEM, APM_EDEVICE. */
 int apm_pool_create(apm_pool** out, const apm_pool_desc* desc);
 
 /* Waits for the pool's internal streams, frees what the library allocated.  NULL is accepted. */
@@ -216,7 +215,8 @@ int apm_unpack(apm_pool* pool, int state, const apm_tensor* dst, int64_t n, void
  *   s = max_grad_norm > 0 ? min(1, max_grad_norm / (norm + 1e-6)) : 1,  g^ = s*g,
  *   m' = b1 m + (1-b1) g^;  v' = b2 v + (1-b2) g^2;
  *   p' = p (1 - lr wd) - lr (m'/(1-b1^t)) / (sqrt(v'/(1-b2^t)) + eps);   p16' = bf16_rne(p').
- * Arithmetic is fp32 with correctly rounded divide and square root.
+ * Arithmetic is fp32 with correctly rounded divide and square root; p' is evaluated as
+ * p - (lr wd p + (lr/(1-b1^t)) m'/denom) so that it is rounded once at the magnitude of p.
  *
  * pages: host pointer to n_pages distinct page indices, or NULL = pages [0, n_pages).
  * grad_norm (float[n_pages]) and skip_mask (uint8_t[n_pages]): device pointers, nullable,

@@ -52,6 +52,11 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 }
 
 // ---- tunables (defaults measured on MI355X; see the sweep notes next to each) ----------------
+#ifndef APM_FAST_RCP_SQRT
+// 1: hardware 1-ulp reciprocal and square root instead of the correctly rounded sequences.
+// Measured slower (6.0 vs 6.25 TB/s): the kernel is not ALU-bound, so the exact forms stay.
+#define APM_FAST_RCP_SQRT 0
+#endif
 #ifndef APM_REDUCE_U
 #define APM_REDUCE_U 4          // 128-bit loads in flight per lane in the reduce kernel
 #endif
@@ -63,10 +68,10 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 #endif
 #ifndef APM_UPDATE_LDS
 // Dynamic LDS requested per workgroup for no purpose other than capping residency at
-// 160 KiB / 16 KiB = 10 wavefronts per CU: with four read and four write streams per wavefront,
-// more resident wavefronts lower the achieved HBM bandwidth (6.1 TB/s unlimited, 6.4 TB/s at 10,
-// 5.7 TB/s at 6 on the 28 B/element access pattern).
-#define APM_UPDATE_LDS 16384
+// 160 KiB / 20 KiB = 8 wavefronts per CU: with four read and four write streams per wavefront,
+// more resident wavefronts lower the achieved HBM bandwidth (measured on the 1.3 B-parameter
+// workload: 5.6 TB/s uncapped, 6.0 at 13, 6.18 at 10, 6.25 at 8, 6.1 at 6 wavefronts per CU).
+#define APM_UPDATE_LDS 20480
 #endif
 
 struct ReduceArgs {
@@ -222,10 +227,16 @@ __device__ __forceinline__ void adamw_elem(float& p, float& m, float& v, float g
     const float gs = g * scale;
     m = fmaf(a.b1, m, a.omb1 * gs);
     v = fmaf(a.b2, v, a.omb2 * (gs * gs));
+#if APM_FAST_RCP_SQRT
+    const float denom = fmaf(__builtin_amdgcn_sqrtf(v), a.inv_sqrt_bc2, a.eps);
+    const float upd = m * __builtin_amdgcn_rcpf(denom);
+#else
     const float denom = fmaf(sqrtf(v), a.inv_sqrt_bc2, a.eps);
+    const float upd = m / denom;
+#endif
     // p' = p - (lr wd p + (lr/bc1) m'/denom): the two small terms are summed first, so the only
     // rounding at the magnitude of p is the final subtraction (half an ulp per step).
-    const float delta = fmaf(a.step_size, m / denom, a.lr_wd * p);
+    const float delta = fmaf(a.step_size, upd, a.lr_wd * p);
     p = p - delta;
 }
 

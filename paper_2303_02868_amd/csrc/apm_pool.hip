@@ -1,5 +1,6 @@
 // Page pool, page table, pack / unpack entry points and page copies (host side).
 #include <cstring>
+#include <thread>
 
 #include "apm_internal.h"
 
@@ -64,13 +65,24 @@ size_t region_bytes(const apm_pool* p, int state) {
     return (size_t)p->desc.n_pages * (size_t)p->desc.page_elems * (size_t)elem_bytes(state);
 }
 
-int zero_regions(apm_pool* pool, hipStream_t s, bool only_unowned_if_flag) {
+int zero_regions(apm_pool* pool, hipStream_t s, bool at_create) {
     for (int st = 0; st < APM_N_STATES; ++st) {
         if (!pool->stores(st)) continue;
-        if (only_unowned_if_flag && !pool->owned[st] && (pool->desc.flags & APM_POOL_NO_ZERO)) continue;
+        if (at_create && (pool->desc.flags & APM_POOL_NO_ZERO)) continue;
         if (pool->desc.device == APM_DEV_HOST) {
             APM_HIP(hipStreamSynchronize(s));
-            std::memset(pool->base[st], 0, region_bytes(pool, st));
+            // a host region can be ~100 GB: spread the page-touching over a few threads
+            const size_t bytes = region_bytes(pool, st);
+            const size_t n_thr = bytes >= ((size_t)1 << 30) ? 8 : 1;
+            const size_t per = (bytes / n_thr + 4095) / 4096 * 4096;
+            std::vector<std::thread> thr;
+            char* base = static_cast<char*>(pool->base[st]);
+            for (size_t k = 0; k < n_thr; ++k) {
+                const size_t a = k * per < bytes ? k * per : bytes;
+                const size_t b = (k + 1) * per < bytes ? (k + 1) * per : bytes;
+                if (b > a) thr.emplace_back([=] { std::memset(base + a, 0, b - a); });
+            }
+            for (auto& t : thr) t.join();
         } else {
             APM_HIP(hipMemsetAsync(pool->base[st], 0, region_bytes(pool, st), s));
         }
@@ -211,8 +223,10 @@ extern "C" int apm_pool_create(apm_pool** out, const apm_pool_desc* desc) {
                                                     : hipMalloc(&p, region_bytes(pool, st));
         if (e != hipSuccess) {
             (void)hipGetLastError();
+            const size_t wanted = region_bytes(pool, st);
             free_pool(pool);
-            return fail(APM_ENOMEM, "allocating %zu bytes for state class %d failed: %s", region_bytes(pool, st), st, hipGetErrorString(e));
+            return fail(APM_ENOMEM, "allocating %zu bytes of %s memory for state class %d failed: %s", wanted,
+                        desc->device == APM_DEV_HOST ? "pinned host" : "device", st, hipGetErrorString(e));
         }
         pool->base[st] = p;
         pool->owned[st] = true;

@@ -84,3 +84,64 @@ def test_streamed_equals_resident_bit_exact(batch, slots, clip):
     host.destroy()
     dev.destroy()
     res.destroy()
+
+
+def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
+    # GPT-13B-shaped layers (d = 5120, ffn = 20480); fp32 state only ever lives in pinned host pages.
+    # The box decides how much can be pinned: the layer count shrinks until the host pool fits (the
+    # full 40 layers need ~158 GB pinned), which changes the page count but not the path.
+    from gpu_helpers import HOST_THREADS
+    E = 1 << 20
+    host = None
+    for layers in (40, 32, 24, 16, 8, 4):
+        specs = synth.gpt_tensor_list(layers, 5120, 20480, 50257, 2048)
+        plan = oracle.plan_pack([t.numel for t in specs], E)
+        try:
+            host = apm.apm_pool_create(apm.APM_DEV_HOST, E, plan.n_pages, state_mask=apm.FP32_STATES)
+            break
+        except apm.ApmError as e:
+            assert e.code == apm.APM_ENOMEM
+            print(f"cfg4: {layers} layers ({plan.n_pages} pages) cannot be pinned: {e}", flush=True)
+    assert host is not None
+    model = Model(specs, E, seed=0)
+    n_pages, n_t = plan.n_pages, len(specs)
+    print(f"cfg4: {layers} layers, {model.total} params, {n_pages} pages, "
+          f"{n_pages * E * 12 / 2**30:.1f} GiB pinned", flush=True)
+    sample = sorted(set(range(0, n_pages, 257)) | {0, n_pages - 1}
+                    | {k for k, p in enumerate(plan.pages) if p.used < E})
+    used = [plan.pages[p].used for p in sample]
+    h = oracle.Hyper(max_grad_norm=1.0)
+    hy = to_hyper(h)
+
+    tmp = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=1 << apm.APM_P32)
+    apm.apm_pack_tensors(tmp, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    apm.apm_page_copy_async(host, 0, tmp, 0, n_pages, apm.APM_P32)
+    torch.cuda.synchronize()
+    tmp.destroy()
+    st = oracle.PagedAdamWState(model.host_pages(model.p_flat, sample).view(np.float32), used)
+    del model.p_flat
+    torch.cuda.empty_cache()
+
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, apm.make_tensors(model.numels, apm.APM_BF16), n_t)
+    streamer = apm.apm_streamer_create(host, dev.pool, 32, 3)
+    norm_d = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_streamer_step(streamer, t, hy, norm_d, None)
+        norms, _ = st.step(model.host_pages(g, sample), t, h, threads=HOST_THREADS)
+        torch.cuda.synchronize()
+        got = norm_d.cpu().numpy()[sample]
+        assert np.all(np.abs(got - norms) <= 1e-6 * np.abs(norms))
+        del g
+    rows = {}
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        rows[s_] = host_view(host, s_, n_pages, E)[sample]
+    worst = {k: check_state_close(k, rows[s_], ref, used)
+             for k, s_, ref in (("p", apm.APM_P32, st.p), ("m", apm.APM_M32, st.m), ("v", apm.APM_V32, st.v))}
+    print(f"cfg4 worst rel err {worst}", flush=True)
+    check_p16(dev.rows_b16(apm.APM_P16, sample), rows[apm.APM_P32], st.p16, used)
+    streamer.destroy()
+    host.destroy()
+    dev.destroy()
