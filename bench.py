@@ -205,6 +205,56 @@ def pcie_raw(host, devp, n_pages, E, state):
             "duplex_each_GBps": nbytes / tb / 1e9, "copy_bytes": run * E * 4}
 
 
+def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_params):
+    """Warm-up step, copy-only pipeline passes (the denominator), timed full steps."""
+    import torch
+    import paper_2303_02868_amd as apm
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    t = [first_step]
+
+    def full():
+        apm.apm_streamer_step(streamer, t[0], hyper, None, None, stream)
+        t[0] += 1
+
+    full()                                                    # warm-up
+    # Full steps and copy-only passes are interleaved and the fastest of each is kept: the PCIe
+    # path is shared with other tenants of the host, and its rate was seen to dip for whole runs.
+    walls, boths = [], []
+    t_h2d = timed(lambda: apm.apm_streamer_copy_only(streamer, 1, stream), 1)
+    for _ in range(args.stream_steps):
+        boths.append(timed(lambda: apm.apm_streamer_copy_only(streamer, 3, stream), 1))
+        walls.append(timed(full, 1))
+    wall, t_both = min(walls), min(boths)
+    t_both2 = t_both
+    # copy-out alone writes stale staging contents back to the host pool: measured last
+    t_d2h = timed(lambda: apm.apm_streamer_copy_only(streamer, 2, stream), 1)
+    each_way = n_pages * E * 12
+    t_copy = max(min(t_both, t_both2), t_h2d, t_d2h)
+    out = {"ms_per_step": wall * 1e3, "ms_per_step_all": [w * 1e3 for w in walls],
+           "params_per_s": total_params / wall,
+           "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_each_way": each_way,
+           "batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
+           "host_pinned_GB": n_pages * E * 12 / 1e9,
+           "copy_only_pipeline": {"both_ms": min(t_both, t_both2) * 1e3, "h2d_only_ms": t_h2d * 1e3,
+                                  "d2h_only_ms": t_d2h * 1e3,
+                                  "both_GBps_each_way": each_way / min(t_both, t_both2) / 1e9,
+                                  "h2d_GBps": each_way / t_h2d / 1e9, "d2h_GBps": each_way / t_d2h / 1e9},
+           "frac_of_measured_pcie": t_copy / wall,
+           "update_hidden": wall <= 1.02 * t_copy}
+    if raw:
+        out["raw_pinned_copy"] = raw
+    return out
+
+
 def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
     """fp32 state in pinned host pages; dev_pool supplies G16/P16 and the layout."""
     import torch
@@ -224,28 +274,9 @@ def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
             apm.apm_page_copy_async(dev_pool, 0, host, 0, n_pages, st)
         torch.cuda.synchronize()
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
-    stream = torch.cuda.current_stream()
-    t = first_step
-    apm.apm_streamer_step(streamer, t, hyper, None, None, stream)       # warm-up
-    t += 1
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.stream_steps):
-        apm.apm_streamer_step(streamer, t, hyper, None, None, stream)
-        t += 1
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) / args.stream_steps
+    out = time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, wl.total)
     streamer.destroy()
     host.destroy()
-    each_way = n_pages * E * 12
-    out = {"ms_per_step": wall * 1e3, "params_per_s": wl.total / wall,
-           "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_each_way": each_way,
-           "batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
-           "host_pinned_GB": n_pages * E * 12 / 1e9}
-    if raw:
-        out["raw_pinned_copy"] = raw
-        out["frac_of_measured_duplex"] = out["pcie_GBps_each_way"] / raw["duplex_each_GBps"]
-        out["update_hidden"] = wall <= 1.02 * each_way / (raw["duplex_each_GBps"] * 1e9)
     return out
 
 
@@ -372,40 +403,21 @@ def streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages):
     import paper_2303_02868_amd as apm
     E = wl.E
     host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
-    # master parameters: pack into a P32-only GPU pool, move the pages to the host, free it
+    # Master parameters: pack into a P32-only GPU pool and move the pages to the host.  That pool
+    # stays alive until the end: on this platform, releasing a multi-GB device allocation lowered
+    # device-to-host copy throughput (57 -> 30 GB/s) for the rest of the process.
     tmp = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=1 << apm.APM_P32)
     p_flat = wl.gen(1, False, 0.02)
     apm.apm_pack_tensors(tmp, apm.APM_P32, wl.tensors(p_flat), wl.n_t)
     apm.apm_page_copy_async(host, 0, tmp, 0, n_pages, apm.APM_P32)
     torch.cuda.synchronize()
-    del p_flat
-    # raw PCIe with the momentum class of the host pool against the temporary pool's memory
-    tmp.destroy()
-    tmp2 = apm.apm_pool_create(apm.APM_DEV_GPU, E, min(n_pages, 2048), state_mask=1 << apm.APM_M32)
-    raw = pcie_raw(host, tmp2, min(n_pages, 2048), E, apm.APM_M32)
-    tmp2.destroy()
-    # the raw copies left arbitrary (zero) data in the first host momentum pages: still zero
+    # raw PCIe: both pools hold the same P32 pages, so copying them either way changes nothing
+    raw = pcie_raw(host, tmp, n_pages, E, apm.APM_P32)
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
-    stream = torch.cuda.current_stream()
-    t = 1
-    apm.apm_streamer_step(streamer, t, hyper, None, None, stream)
-    t += 1
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.stream_steps):
-        apm.apm_streamer_step(streamer, t, hyper, None, None, stream)
-        t += 1
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) / args.stream_steps
+    out = time_streamer(args, streamer, hyper, 1, n_pages, E, raw, wl.total)
     streamer.destroy()
     host.destroy()
-    each_way = n_pages * E * 12
-    out = {"ms_per_step": wall * 1e3, "params_per_s": wl.total / wall,
-           "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_each_way": each_way,
-           "batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
-           "host_pinned_GB": n_pages * E * 12 / 1e9, "raw_pinned_copy": raw,
-           "frac_of_measured_duplex": each_way / wall / 1e9 / raw["duplex_each_GBps"],
-           "update_hidden": wall <= 1.02 * each_way / (raw["duplex_each_GBps"] * 1e9)}
+    tmp.destroy()
     return out
 
 

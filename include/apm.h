@@ -262,6 +262,14 @@ int apm_streamer_destroy(apm_streamer* s);
 int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, float* grad_norm,
                       uint8_t* skip_mask, void* stream);
 
+/*
+ * Measurement aid: the same pipeline (streams, events, copy sizes, slot reuse) with the kernels
+ * left out.  directions: 1 = copy-in only, 2 = copy-out only, 3 = both.  The data make a round
+ * trip host -> staging -> host, so the host pool's contents are unchanged (with 2 alone, staging
+ * contents left by an earlier step are written back: call it only after 1 or 3, or a full step).
+ */
+int apm_streamer_copy_only(apm_streamer* s, int directions, void* stream);
+
 /* ---- one-step-stale update (Alg. 2 reduced to one GPU: apply the buffered gradient while the
  *      next one is being staged) -------------------------------------------------------------- */
 

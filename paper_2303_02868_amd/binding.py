@@ -28,7 +28,7 @@ EXPORTS = [
     "apm_last_error", "apm_pack_plan", "apm_pool_create", "apm_pool_destroy",
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_copy_async",
-    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_step_delayed",
+    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -103,6 +103,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
+    L.apm_streamer_copy_only.argtypes = [vp, i32, vp]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
     L.apm_delayed_applied.argtypes = [vp]
     L.apm_delayed_applied.restype = i64
@@ -305,6 +306,10 @@ def apm_streamer_step(s: Streamer, step: int, hyper: apm_hyper, grad_norm=None, 
                       stream=None) -> None:
     _check(lib().apm_streamer_step(s.handle, step, C.byref(hyper), _ptr(grad_norm),
                                    _ptr(skip_mask), _stream(stream)))
+
+
+def apm_streamer_copy_only(s: Streamer, directions: int, stream=None) -> None:
+    _check(lib().apm_streamer_copy_only(s.handle, directions, _stream(stream)))
 
 
 def apm_step_delayed(pool: Pool, pages: Optional[Sequence[int]], n_pages: int, new_g16,

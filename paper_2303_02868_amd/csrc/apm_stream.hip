@@ -89,14 +89,20 @@ extern "C" int apm_streamer_destroy(apm_streamer* s) {
     return APM_OK;
 }
 
-extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper,
-                                 float* grad_norm, uint8_t* skip_mask, void* stream) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
+namespace {
+enum { kDoH2D = 1, kDoD2H = 2, kDoUpdate = 4 };
+
+// The pipeline.  `what` selects its parts: the full step uses all three; the copy-only
+// measurement entry point drops the kernels (and optionally one direction) but keeps the streams,
+// the event structure and the copy sizes.
+int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper, float* grad_norm,
+                 uint8_t* skip_mask, void* stream) {
     apm_pool* dev = s->dev;
     apm_pool* host = s->host;
     if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
     AdamwLaunch L{};
-    int rc = prepare_hyper(hyper, step, &L);
+    int rc = APM_OK;
+    if (what & kDoUpdate) rc = prepare_hyper(hyper, step, &L);
     if (rc != APM_OK) return rc;
     APM_HIP(hipSetDevice(dev->desc.hip_device));
     hipStream_t caller = static_cast<hipStream_t>(stream);
@@ -131,7 +137,7 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
         const int64_t nb = N - first < s->B ? N - first : s->B;
         const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
         if (b >= s->n_slots) APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_d2h[slot], 0));
-        for (int k = 0; k < 3; ++k) {
+        for (int k = 0; k < 3 && (what & kDoH2D); ++k) {
             const char* src = static_cast<const char*>(host->base[states[k]]) + (size_t)first * pb;
             APM_HIP(hipMemcpyAsync(s->stage[k] + slot_off, src, pb * (size_t)nb, hipMemcpyHostToDevice, s->s_in));
         }
@@ -143,12 +149,14 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
         L.n_listed = nb;
         L.grad_norm = grad_norm ? grad_norm + first : nullptr;
         L.skip_mask = skip_mask ? skip_mask + first : nullptr;
-        if (need_reduce) APM_HIP(launch_grad_reduce(L, s->s_cmp));
-        APM_HIP(launch_adamw(L, s->s_cmp));
+        if (what & kDoUpdate) {
+            if (need_reduce) APM_HIP(launch_grad_reduce(L, s->s_cmp));
+            APM_HIP(launch_adamw(L, s->s_cmp));
+        }
         APM_HIP(hipEventRecord(s->ev_cmp[slot], s->s_cmp));
 
         APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_cmp[slot], 0));
-        for (int k = 0; k < 3; ++k) {
+        for (int k = 0; k < 3 && (what & kDoD2H); ++k) {
             char* dst = static_cast<char*>(host->base[states[k]]) + (size_t)first * pb;
             APM_HIP(hipMemcpyAsync(dst, s->stage[k] + slot_off, pb * (size_t)nb, hipMemcpyDeviceToHost, s->s_out));
         }
@@ -157,4 +165,17 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
     APM_HIP(hipEventRecord(s->ev_done, s->s_out));
     APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
     return APM_OK;
+}
+}  // namespace
+
+extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper,
+                                 float* grad_norm, uint8_t* skip_mask, void* stream) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+}
+
+extern "C" int apm_streamer_copy_only(apm_streamer* s, int directions, void* stream) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    if (directions < 1 || directions > 3) return fail(APM_EINVAL, "directions must be 1 (H2D), 2 (D2H) or 3 (both)");
+    return run_pipeline(s, directions, 1, nullptr, nullptr, nullptr, stream);
 }

@@ -117,10 +117,7 @@ def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
     apm.apm_pack_tensors(tmp, apm.APM_P32, model.tensors(model.p_flat), n_t)
     apm.apm_page_copy_async(host, 0, tmp, 0, n_pages, apm.APM_P32)
     torch.cuda.synchronize()
-    tmp.destroy()
     st = oracle.PagedAdamWState(model.host_pages(model.p_flat, sample).view(np.float32), used)
-    del model.p_flat
-    torch.cuda.empty_cache()
 
     dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
     apm.apm_pool_set_layout(dev.pool, apm.make_tensors(model.numels, apm.APM_BF16), n_t)
@@ -145,3 +142,4 @@ def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
     streamer.destroy()
     host.destroy()
     dev.destroy()
+    tmp.destroy()
