@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--clip", type=float, default=None,
                     help="per-page max grad norm (default: 1.0 for gpt_1p3b, else off)")
     ap.add_argument("--update-only", action="store_true", help="time reduce+update only (no pack/unpack)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="headline step = separate pack g16 / unpack p16 kernels instead of the fused gather/scatter")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pages", type=int, default=192, help="pages of the workload the oracle is timed on")
     ap.add_argument("--cpu-steps", type=int, default=2)
@@ -94,7 +96,7 @@ class Workload:
                                                   for i in range(self.n_t)])
 
 
-def resident_leg(args, wl, pool, hyper, n_pages):
+def resident_leg(args, wl, pool, hyper, n_pages, fused, steps, warmup, first_step=1):
     import torch
     import paper_2303_02868_amd as apm
     import synth
@@ -111,20 +113,24 @@ def resident_leg(args, wl, pool, hyper, n_pages):
     stream = torch.cuda.current_stream()
 
     def step(t):
-        if not args.update_only:
+        if args.update_only:
+            apm.apm_page_adamw_step(pool, None, n_pages, t, hyper, None, None, stream)
+        elif fused:
+            apm.apm_page_adamw_step_fused(pool, None, n_pages, t, hyper, g_tensors[t & 1], p16_tensors,
+                                          wl.n_t, None, None, stream)
+        else:
             apm.apm_pack_tensors(pool, apm.APM_G16, g_tensors[t & 1], wl.n_t, stream)
-        apm.apm_page_adamw_step(pool, None, n_pages, t, hyper, None, None, stream)
-        if not args.update_only:
+            apm.apm_page_adamw_step(pool, None, n_pages, t, hyper, None, None, stream)
             apm.apm_unpack(pool, apm.APM_P16, p16_tensors, wl.n_t, stream)
 
-    t_step = 1
-    for _ in range(args.warmup):
+    t_step = first_step
+    for _ in range(warmup):
         step(t_step)
         t_step += 1
     torch.cuda.synchronize()
     apm.apm_pool_set_timing(pool, True)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(t_step)
         t_step += 1
     torch.cuda.synchronize()
@@ -336,10 +342,19 @@ def main():
         apm.apm_pack_tensors(pool, apm.APM_P32, wl.tensors(p_flat), wl.n_t)
         torch.cuda.synchronize()
         del p_flat
-        r = resident_leg(args, wl, pool, hyper, n_pages)
+        fused = not args.unfused and not args.update_only
+        r = resident_leg(args, wl, pool, hyper, n_pages, fused, args.steps, args.warmup)
         out["value"] = r["elems_update"] * args.steps / r["wall"]
         out["ms_per_step"] = r["wall"] * 1e3 / args.steps
-        out["config"]["step"] = "reduce+update" if args.update_only else "pack_g16+reduce+update+unpack_p16"
+        out["config"]["step"] = ("reduce+update on resident pages" if args.update_only else
+                                 "grad reduce + fused AdamW, both reading g16 from the tensors; p16 written to "
+                                 "the tensors (pack/unpack fused into the kernels)" if fused else
+                                 "pack_g16 + reduce + update + unpack_p16 (separate kernels)")
+        if fused:   # the same step with separate pack / unpack kernels, for comparison
+            r2 = resident_leg(args, wl, pool, hyper, n_pages, False, max(3, args.steps // 4), 1, r["next_step"])
+            out["unfused_step"] = {"ms_per_step": r2["wall"] * 1e3 / max(3, args.steps // 4),
+                                   "kernels": r2["kernels"]}
+            r["next_step"] = r2["next_step"]
         out["config"]["state"] = "fp32 p/m/v + bf16 g/p16 resident in HBM"
         traffic = None
         pmc = os.path.join(ROOT, "profiles", f"adamw_update_{args.workload}_pmc.txt")

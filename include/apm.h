@@ -228,6 +228,22 @@ int apm_page_adamw_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, i
                         const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,
                         void* stream);
 
+/*
+ * The same step with the gather and/or scatter fused into the kernels: gradients are read straight
+ * from the caller's contiguous bf16 tensors (grad_tensors != NULL; the G16 class is not touched
+ * and need not be stored) and the bf16 parameters are written straight into the caller's
+ * contiguous bf16 tensors (p16_tensors != NULL; the P16 class is not touched).  This removes the
+ * pack / unpack passes over 16-bit data (8 B/element of HBM traffic) from a training step; the
+ * result is bit-identical to apm_pack_tensors(G16) + apm_page_adamw_step + apm_unpack(P16).
+ * Each list must have the numels of the installed layout (APM_ESTATE otherwise), dtype APM_BF16
+ * and 16-byte aligned device pointers (APM_EINVAL otherwise); either list may be NULL.
+ * Listed pages must be pages the layout uses.
+ */
+int apm_page_adamw_step_fused(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
+                              const apm_hyper* hyper, const apm_tensor* grad_tensors,
+                              const apm_tensor* p16_tensors, int64_t n_tensors, float* grad_norm,
+                              uint8_t* skip_mask, void* stream);
+
 /* ---- page movement (Page listing: move; Sec. 5 "Allocator": asynchronous GPU-CPU copies) --- */
 
 /*

@@ -27,7 +27,8 @@ B16_STATES = 0b11000
 EXPORTS = [
     "apm_last_error", "apm_pack_plan", "apm_pool_create", "apm_pool_destroy",
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
-    "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_copy_async",
+    "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
+    "apm_page_copy_async",
     "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
@@ -99,6 +100,8 @@ def lib() -> C.CDLL:
                                    P(C.c_double), vp]
     L.apm_unpack.argtypes = [vp, i32, P(apm_tensor), i64, vp]
     L.apm_page_adamw_step.argtypes = [vp, P(i64), i64, i64, P(apm_hyper), vp, vp, vp]
+    L.apm_page_adamw_step_fused.argtypes = [vp, P(i64), i64, i64, P(apm_hyper), P(apm_tensor),
+                                            P(apm_tensor), i64, vp, vp, vp]
     L.apm_page_copy_async.argtypes = [vp, i64, vp, i64, i64, i32, vp]
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
@@ -268,6 +271,15 @@ def apm_page_adamw_step(pool: Pool, pages: Optional[Sequence[int]], n_pages: int
     arr, _ = _i64_array(pages)
     _check(lib().apm_page_adamw_step(pool.handle, arr, n_pages, step, C.byref(hyper),
                                      _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
+
+
+def apm_page_adamw_step_fused(pool: Pool, pages: Optional[Sequence[int]], n_pages: int, step: int,
+                              hyper: apm_hyper, grad_tensors, p16_tensors, n_tensors: int,
+                              grad_norm=None, skip_mask=None, stream=None) -> None:
+    arr, _ = _i64_array(pages)
+    _check(lib().apm_page_adamw_step_fused(pool.handle, arr, n_pages, step, C.byref(hyper),
+                                           grad_tensors, p16_tensors, n_tensors, _ptr(grad_norm),
+                                           _ptr(skip_mask), _stream(stream)))
 
 
 def apm_page_copy_async(dst: Pool, dst_page: int, src: Pool, src_page: int, n_pages: int,

@@ -74,8 +74,60 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 #define APM_UPDATE_LDS 20480
 #endif
 
+// Gradient elements [e, e+8) of a page, read from its tenant tensors; elements that belong to no
+// tenant (alignment gap, padding) read as zero.  e is a multiple of 8, as every tenant offset is,
+// so a vector never straddles the start of the second tenant.
+__device__ __forceinline__ u32x4 gather_g8(const PageSegs& s, int e) {
+    const int k = (s.n[1] > 0 && e >= s.off[1]) ? 1 : 0;
+    const int rel = e - s.off[k];
+    const int n = s.n[k];
+    u32x4 w = u32x4{0u, 0u, 0u, 0u};
+    if (rel >= 0 && rel + 8 <= n) {
+        w = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(s.g[k] + rel));
+    } else if (rel >= 0 && rel < n) {  // last, partial vector of the tensor: never read past its end
+        const uint16_t* src = s.g[k] + rel;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (rel + j < n) w[j >> 1] |= (uint32_t)src[j] << (16 * (j & 1));
+    }
+    return w;
+}
+
+__device__ __forceinline__ u32x2 gather_g4(const PageSegs& s, int e) {
+    const int k = (s.n[1] > 0 && e >= s.off[1]) ? 1 : 0;
+    const int rel = e - s.off[k];
+    const int n = s.n[k];
+    u32x2 w = u32x2{0u, 0u};
+    if (rel >= 0 && rel + 4 <= n) {
+        w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(s.g[k] + rel));
+    } else if (rel >= 0 && rel < n) {
+        const uint16_t* src = s.g[k] + rel;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (rel + j < n) w[j >> 1] |= (uint32_t)src[j] << (16 * (j & 1));
+    }
+    return w;
+}
+
+// bf16 parameters of page elements [e, e+4) written to the tenant tensor they belong to; elements
+// of no tenant are dropped.
+__device__ __forceinline__ void scatter_q4(const PageSegs& s, int e, u32x2 o) {
+    const int k = (s.n[1] > 0 && e >= s.off[1]) ? 1 : 0;
+    const int rel = e - s.off[k];
+    const int n = s.n[k];
+    if (rel >= 0 && rel + 4 <= n) {
+        __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(s.q[k] + rel));
+    } else if (rel >= 0 && rel < n) {
+        uint16_t* dst = s.q[k] + rel;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (rel + j < n) dst[j] = (uint16_t)(o[j >> 1] >> (16 * (j & 1)));
+    }
+}
+
 struct ReduceArgs {
     const uint16_t* g16;
+    const PageSegs* segs;
     const int32_t* used;
     const int64_t* grad_pages;
     int64_t grad_first;
@@ -90,6 +142,7 @@ struct ReduceArgs {
 // gradient elements.  Slice 0 always writes (a zero for an empty page); other slices only when
 // they hold used elements.  The fixed order (lane-sequential, wavefront butterfly, wave 0..3)
 // makes the result independent of scheduling.
+template <bool GATHER>
 __global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a) {
     const int64_t i = a.list_offset + blockIdx.y;
     const int64_t page = a.grad_pages ? a.grad_pages[i] : a.grad_first + i;
@@ -97,7 +150,17 @@ __global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a)
     const int start = blockIdx.x * kReduceTile;
     if (start >= used && blockIdx.x != 0) return;
     const int end = min(start + kReduceTile, used);
-    const uint16_t* g = a.g16 + page * a.E;
+    const uint16_t* g = GATHER ? nullptr : a.g16 + page * a.E;
+    PageSegs segs{};
+    bool edge = false;  // gather only: this slice is not wholly inside one tenant
+    if (GATHER) {
+        segs = a.segs[page];
+        const int k = (segs.n[1] > 0 && start >= segs.off[1]) ? 1 : 0;
+        const int rel = start - segs.off[k];
+        // Wholly inside tenant k: address it like a page whose element 0 sits at g[k] - off[k].
+        if (rel >= 0 && rel + (end - start) <= segs.n[k]) g = segs.g[k] - segs.off[k];
+        else edge = true;
+    }
 
     double acc0 = 0.0, acc1 = 0.0;
     uint32_t nz = 0;
@@ -113,7 +176,10 @@ __global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a)
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * (kThreads * 8);
             w[u] = u32x4{0u, 0u, 0u, 0u};
-            if (e < end) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g + e));
+            if (e < end) {
+                if (GATHER && edge) w[u] = gather_g8(segs, e);
+                else w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(g + e));
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -211,6 +277,7 @@ struct UpdateArgs {
     float* v32;
     const uint16_t* g16;
     uint16_t* p16;
+    const PageSegs* segs;
     const int32_t* used;
     const int64_t* state_pages;
     const int64_t* grad_pages;
@@ -247,6 +314,8 @@ constexpr int kUpdTile = kUpdThreads * 4 * kUpdU;  // elements per workgroup
 // Fused update of one slice of one page: 12 B + 2 B read and 12 B + 2 B written per element.
 // Each lane keeps kUpdU 128-bit vectors per fp32 class in flight; every wavefront-wide access is
 // one contiguous 1 KiB (fp32) or 512 B (bf16) span.
+// GATHER / SCATTER: read g from / write p16 to the tenant tensors instead of the page classes.
+template <bool GATHER, bool SCATTER>
 __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     const int64_t i = a.list_offset + blockIdx.y;
     const int64_t gpage = a.grad_pages ? a.grad_pages[i] : a.grad_first + i;
@@ -262,8 +331,24 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
     f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
     f32x4* __restrict__ V = reinterpret_cast<f32x4*>(a.v32 + spage * a.E);
-    const u32x2* __restrict__ G = reinterpret_cast<const u32x2*>(a.g16 + gpage * a.E);
-    u32x2* __restrict__ P16 = reinterpret_cast<u32x2*>(a.p16 + gpage * a.E);
+    const u32x2* __restrict__ G = GATHER ? nullptr : reinterpret_cast<const u32x2*>(a.g16 + gpage * a.E);
+    u32x2* __restrict__ P16 = SCATTER ? nullptr : reinterpret_cast<u32x2*>(a.p16 + gpage * a.E);
+    PageSegs segs{};
+    bool edge = false;  // gather / scatter only: this slice is not wholly inside one tenant
+    if (GATHER || SCATTER) {
+        segs = a.segs[gpage];
+        const int k = (segs.n[1] > 0 && start >= segs.off[1]) ? 1 : 0;
+        const int rel = start - segs.off[k];
+        const int span = min(kUpdTile, used8 - start);
+        // Wholly inside tenant k (the common case): address the tensor like a page whose element 0
+        // sits at ptr - off[k]; the slice then runs the same code as the page-class path.
+        if (rel >= 0 && rel + span <= segs.n[k]) {
+            if (GATHER) G = reinterpret_cast<const u32x2*>(segs.g[k] - segs.off[k]);
+            if (SCATTER) P16 = reinterpret_cast<u32x2*>(segs.q[k] - segs.off[k]);
+        } else {
+            edge = true;
+        }
+    }
 
     const int nvec = used8 >> 2;
     const int v0 = (start >> 2) + (int)threadIdx.x;
@@ -273,7 +358,8 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     for (int u = 0; u < kUpdU; ++u) {
         const int vi = v0 + u * kUpdThreads;
         if (vi < nvec) {
-            g[u] = __builtin_nontemporal_load(G + vi);
+            if (GATHER && edge) g[u] = gather_g4(segs, vi << 2);
+            else g[u] = __builtin_nontemporal_load(G + vi);
             p[u] = __builtin_nontemporal_load(P + vi);
             m[u] = __builtin_nontemporal_load(M + vi);
             v[u] = __builtin_nontemporal_load(V + vi);
@@ -298,7 +384,8 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
             __builtin_nontemporal_store(p[u], P + vi);
             __builtin_nontemporal_store(m[u], M + vi);
             __builtin_nontemporal_store(v[u], V + vi);
-            __builtin_nontemporal_store(o, P16 + vi);
+            if (SCATTER && edge) scatter_q4(segs, vi << 2, o);
+            else __builtin_nontemporal_store(o, P16 + vi);
         }
     }
 }
@@ -308,11 +395,12 @@ constexpr int kMaxGridY = 65535;
 }  // namespace
 
 hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
-    ReduceArgs a{L.g16, L.used, L.grad_pages, L.grad_first, 0, L.E, L.partials, L.nzflags, L.S};
+    ReduceArgs a{L.g16, L.segs, L.used, L.grad_pages, L.grad_first, 0, L.E, L.partials, L.nzflags, L.S};
     for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
         const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
         a.list_offset = off;
-        hipLaunchKernelGGL(apm_grad_reduce_kernel, dim3((unsigned)L.S, (unsigned)ny), dim3(kThreads), 0, s, a);
+        if (L.gather) hipLaunchKernelGGL(apm_grad_reduce_kernel<true>, dim3((unsigned)L.S, (unsigned)ny), dim3(kThreads), 0, s, a);
+        else hipLaunchKernelGGL(apm_grad_reduce_kernel<false>, dim3((unsigned)L.S, (unsigned)ny), dim3(kThreads), 0, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -327,6 +415,7 @@ hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
 hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
     UpdateArgs a{};
     a.p32 = L.p32; a.m32 = L.m32; a.v32 = L.v32; a.g16 = L.g16; a.p16 = L.p16;
+    a.segs = L.segs;
     a.used = L.used; a.state_pages = L.state_pages; a.grad_pages = L.grad_pages;
     a.state_first = L.state_first; a.grad_first = L.grad_first; a.E = L.E;
     a.scale = L.partials ? L.scale : nullptr;
@@ -336,7 +425,11 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
     for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
         const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
         a.list_offset = off;
-        hipLaunchKernelGGL(apm_adamw_kernel, dim3(nx, (unsigned)ny), dim3(kUpdThreads), APM_UPDATE_LDS, s, a);
+        const dim3 grid(nx, (unsigned)ny), block(kUpdThreads);
+        if (L.gather && L.scatter) hipLaunchKernelGGL((apm_adamw_kernel<true, true>), grid, block, APM_UPDATE_LDS, s, a);
+        else if (L.gather) hipLaunchKernelGGL((apm_adamw_kernel<true, false>), grid, block, APM_UPDATE_LDS, s, a);
+        else if (L.scatter) hipLaunchKernelGGL((apm_adamw_kernel<false, true>), grid, block, APM_UPDATE_LDS, s, a);
+        else hipLaunchKernelGGL((apm_adamw_kernel<false, false>), grid, block, APM_UPDATE_LDS, s, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -62,6 +62,17 @@ struct StageRing {
 // ---- kernels ------------------------------------------------------------------------------
 constexpr int kReduceTile = 16384;  // gradient elements per workgroup of the reduce kernel
 
+// Per-page view of the tenant tensors, for kernels that read gradients from / write bf16
+// parameters to the caller's contiguous tensors directly instead of the G16 / P16 page classes.
+// Tenant k covers page elements [off[k], off[k]+n[k]); g[k] / q[k] point at the tensor element
+// that sits at off[k].  off[k] is a multiple of 8 and the pointers are 16-byte aligned.
+struct PageSegs {
+    int32_t off[2];
+    int32_t n[2];
+    const uint16_t* g[2];
+    uint16_t* q[2];
+};
+
 struct AdamwLaunch {
     float* p32;
     float* m32;
@@ -69,6 +80,9 @@ struct AdamwLaunch {
     const uint16_t* g16;
     uint16_t* p16;
     const int32_t* used;          // device, indexed by grad page id
+    const PageSegs* segs;         // device, indexed by grad page id; needed if gather or scatter
+    bool gather;                  // read g from the tenant tensors (segs[].g) instead of g16
+    bool scatter;                 // write p16 to the tenant tensors (segs[].q) instead of p16
     const int64_t* state_pages;   // device list or nullptr (then state_first + i)
     const int64_t* grad_pages;    // device list or nullptr (then grad_first + i)
     int64_t state_first;
@@ -144,7 +158,8 @@ namespace apm {
 // replaces the pool's G16 region as the gradient source.
 int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
                  const apm_hyper* hyper, const uint16_t* g16_override, float* grad_norm,
-                 uint8_t* skip_mask, hipStream_t stream);
+                 uint8_t* skip_mask, hipStream_t stream, const apm_tensor* grad_tensors = nullptr,
+                 const apm_tensor* p16_tensors = nullptr, int64_t n_tensors = 0);
 int ensure_scratch(apm_pool* pool);
 
 // Brackets one kernel launch with events when the pool's timing is on.

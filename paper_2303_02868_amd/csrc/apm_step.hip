@@ -29,14 +29,38 @@ int prepare_hyper(const apm_hyper* h, int64_t step, AdamwLaunch* a) {
     return APM_OK;
 }
 
+namespace {
+// Checks a bf16 tensor list against the installed layout for the gather / scatter kernels.
+int check_fused_list(const apm_pool* pool, const apm_tensor* t, int64_t n, const char* what) {
+    if (!pool->has_layout || (int64_t)pool->layout_numels.size() != n) return fail(APM_ESTATE, "%s list does not match the pool's installed layout", what);
+    for (int64_t i = 0; i < n; ++i) {
+        if (t[i].numel != pool->layout_numels[(size_t)i]) return fail(APM_ESTATE, "%s list does not match the pool's installed layout", what);
+        if (t[i].numel == 0) continue;
+        if (t[i].dtype != APM_BF16) return fail(APM_EINVAL, "%s tensor %lld is not bf16", what, (long long)i);
+        if (!t[i].data || (reinterpret_cast<uintptr_t>(t[i].data) & 15u)) return fail(APM_EINVAL, "%s tensor %lld: data must be a 16-byte aligned device pointer", what, (long long)i);
+    }
+    return APM_OK;
+}
+}  // namespace
+
 int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
                  const apm_hyper* hyper, const uint16_t* g16_override, float* grad_norm,
-                 uint8_t* skip_mask, hipStream_t stream) {
+                 uint8_t* skip_mask, hipStream_t stream, const apm_tensor* grad_tensors,
+                 const apm_tensor* p16_tensors, int64_t n_tensors) {
     if (!pool) return fail(APM_EINVAL, "NULL pool");
     if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the update runs on GPU pools only");
     for (int st = 0; st < APM_N_STATES; ++st) {
-        if (st == APM_G16 && g16_override) continue;
+        if (st == APM_G16 && (g16_override || grad_tensors)) continue;
+        if (st == APM_P16 && p16_tensors) continue;
         if (!pool->stores(st)) return fail(APM_ESTATE, "pool does not store state class %d", st);
+    }
+    if (grad_tensors) {
+        int rc0 = check_fused_list(pool, grad_tensors, n_tensors, "gradient");
+        if (rc0 != APM_OK) return rc0;
+    }
+    if (p16_tensors) {
+        int rc0 = check_fused_list(pool, p16_tensors, n_tensors, "bf16 parameter");
+        if (rc0 != APM_OK) return rc0;
     }
     if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
     AdamwLaunch L{};
@@ -67,6 +91,35 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
         d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
     }
 
+    if (grad_tensors || p16_tensors) {
+        const int64_t in_use = (int64_t)pool->plan.pages.size();
+        if (!pages && n_pages > in_use) return fail(APM_ERANGE, "page count %lld exceeds the %lld pages in use", (long long)n_pages, (long long)in_use);
+        if (pages)
+            for (int64_t k = 0; k < n_pages; ++k)
+                if (pages[k] >= in_use) return fail(APM_ERANGE, "pages[%lld] = %lld is not in use by the layout", (long long)k, (long long)pages[k]);
+        // One PageSegs entry per page in use, rebuilt per call: the tensors are caller-owned and
+        // their addresses may change from step to step.
+        const size_t n_in_use = pool->plan.pages.size();
+        int slot;
+        rc = pool->ring.acquire(n_in_use * sizeof(PageSegs), &slot);
+        if (rc != APM_OK) return rc;
+        PageSegs* h = static_cast<PageSegs*>(pool->ring.h[slot]);
+        for (size_t k = 0; k < n_in_use; ++k) h[k] = PageSegs{};
+        std::vector<uint8_t> filled(n_in_use, 0);
+        for (const apm_segment& sg : pool->plan.segs) {  // a page's tenants appear in offset order
+            PageSegs& e = h[(size_t)sg.page];
+            const int k = filled[(size_t)sg.page]++;
+            e.off[k] = (int32_t)sg.page_off;
+            e.n[k] = (int32_t)sg.n;
+            if (grad_tensors) e.g[k] = static_cast<const uint16_t*>(grad_tensors[sg.tensor].data) + sg.tensor_off;
+            if (p16_tensors) e.q[k] = static_cast<uint16_t*>(p16_tensors[sg.tensor].data) + sg.tensor_off;
+        }
+        rc = pool->ring.commit(slot, n_in_use * sizeof(PageSegs), stream);
+        if (rc != APM_OK) return rc;
+        L.segs = static_cast<const PageSegs*>(pool->ring.d[slot]);
+        L.gather = grad_tensors != nullptr;
+        L.scatter = p16_tensors != nullptr;
+    }
     L.p32 = static_cast<float*>(pool->base[APM_P32]);
     L.m32 = static_cast<float*>(pool->base[APM_M32]);
     L.v32 = static_cast<float*>(pool->base[APM_V32]);
@@ -145,6 +198,17 @@ extern "C" int apm_page_adamw_step(apm_pool* pool, const int64_t* pages, int64_t
                                    uint8_t* skip_mask, void* stream) {
     return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int apm_page_adamw_step_fused(apm_pool* pool, const int64_t* pages, int64_t n_pages,
+                                         int64_t step, const apm_hyper* hyper,
+                                         const apm_tensor* grad_tensors,
+                                         const apm_tensor* p16_tensors, int64_t n_tensors,
+                                         float* grad_norm, uint8_t* skip_mask, void* stream) {
+    if (!grad_tensors && !p16_tensors) return fail(APM_EINVAL, "neither a gradient nor a parameter tensor list was given");
+    if (n_tensors < 0) return fail(APM_EINVAL, "negative tensor count");
+    return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
+                        static_cast<hipStream_t>(stream), grad_tensors, p16_tensors, n_tensors);
 }
 
 extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages,

@@ -46,7 +46,8 @@ class Model:
 
     def __init__(self, specs: Sequence[synth.TensorSpec], E: int, seed: int = 0,
                  sigma_p: float = 0.02, sigma_g: float = 1e-3,
-                 active_fn: Optional[Callable[[int], np.ndarray]] = None, pad_elems: int = 0):
+                 active_fn: Optional[Callable[[int], np.ndarray]] = None, pad_elems: int = 0,
+                 align_elems: int = 1):
         self.specs = list(specs)
         self.numels = [t.numel for t in self.specs]
         self.E = E
@@ -54,9 +55,10 @@ class Model:
         self.active_fn = active_fn
         # pad_elems shifts every tensor by that many elements per preceding tensor, to produce
         # unaligned tensor pointers when wanted
+        # align_elems rounds every tensor start up to that many elements (8 = 16-byte aligned bf16)
         self.off = np.zeros(len(self.specs) + 1, dtype=np.int64)
         for i, n in enumerate(self.numels):
-            self.off[i + 1] = self.off[i] + n + pad_elems
+            self.off[i + 1] = -(-(self.off[i] + n + pad_elems) // align_elems) * align_elems
         self.total = int(self.off[-1])
         self.plan = oracle.plan_pack(self.numels, E)
         self.p_flat = gen_flat(seed, STREAM_P, self.total, sigma_p, bf16=False)

@@ -181,6 +181,72 @@ def test_edge_ragged_lists_page_lists_clip_and_skip():
     dp.destroy()
 
 
+@pytest.mark.parametrize("gather,scatter", [(True, True), (True, False), (False, True)])
+def test_fused_gather_scatter_is_bit_identical_to_pack_step_unpack(gather, scatter):
+    # gradients read straight from the tensors / bf16 parameters written straight to the tensors
+    E = 40960
+    numels = [E * 2 + 4097, 1, 7, E - 1, E, E + 1, 0, 3 * E + 12345, 255, 8193, 2 * E, 5 * E + 3]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    zero_grad = {3, 8}
+    act = lambda t: np.array([i not in zero_grad for i in range(len(numels))])
+    model = Model(specs, E, seed=6, sigma_g=2e-3, active_fn=act, align_elems=8)
+    n_t, n_pages = len(specs), model.plan.n_pages
+    hy = to_hyper(oracle.Hyper(max_grad_norm=0.3, skip_mode=1))
+    a = DevicePool(n_pages, E)
+    b = DevicePool(n_pages, E)
+    for dp in (a, b):
+        apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    q_a = torch.zeros(model.total, dtype=torch.bfloat16, device=DEV)
+    q_b = torch.full((model.total,), 7.0, dtype=torch.bfloat16, device=DEV)
+    q_a.fill_(7.0)
+    norm_a = torch.zeros(n_pages, device=DEV)
+    norm_b = torch.zeros(n_pages, device=DEV)
+    skip_a = torch.zeros(n_pages, dtype=torch.uint8, device=DEV)
+    skip_b = torch.zeros(n_pages, dtype=torch.uint8, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(a.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(a.pool, None, n_pages, t, hy, norm_a, skip_a)
+        apm.apm_unpack(a.pool, apm.APM_P16, model.tensors(q_a), n_t)
+        if not gather:
+            apm.apm_pack_tensors(b.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step_fused(b.pool, None, n_pages, t, hy,
+                                      model.tensors(g) if gather else None,
+                                      model.tensors(q_b) if scatter else None, n_t, norm_b, skip_b)
+        if not scatter:
+            apm.apm_unpack(b.pool, apm.APM_P16, model.tensors(q_b), n_t)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_a, norm_b) and torch.equal(skip_a, skip_b)
+        assert skip_a.sum().item() == 2
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        assert torch.equal(a.reg[s_].view(torch.int32), b.reg[s_].view(torch.int32)), f"state {s_}"
+    # never-updated tensors: the fused path leaves the caller's tensor alone (still 7.0), the
+    # unfused path copies the never-written P16 pages (zeros); everything else is identical
+    keep = torch.ones(model.total, dtype=torch.bool, device=DEV)
+    for i in zero_grad:
+        sl = slice(int(model.off[i]), int(model.off[i]) + numels[i])
+        keep[sl] = False
+        if scatter:
+            assert (q_b[sl] == 7.0).all()
+        assert (q_a[sl] == 0.0).all()
+    assert torch.equal(q_a.view(torch.int16)[keep], q_b.view(torch.int16)[keep])
+    if scatter:     # the P16 page class was never written
+        assert not b.reg[apm.APM_P16].view(torch.int16).any()
+    # misaligned tensors are refused, not mis-read
+    bad = model.grad_flat(1)
+    ptrs = [bad.data_ptr() + 2 * int(model.off[i]) + 2 for i in range(n_t)]
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_adamw_step_fused(b.pool, None, n_pages, 4, hy,
+                                      apm.make_tensors(numels, apm.APM_BF16, ptrs), None, n_t)
+    assert e.value.code == apm.APM_EINVAL
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_adamw_step_fused(b.pool, None, n_pages, 4, hy,
+                                      apm.make_tensors(numels[:-1], apm.APM_BF16, ptrs[:-1]), None, n_t - 1)
+    assert e.value.code == apm.APM_ESTATE
+    a.destroy()
+    b.destroy()
+
+
 def test_no_outputs_no_clip_path_matches_path_with_reduce():
     # without clip/skip/outputs the reduce pass is not launched; results must be identical
     E = 16384
