@@ -304,6 +304,17 @@ int apm_streamer_copy_only(apm_streamer* s, int directions, void* stream);
 int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
                      const apm_hyper* hyper, void* stream);
 
+/*
+ * Zero-copy hand-over for apm_step_delayed: returns the half of the ping-pong gradient buffer the
+ * next call will stage into (device pointer, n_pool_pages*E bf16 elements in page layout) and
+ * makes `stream` wait until the update that last read that half has finished.  A producer that
+ * writes its gradient there (on `stream`) and passes the same pointer as new_g16 skips the
+ * staging copy.  Both halves start zero-filled; the producer must leave the elements no tensor
+ * owns (alignment gaps, padding) zero.  The pointer is valid for exactly one apm_step_delayed
+ * call.  NULL on error.
+ */
+void* apm_delayed_grad_buffer(apm_pool* pool, void* stream);
+
 /* Number of updates apm_step_delayed has applied (enqueued) on this pool so far. */
 int64_t apm_delayed_applied(const apm_pool* pool);
 

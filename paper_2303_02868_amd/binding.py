@@ -30,7 +30,7 @@ EXPORTS = [
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
     "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_step_delayed",
-    "apm_delayed_applied", "apm_delayed_set_outputs", "apm_pool_set_timing", "apm_pool_read_timing",
+    "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
 
@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_copy_only.argtypes = [vp, i32, vp]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
+    L.apm_delayed_grad_buffer.argtypes = [vp, vp]
+    L.apm_delayed_grad_buffer.restype = vp
     L.apm_delayed_applied.argtypes = [vp]
     L.apm_delayed_applied.restype = i64
     L.apm_delayed_set_outputs.argtypes = [vp, vp, vp]
@@ -329,6 +331,13 @@ def apm_step_delayed(pool: Pool, pages: Optional[Sequence[int]], n_pages: int, n
     arr, _ = _i64_array(pages)
     _check(lib().apm_step_delayed(pool.handle, arr, n_pages, _ptr(new_g16), C.byref(hyper),
                                   _stream(stream)))
+
+
+def apm_delayed_grad_buffer(pool: Pool, stream=None) -> int:
+    p = lib().apm_delayed_grad_buffer(pool.handle, _stream(stream))
+    if not p:
+        raise ApmError(APM_EDEVICE, apm_last_error())
+    return p
 
 
 def apm_delayed_applied(pool: Pool) -> int:

@@ -166,6 +166,9 @@ int ensure_delayed(apm_pool* pool) {
             return fail(APM_ENOMEM, "allocating the %zu-byte buffered-gradient halves failed: %s", bytes, hipGetErrorString(e));
         }
     }
+    // Zero once: a producer that fills a half in place writes its tensors' elements only, and the
+    // alignment gaps inside a page's used extent are read as gradient.
+    for (int k = 0; k < 2; ++k) APM_HIP(hipMemset(pool->gbuf[k], 0, bytes));
     for (int k = 0; k < 2; ++k) {
         APM_HIP(hipEventCreateWithFlags(&pool->ev_staged[k], hipEventDisableTiming));
         APM_HIP(hipEventCreateWithFlags(&pool->ev_applied[k], hipEventDisableTiming));
@@ -240,11 +243,14 @@ extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_
     // Stage the new gradient into the other half; that half was last read by the update enqueued
     // two calls ago, which must have finished before it is overwritten.
     const int nxt = pool->cur ^ 1;
-    if (pool->applied_valid[nxt]) APM_HIP(hipStreamWaitEvent(s, pool->ev_applied[nxt], 0));
     const size_t pb = (size_t)pool->desc.page_elems * 2u;
     const char* src = static_cast<const char*>(new_g16);
     char* dst = reinterpret_cast<char*>(pool->gbuf[nxt]);
-    int64_t k = 0;
+    // A producer that wrote its gradient straight into the half handed out by
+    // apm_delayed_grad_buffer has already staged it (and waited for the half to be free there).
+    const bool in_place = src == dst;
+    if (!in_place && pool->applied_valid[nxt]) APM_HIP(hipStreamWaitEvent(s, pool->ev_applied[nxt], 0));
+    int64_t k = in_place ? n_pages : 0;
     while (k < n_pages) {  // one copy per run of consecutive pages
         const int64_t p0 = pages ? pages[k] : k;
         int64_t len = 1;
@@ -256,6 +262,21 @@ extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_
     pool->cur = nxt;
     pool->buffered = true;
     return APM_OK;
+}
+
+extern "C" void* apm_delayed_grad_buffer(apm_pool* pool, void* stream) {
+    if (!pool || pool->desc.device != APM_DEV_GPU) {
+        fail(APM_EINVAL, "NULL or non-GPU pool");
+        return nullptr;
+    }
+    if (hipSetDevice(pool->desc.hip_device) != hipSuccess || ensure_delayed(pool) != APM_OK) return nullptr;
+    const int nxt = pool->cur ^ 1;
+    if (pool->applied_valid[nxt] &&
+        hipStreamWaitEvent(static_cast<hipStream_t>(stream), pool->ev_applied[nxt], 0) != hipSuccess) {
+        fail(APM_EDEVICE, "hipStreamWaitEvent failed");
+        return nullptr;
+    }
+    return pool->gbuf[nxt];
 }
 
 extern "C" int64_t apm_delayed_applied(const apm_pool* pool) { return pool ? pool->applied : 0; }

@@ -158,6 +158,44 @@ def test_delayed_small_with_page_list_and_outputs():
     dp.destroy()
 
 
+def test_delayed_zero_copy_handover_equals_sync():
+    # the producer writes its gradient pages straight into the half handed out by
+    # apm_delayed_grad_buffer (here: by packing into a pool whose G16 class aliases that half)
+    E = 16384
+    numels = [3 * E + 5, 100, 2 * E, 9000, E]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=10, sigma_g=5e-3)
+    n, n_t = model.plan.n_pages, len(specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=0.5))
+    a = DevicePool(n, E)
+    b = DevicePool(n, E, states=(apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16))
+    for dp in (a, b):
+        apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    halves = {}
+    for t in range(1, 6):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(a.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(a.pool, None, n, t, hy)
+        ptr = apm.apm_delayed_grad_buffer(b.pool)
+        if ptr not in halves:
+            # NO_ZERO: the library hands the halves out zero-filled, and pack leaves gaps alone
+            halves[ptr] = apm.apm_pool_create(apm.APM_DEV_GPU, E, n, state_mask=1 << apm.APM_G16,
+                                              flags=apm.APM_POOL_NO_ZERO, base={apm.APM_G16: ptr})
+        apm.apm_pack_tensors(halves[ptr], apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_step_delayed(b.pool, None, n, ptr, hy)
+        torch.cuda.synchronize()
+    assert len(halves) == 2
+    apm.apm_step_delayed(b.pool, None, n, None, hy)
+    torch.cuda.synchronize()
+    assert apm.apm_delayed_applied(b.pool) == 5
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16):
+        assert torch.equal(a.reg[s_].view(torch.int16), b.reg[s_].view(torch.int16)), f"state {s_}"
+    for h in halves.values():
+        h.destroy()
+    a.destroy()
+    b.destroy()
+
+
 def test_edge_ragged_lists_page_lists_clip_and_skip():
     # small pages so that tensors span several tiles with ragged tails; odd numels so that tensor
     # pointers are not 16-byte aligned; zero-size tensors; exact-page tensors
