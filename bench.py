@@ -165,6 +165,54 @@ def resident_leg(args, wl, pool, hyper, n_pages, fused, steps, warmup, first_ste
             "upd_ms": upd_ms, "next_step": t_step}
 
 
+def delayed_leg(args, wl, pool, hyper, n_pages, first_step):
+    """Synchronous vs one-step-stale stepping with the same producer (packing the step's gradient
+    tensors into page layout): wall time of `steps` steps each.  Both are HBM-bound here, so the
+    overlap the delayed form allows cannot shorten the run; it shows that decoupling costs nothing."""
+    import torch
+    import paper_2303_02868_amd as apm
+    import synth
+    moe = wl.name == "moe_8x64"
+    grads = [wl.gen(1001 + k, True, 1e-3, synth.moe_active_tensors(wl.specs, k + 1, 0, 64, 8) if moe else None)
+             for k in range(2)]
+    g_tensors = [wl.tensors(g) for g in grads]
+    stream = torch.cuda.current_stream()
+    steps = max(4, args.steps // 2)
+    t = first_step
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        apm.apm_pack_tensors(pool, apm.APM_G16, g_tensors[k & 1], wl.n_t, stream)
+        apm.apm_page_adamw_step(pool, None, n_pages, t, hyper, None, None, stream)
+        t += 1
+    torch.cuda.synchronize()
+    t_sync = (time.perf_counter() - t0) / steps
+
+    halves = {}
+    def produce(k):
+        ptr = apm.apm_delayed_grad_buffer(pool, stream)
+        if ptr not in halves:
+            halves[ptr] = apm.apm_pool_create(apm.APM_DEV_GPU, wl.E, n_pages, state_mask=1 << apm.APM_G16,
+                                              flags=apm.APM_POOL_NO_ZERO, base={apm.APM_G16: ptr})
+        apm.apm_pack_tensors(halves[ptr], apm.APM_G16, g_tensors[k & 1], wl.n_t, stream)
+        return ptr
+    for k in range(2):      # create both alias pools and warm up
+        apm.apm_step_delayed(pool, None, n_pages, produce(k), hyper, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        apm.apm_step_delayed(pool, None, n_pages, produce(k), hyper, stream)
+    apm.apm_step_delayed(pool, None, n_pages, None, hyper, stream)      # flush
+    torch.cuda.synchronize()
+    t_del = (time.perf_counter() - t0) / steps
+    for h in halves.values():
+        h.destroy()
+    return {"steps": steps, "sync_ms_per_step": t_sync * 1e3, "delayed_ms_per_step": t_del * 1e3,
+            "producer": "apm_pack_tensors of the step's bf16 gradient tensors into page layout",
+            "applied_updates": apm.apm_delayed_applied(pool)}
+
+
 def d2d_copy_ceiling():
     import torch
     n_copy = 1 << 29
@@ -371,6 +419,8 @@ def main():
                            "avg_launch_ms": r["upd_ms"]}
         out["kernels"] = r["kernels"]
         out["d2d_copy_GBps"] = d2d_copy_ceiling()
+        if args.workload == "moe_8x64" and not args.update_only:
+            out["delayed"] = delayed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
         if not args.no_streamed:
             apm.apm_pack_tensors(pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
             out["streamed"] = streamed_leg(args, wl, pool, hyper, n_pages, r["next_step"])

@@ -279,6 +279,15 @@ int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, flo
                       uint8_t* skip_mask, void* stream);
 
 /*
+ * Mixed residency (the GPU cache of optimizer states, Sec. 4.2): pages [0, n_resident) keep their
+ * fp32 classes in `cache` (a GPU pool storing P32, M32, V32, same page size; its page k is model
+ * page k) and are updated in place; only pages [n_resident, N) are streamed from the host pool.
+ * Moving a page between the tiers is the caller's apm_page_copy_async between `cache` and the
+ * host pool, done between steps.  cache == NULL or n_resident == 0 switches the cache off.
+ */
+int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident);
+
+/*
  * Measurement aid: the same pipeline (streams, events, copy sizes, slot reuse) with the kernels
  * left out.  directions: 1 = copy-in only, 2 = copy-out only, 3 = both.  The data make a round
  * trip host -> staging -> host, so the host pool's contents are unchanged (with 2 alone, staging

@@ -3,6 +3,10 @@
 // so that the three overlap (Sec. 4.2: overlap movement with computation; Sec. 5 "Allocator":
 // asynchronous page copies; the update is page-granular by Sec. 4.3's last paragraph).
 //
+// Mixed residency (Sec. 4.2, the GPU cache of optimizer states): the first R pages may keep their
+// fp32 classes in a GPU pool; they are updated in place, in chunks interleaved with the streamed
+// batches on the compute stream, and only pages [R, N) cross PCIe.
+//
 // Slot life cycle for batch b (slot = b mod n_slots):
 //   copy-in : wait D2H(b - n_slots) -> H2D p,m,v           -> record h2d[slot]
 //   compute : wait h2d[slot]        -> reduce + update      -> record cmp[slot]
@@ -13,6 +17,8 @@
 struct apm_streamer {
     apm_pool* host = nullptr;
     apm_pool* dev = nullptr;
+    apm_pool* cache = nullptr;  // optional GPU pool holding the fp32 classes of pages [0, R)
+    int64_t R = 0;              // number of leading pages whose fp32 state is HBM-resident
     int64_t B = 0;
     int n_slots = 0;
     float* stage[3] = {nullptr, nullptr, nullptr};  // each n_slots * B * E floats
@@ -130,10 +136,36 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         L.scale = dev->d_scale;
     }
     const int states[3] = {APM_P32, APM_M32, APM_V32};
-    const int64_t n_batches = (N + s->B - 1) / s->B;
+    const int64_t R = s->cache ? (s->R < N ? s->R : N) : 0;
+    const int64_t n_batches = (N - R + s->B - 1) / s->B;
+    // resident pages are updated in n_batches chunks (one chunk if nothing is streamed)
+    const int64_t chunk = n_batches > 0 ? (R + n_batches - 1) / n_batches : R;
+    int64_t r_done = 0;
+    auto resident_chunk = [&]() -> int {
+        if (!(what & kDoUpdate) || r_done >= R) return APM_OK;
+        const int64_t nr = R - r_done < chunk ? R - r_done : chunk;
+        AdamwLaunch C = L;
+        C.p32 = static_cast<float*>(s->cache->base[APM_P32]);
+        C.m32 = static_cast<float*>(s->cache->base[APM_M32]);
+        C.v32 = static_cast<float*>(s->cache->base[APM_V32]);
+        C.state_first = C.grad_first = r_done;
+        C.n_listed = nr;
+        C.grad_norm = grad_norm ? grad_norm + r_done : nullptr;
+        C.skip_mask = skip_mask ? skip_mask + r_done : nullptr;
+        if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
+        APM_HIP(launch_adamw(C, s->s_cmp));
+        r_done += nr;
+        return APM_OK;
+    };
+    if (n_batches == 0) {
+        rc = resident_chunk();
+        if (rc != APM_OK) return rc;
+        APM_HIP(hipEventRecord(s->ev_cmp[0], s->s_cmp));
+        APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_cmp[0], 0));
+    }
     for (int64_t b = 0; b < n_batches; ++b) {
         const size_t slot = (size_t)(b % s->n_slots);
-        const int64_t first = b * s->B;
+        const int64_t first = R + b * s->B;
         const int64_t nb = N - first < s->B ? N - first : s->B;
         const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
         if (b >= s->n_slots) APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_d2h[slot], 0));
@@ -143,6 +175,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         }
         APM_HIP(hipEventRecord(s->ev_h2d[slot], s->s_in));
 
+        rc = resident_chunk();  // runs while this batch's copy-in is in flight
+        if (rc != APM_OK) return rc;
         APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_h2d[slot], 0));
         L.state_first = (int64_t)slot * s->B;
         L.grad_first = first;
@@ -172,6 +206,22 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
                                  float* grad_norm, uint8_t* skip_mask, void* stream) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+}
+
+extern "C" int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    if (!cache || n_resident == 0) {
+        s->cache = nullptr;
+        s->R = 0;
+        return APM_OK;
+    }
+    if (cache->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the cache must be a GPU pool");
+    for (int st : {APM_P32, APM_M32, APM_V32}) if (!cache->stores(st)) return fail(APM_ESTATE, "cache pool lacks fp32 class %d", st);
+    if (cache->desc.page_elems != s->dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
+    if (n_resident < 0 || n_resident > cache->desc.n_pages) return fail(APM_ERANGE, "n_resident %lld exceeds the cache pool's %lld pages", (long long)n_resident, (long long)cache->desc.n_pages);
+    s->cache = cache;
+    s->R = n_resident;
+    return APM_OK;
 }
 
 extern "C" int apm_streamer_copy_only(apm_streamer* s, int directions, void* stream) {

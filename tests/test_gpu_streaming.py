@@ -86,6 +86,53 @@ def test_streamed_equals_resident_bit_exact(batch, slots, clip):
     res.destroy()
 
 
+@pytest.mark.parametrize("frac", [0.0, 0.35, 1.0])
+def test_mixed_residency_equals_resident_bit_exact(frac):
+    # the first R pages keep their fp32 state in an HBM cache pool, the rest is streamed
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=2)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    R = int(round(frac * n_pages))
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    cache = DevicePool(max(R, 1), E, states=(apm.APM_P32, apm.APM_M32, apm.APM_V32))
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    if R:
+        apm.apm_page_copy_async(cache.pool, 0, res.pool, 0, R, apm.APM_P32)
+        # the host copy of the cached pages is stale from now on: poison it to prove it is unused
+        hv = host_view(host, apm.APM_P32, n_pages, E)
+        torch.cuda.synchronize()
+        hv[:R] = np.nan
+    st = apm.apm_streamer_create(host, dev.pool, 16, 3)
+    apm.apm_streamer_set_cache(st, cache.pool if R else None, R)
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, None)
+        apm.apm_streamer_step(st, t, hy, norm_s, None)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s)
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        want = res.reg[s_].cpu().numpy().view(np.uint32)
+        if R:
+            assert np.array_equal(cache.reg[s_][:R].cpu().numpy().view(np.uint32), want[:R]), f"cached state {s_}"
+        hv = host_view(host, s_, n_pages, E)
+        assert np.array_equal(hv[R:].view(np.uint32), want[R:]), f"streamed state {s_}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    st.destroy()
+    host.destroy()
+    cache.destroy()
+    dev.destroy()
+    res.destroy()
+
+
 def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
     # GPT-13B-shaped layers (d = 5120, ffn = 20480); fp32 state only ever lives in pinned host pages.
     # The box decides how much can be pinned: the layer count shrinks until the host pool fits (the
