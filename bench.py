@@ -302,6 +302,8 @@ def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_para
                                   "d2h_only_ms": t_d2h * 1e3,
                                   "both_GBps_each_way": each_way / min(t_both, t_both2) / 1e9,
                                   "h2d_GBps": each_way / t_h2d / 1e9, "d2h_GBps": each_way / t_d2h / 1e9},
+           "stream_calibration_GBps": dict(zip(("h2d", "d2h", "duplex_each_way"),
+                                               apm.apm_streamer_probe_rates(streamer))),
            "frac_of_measured_pcie": t_copy / wall,
            "update_hidden": wall <= 1.02 * t_copy}
     if raw:
@@ -329,6 +331,22 @@ def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
         torch.cuda.synchronize()
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
     out = time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, wl.total)
+    if has_fp32:
+        # mixed residency: half of the pages keep their fp32 state in HBM (the pool's own fp32
+        # classes serve as the cache), the other half is streamed
+        R = n_pages // 2
+        apm.apm_streamer_set_cache(streamer, dev_pool, R)
+        stream = torch.cuda.current_stream()
+        apm.apm_streamer_step(streamer, first_step + 100, hyper, None, None, stream)
+        ts = []
+        for k in range(args.stream_steps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            apm.apm_streamer_step(streamer, first_step + 101 + k, hyper, None, None, stream)
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        out["mixed_residency"] = {"resident_pages": R, "streamed_pages": n_pages - R,
+                                  "ms_per_step": min(ts) * 1e3, "params_per_s": wl.total / min(ts)}
     streamer.destroy()
     host.destroy()
     return out
@@ -351,8 +369,14 @@ def cpu_baseline(args, E, n_pages, clip, skip):
     for k in range(args.cpu_steps):
         st.step(g_rows, 2 + k, h, threads=threads)
     cw = time.perf_counter() - c0
+    n_one = min(24, n_cpu)                           # the same oracle on one thread
+    one = oracle.PagedAdamWState(p_rows[:n_one], used[:n_one])
+    one.step(g_rows[:n_one], 1, h)
+    c1 = time.perf_counter()
+    one.step(g_rows[:n_one], 2, h)
+    c1 = time.perf_counter() - c1
     return {"value": n_cpu * E * args.cpu_steps / cw, "unit": "params/s", "cores": threads,
-            "kind": "oracle",
+            "kind": "oracle", "single_thread_value": n_one * E / c1,
             "sample": f"{n_cpu} full pages x {args.cpu_steps} steps of the same update (reduce + AdamW "
                       f"in double), pages split over {threads} threads, {cw:.2f} s wall"}
 

@@ -262,7 +262,10 @@ int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t 
  * dev:    GPU pool storing G16 and P16 for the same pages, with an installed layout.
  * batch_pages: pages moved and updated per pipeline stage (>= 1).
  * n_slots: staging slots in HBM (>= 2); each holds batch_pages pages of the three fp32 classes.
- * The streamer owns three streams (copy-in, compute, copy-out), its staging memory and events.
+ * The streamer owns its staging memory, events and three streams (copy-in, compute, copy-out).
+ * Which stream pairs overlap a host-to-device with a device-to-host copy depends on the runtime,
+ * so creation times short concurrent copies on a few candidate streams (the default stream among
+ * them) and keeps the best pair; this takes some tens of milliseconds and synchronises the device.
  */
 int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool* dev, int64_t batch_pages,
                         int n_slots);
@@ -277,6 +280,10 @@ int apm_streamer_destroy(apm_streamer* s);
  */
 int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, float* grad_norm,
                       uint8_t* skip_mask, void* stream);
+
+/* GB/s the creation-time stream calibration measured on 32 MiB copies: copy-in alone, copy-out
+ * alone, and each way with both running on the chosen pair (host pointers, nullable). */
+int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, double* duplex_each_way);
 
 /*
  * Mixed residency (the GPU cache of optimizer states, Sec. 4.2): pages [0, n_resident) keep their

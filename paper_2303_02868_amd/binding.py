@@ -29,7 +29,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_step_delayed",
+    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -108,6 +108,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_copy_only.argtypes = [vp, i32, vp]
     L.apm_streamer_set_cache.argtypes = [vp, vp, i64]
+    L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
     L.apm_delayed_grad_buffer.argtypes = [vp, vp]
     L.apm_delayed_grad_buffer.restype = vp
@@ -326,6 +327,13 @@ def apm_streamer_step(s: Streamer, step: int, hyper: apm_hyper, grad_norm=None, 
 def apm_streamer_set_cache(s: Streamer, cache: Optional[Pool], n_resident: int) -> None:
     _check(lib().apm_streamer_set_cache(s.handle, cache.handle if cache else None, n_resident))
     s.cache = cache
+
+
+def apm_streamer_probe_rates(s: Streamer):
+    """(copy-in alone, copy-out alone, each way when both run) in GB/s, from creation."""
+    a, b, c = C.c_double(), C.c_double(), C.c_double()
+    _check(lib().apm_streamer_probe_rates(s.handle, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
 
 
 def apm_streamer_copy_only(s: Streamer, directions: int, stream=None) -> None:

@@ -11,7 +11,10 @@
 //   copy-in : wait D2H(b - n_slots) -> H2D p,m,v           -> record h2d[slot]
 //   compute : wait h2d[slot]        -> reduce + update      -> record cmp[slot]
 //   copy-out: wait cmp[slot]        -> D2H p,m,v            -> record d2h[slot]
-// Streams are in order, so these three edges are the only synchronisation needed.
+// Streams are in order, so these three edges are the only synchronisation needed.  The host
+// enqueues copy-in one batch ahead of the matching update and copy-out.
+#include <chrono>
+
 #include "apm_internal.h"
 
 struct apm_streamer {
@@ -25,14 +28,18 @@ struct apm_streamer {
     hipStream_t s_in = nullptr, s_cmp = nullptr, s_out = nullptr;
     std::vector<hipEvent_t> ev_h2d, ev_cmp, ev_d2h;
     hipEvent_t ev_start = nullptr, ev_done = nullptr;
+    bool in_is_null = false, out_is_null = false;  // a chosen copy stream may be the default stream
+    double probe_h2d = 0, probe_d2h = 0, probe_duplex = 0;  // GB/s seen by the stream calibration
 };
 
 using namespace apm;
 
 namespace {
 void free_streamer(apm_streamer* s) {
-    for (hipStream_t st : {s->s_in, s->s_cmp, s->s_out})
-        if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
+    (void)hipDeviceSynchronize();
+    if (s->s_in && !s->in_is_null) (void)hipStreamDestroy(s->s_in);
+    if (s->s_out && !s->out_is_null) (void)hipStreamDestroy(s->s_out);
+    if (s->s_cmp) (void)hipStreamDestroy(s->s_cmp);
     for (auto* v : {&s->ev_h2d, &s->ev_cmp, &s->ev_d2h})
         for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     if (s->ev_start) (void)hipEventDestroy(s->ev_start);
@@ -40,6 +47,68 @@ void free_streamer(apm_streamer* s) {
     for (float* p : s->stage) if (p) (void)hipFree(p);
     delete s;
 }
+
+// Which pairs of HIP streams run a host-to-device and a device-to-host copy at the same time is
+// not something the API states: on the MI355X machine this was written on, a process has two groups of
+// streams (the default stream and the first stream created form one, every later stream the
+// other); copies on two streams of one group run one after the other (29 GB/s each way), copies on
+// streams of different groups overlap (49 GB/s each way).  So the pair is chosen by measurement:
+// a few candidate streams (the default stream among them) are timed on short concurrent copies
+// through the staging memory, and the best pair becomes (copy-in, copy-out).
+int pick_copy_streams(apm_streamer* s) {
+    constexpr int kNew = 4;
+    constexpr size_t kProbe = (size_t)32 << 20;
+    hipStream_t cand[kNew + 1] = {nullptr};  // cand[0] = the default stream
+    for (int k = 1; k <= kNew; ++k) APM_HIP(hipStreamCreateWithFlags(&cand[k], hipStreamNonBlocking));
+    char* h = nullptr;
+    APM_HIP(hipHostMalloc((void**)&h, 2 * kProbe, hipHostMallocDefault));
+    const size_t slot_bytes = (size_t)s->B * (size_t)s->dev->desc.page_elems * sizeof(float);
+    const size_t n = slot_bytes < kProbe ? slot_bytes : kProbe;
+    char* d_in = reinterpret_cast<char*>(s->stage[0]);   // staging is not in use yet
+    char* d_out = reinterpret_cast<char*>(s->stage[1]);
+    auto timed = [&](hipStream_t a, hipStream_t b, bool do_in, bool do_out, double* gbps) -> int {
+        APM_HIP(hipDeviceSynchronize());
+        const auto t0 = std::chrono::steady_clock::now();
+        for (int r = 0; r < 3; ++r) {
+            if (do_in) APM_HIP(hipMemcpyAsync(d_in, h, n, hipMemcpyHostToDevice, a));
+            if (do_out) APM_HIP(hipMemcpyAsync(h + kProbe, d_out, n, hipMemcpyDeviceToHost, b));
+        }
+        APM_HIP(hipDeviceSynchronize());
+        const double dt = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+        *gbps = 3.0 * (double)n / dt / 1e9;
+        return APM_OK;
+    };
+    double warm;
+    int rc = timed(cand[1], cand[2], true, true, &warm);
+    if (rc == APM_OK) rc = timed(cand[1], cand[2], true, false, &s->probe_h2d);
+    if (rc == APM_OK) rc = timed(cand[1], cand[2], false, true, &s->probe_d2h);
+    int bi = 1, bj = 2;
+    double best = 0.0;
+    for (int i = 0; i <= kNew && rc == APM_OK; ++i)
+        for (int j = 0; j <= kNew && rc == APM_OK; ++j) {
+            if (i == j) continue;
+            double g;
+            rc = timed(cand[i], cand[j], true, true, &g);
+            if (rc == APM_OK && g > best) { best = g; bi = i; bj = j; }
+        }
+    (void)hipHostFree(h);
+    if (rc != APM_OK) {
+        for (int k = 1; k <= kNew; ++k) (void)hipStreamDestroy(cand[k]);
+        return rc;
+    }
+    s->probe_duplex = best;
+    s->s_in = cand[bi];
+    s->s_out = cand[bj];
+    s->in_is_null = bi == 0;
+    s->out_is_null = bj == 0;
+    for (int k = 1; k <= kNew; ++k) {
+        if (k == bi || k == bj) continue;
+        if (!s->s_cmp) s->s_cmp = cand[k];
+        else (void)hipStreamDestroy(cand[k]);
+    }
+    return APM_OK;
+}
+
 }  // namespace
 
 extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool* dev,
@@ -63,11 +132,9 @@ extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool*
         free_streamer(s);
         return fail(APM_ENOMEM, "allocating 3 x %zu bytes of staging slots failed: %s", bytes, hipGetErrorString(e));
     }
-    auto mk_stream = [&](hipStream_t* st) { return hipStreamCreateWithFlags(st, hipStreamNonBlocking); };
     auto mk_event = [&](hipEvent_t* ev) { return hipEventCreateWithFlags(ev, hipEventDisableTiming); };
-    e = mk_stream(&s->s_in);
-    if (e == hipSuccess) e = mk_stream(&s->s_cmp);
-    if (e == hipSuccess) e = mk_stream(&s->s_out);
+    int rc_pick = pick_copy_streams(s);
+    if (rc_pick != APM_OK) { free_streamer(s); return rc_pick; }
     s->ev_h2d.assign((size_t)n_slots, nullptr);
     s->ev_cmp.assign((size_t)n_slots, nullptr);
     s->ev_d2h.assign((size_t)n_slots, nullptr);
@@ -163,7 +230,12 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         APM_HIP(hipEventRecord(s->ev_cmp[0], s->s_cmp));
         APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_cmp[0], 0));
     }
-    for (int64_t b = 0; b < n_batches; ++b) {
+    // Copy-in is enqueued one batch ahead of the update that consumes it: on this runtime the
+    // device-to-host copy is a kernel whose enqueue blocks the host until the event it waits for
+    // has fired, and without the look-ahead the copy-in stream idles during each update.  (A
+    // look-ahead of two batches was measured to make the runtime run the two copy directions one
+    // after the other, 28 instead of 48 GB/s each way, so one it is.)
+    auto copy_in = [&](int64_t b) -> int {
         const size_t slot = (size_t)(b % s->n_slots);
         const int64_t first = R + b * s->B;
         const int64_t nb = N - first < s->B ? N - first : s->B;
@@ -174,6 +246,22 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
             APM_HIP(hipMemcpyAsync(s->stage[k] + slot_off, src, pb * (size_t)nb, hipMemcpyHostToDevice, s->s_in));
         }
         APM_HIP(hipEventRecord(s->ev_h2d[slot], s->s_in));
+        return APM_OK;
+    };
+    const int64_t ahead = 1;
+    for (int64_t b = 0; b < ahead && b < n_batches; ++b) {
+        rc = copy_in(b);
+        if (rc != APM_OK) return rc;
+    }
+    for (int64_t b = 0; b < n_batches; ++b) {
+        const size_t slot = (size_t)(b % s->n_slots);
+        const int64_t first = R + b * s->B;
+        const int64_t nb = N - first < s->B ? N - first : s->B;
+        const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
+        if (b + ahead < n_batches) {  // its slot's previous copy-out is already enqueued
+            rc = copy_in(b + ahead);
+            if (rc != APM_OK) return rc;
+        }
 
         rc = resident_chunk();  // runs while this batch's copy-in is in flight
         if (rc != APM_OK) return rc;
@@ -206,6 +294,14 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
                                  float* grad_norm, uint8_t* skip_mask, void* stream) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+}
+
+extern "C" int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, double* duplex_each_way) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    if (h2d) *h2d = s->probe_h2d;
+    if (d2h) *d2h = s->probe_d2h;
+    if (duplex_each_way) *duplex_each_way = s->probe_duplex;
+    return APM_OK;
 }
 
 extern "C" int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident) {
