@@ -321,6 +321,17 @@ int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages, cons
                      const apm_hyper* hyper, void* stream);
 
 /*
+ * Adds one more gradient into the gradient buffered by the last apm_step_delayed call, before the
+ * next call applies it (Alg. 2, buffering thread: g'16 <- g'16 + g16): element-wise
+ * bf16_rne(fp32(g') + fp32(g)), the fp32 sum rounded to nearest, over the used extents of the
+ * listed pages.  g16: device pointer, page layout, as new_g16 of apm_step_delayed.  Asynchronous
+ * on `stream`; the caller may reuse g16 once `stream` has passed this point.
+ * Errors: APM_ESTATE if no gradient is buffered; APM_EINVAL, APM_ERANGE.
+ */
+int apm_delayed_accumulate(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* g16,
+                           void* stream);
+
+/*
  * Zero-copy hand-over for apm_step_delayed: returns the half of the ping-pong gradient buffer the
  * next call will stage into (device pointer, n_pool_pages*E bf16 elements in page layout) and
  * makes `stream` wait until the update that last read that half has finished.  A producer that

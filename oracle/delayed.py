@@ -30,3 +30,15 @@ class DelayedStepper:
             out = self.state.step(self.buffered, self.applied, h, pages)
         self.buffered = None if new_g16_pages is None else new_g16_pages.copy()
         return out
+
+    def accumulate(self, g16_pages: np.ndarray) -> None:
+        """Buffering actor of Alg. 2: g' <- g' + g in 16-bit.  The sum of the two bf16 values is
+        formed in fp32 (round to nearest) and rounded to bf16 (nearest even)."""
+        if self.buffered is None:
+            raise RuntimeError("no gradient is being collected")
+        from .adamw import bf16_rne
+        a = (self.buffered.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        b = (g16_pages.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        with np.errstate(over="ignore", invalid="ignore"):
+            s = (a + b).astype(np.float32)
+        self.buffered = bf16_rne(s.view(np.uint32)).reshape(self.buffered.shape)

@@ -30,7 +30,7 @@ EXPORTS = [
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
     "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_probe_rates", "apm_step_delayed",
-    "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_pool_set_timing", "apm_pool_read_timing",
+    "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
 
@@ -110,6 +110,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_set_cache.argtypes = [vp, vp, i64]
     L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
+    L.apm_delayed_accumulate.argtypes = [vp, P(i64), i64, vp, vp]
     L.apm_delayed_grad_buffer.argtypes = [vp, vp]
     L.apm_delayed_grad_buffer.restype = vp
     L.apm_delayed_applied.argtypes = [vp]
@@ -345,6 +346,11 @@ def apm_step_delayed(pool: Pool, pages: Optional[Sequence[int]], n_pages: int, n
     arr, _ = _i64_array(pages)
     _check(lib().apm_step_delayed(pool.handle, arr, n_pages, _ptr(new_g16), C.byref(hyper),
                                   _stream(stream)))
+
+
+def apm_delayed_accumulate(pool: Pool, pages: Optional[Sequence[int]], n_pages: int, g16, stream=None) -> None:
+    arr, _ = _i64_array(pages)
+    _check(lib().apm_delayed_accumulate(pool.handle, arr, n_pages, _ptr(g16), _stream(stream)))
 
 
 def apm_delayed_grad_buffer(pool: Pool, stream=None) -> int:

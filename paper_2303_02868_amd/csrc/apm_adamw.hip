@@ -402,9 +402,74 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     }
 }
 
+struct AccumArgs {
+    uint16_t* acc;        // buffered gradient g' (page layout)
+    const uint16_t* g16;  // incoming gradient (page layout)
+    const int32_t* used;
+    const int64_t* pages;
+    int64_t first;
+    int64_t list_offset;
+    int64_t E;
+};
+
+// g' <- bf16_rne(fp32(g') + fp32(g)) over the used extent of each listed page (Alg. 2, buffering
+// thread: "accumulate buffered gradients").  6 B/element, HBM-bound; same slicing as the reduce.
+__global__ __launch_bounds__(kThreads) void apm_grad_accum_kernel(AccumArgs a) {
+    const int64_t i = a.list_offset + blockIdx.y;
+    const int64_t page = a.pages ? a.pages[i] : a.first + i;
+    const int used8 = (a.used[page] + 7) & ~7;
+    const int start = blockIdx.x * kReduceTile;
+    if (start >= used8) return;
+    const int end = min(start + kReduceTile, used8);
+    u32x4* acc = reinterpret_cast<u32x4*>(a.acc + page * a.E);
+    const u32x4* g = reinterpret_cast<const u32x4*>(a.g16 + page * a.E);
+    constexpr int U = 4;
+#pragma unroll 1
+    for (int e0 = start + (int)threadIdx.x * 8; e0 - (int)threadIdx.x * 8 < end; e0 += kThreads * 8 * U) {
+        u32x4 x[U], y[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * (kThreads * 8);
+            if (e < end) {
+                x[u] = __builtin_nontemporal_load(acc + (e >> 3));
+                y[u] = __builtin_nontemporal_load(g + (e >> 3));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * (kThreads * 8);
+            if (e < end) {
+                u32x4 o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float lo = bf16lo(x[u][j]) + bf16lo(y[u][j]);
+                    const float hi = bf16hi(x[u][j]) + bf16hi(y[u][j]);
+                    o[j] = f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+                }
+                __builtin_nontemporal_store(o, acc + (e >> 3));
+            }
+        }
+    }
+}
+
 constexpr int kMaxGridY = 65535;
 
 }  // namespace
+
+hipError_t launch_grad_accum(uint16_t* acc, const uint16_t* g16, const int32_t* used,
+                             const int64_t* d_pages, int64_t first, int64_t n_listed, int64_t E,
+                             hipStream_t s) {
+    AccumArgs a{acc, g16, used, d_pages, first, 0, E};
+    const unsigned nx = (unsigned)((E + kReduceTile - 1) / kReduceTile);
+    for (int64_t off = 0; off < n_listed; off += kMaxGridY) {
+        const int64_t ny = n_listed - off < kMaxGridY ? n_listed - off : kMaxGridY;
+        a.list_offset = off;
+        hipLaunchKernelGGL(apm_grad_accum_kernel, dim3(nx, (unsigned)ny), dim3(kThreads), 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 
 hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
     ReduceArgs a{L.g16, L.segs, L.used, L.grad_pages, L.grad_first, 0, L.E, L.partials, L.nzflags, L.S};

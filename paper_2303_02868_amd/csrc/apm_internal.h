@@ -102,6 +102,9 @@ struct AdamwLaunch {
 
 hipError_t launch_grad_reduce(const AdamwLaunch& a, hipStream_t s);
 hipError_t launch_adamw(const AdamwLaunch& a, hipStream_t s);
+hipError_t launch_grad_accum(uint16_t* acc, const uint16_t* g16, const int32_t* used,
+                             const int64_t* d_pages, int64_t first, int64_t n_listed, int64_t E,
+                             hipStream_t s);
 
 struct SegDesc {
     const void* src;

@@ -264,6 +264,45 @@ extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_
     return APM_OK;
 }
 
+extern "C" int apm_delayed_accumulate(apm_pool* pool, const int64_t* pages, int64_t n_pages,
+                                      const void* g16, void* stream) {
+    if (!pool || !g16) return fail(APM_EINVAL, "NULL argument");
+    if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "GPU pools only");
+    if (!pool->buffered) return fail(APM_ESTATE, "no gradient is being collected: call apm_step_delayed with a gradient first");
+    if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
+    if (n_pages == 0) return APM_OK;
+    APM_HIP(hipSetDevice(pool->desc.hip_device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t first = 0;
+    bool run = true;
+    if (pages) {
+        first = pages[0];
+        for (int64_t k = 0; k < n_pages; ++k) {
+            if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
+            if (pages[k] != first + k) run = false;
+        }
+    }
+    const int64_t* d_list = nullptr;
+    if (!run) {
+        int slot;
+        int rc = pool->ring.acquire((size_t)n_pages * sizeof(int64_t), &slot);
+        if (rc != APM_OK) return rc;
+        int64_t* h = static_cast<int64_t*>(pool->ring.h[slot]);
+        for (int64_t k = 0; k < n_pages; ++k) h[k] = pages[k];
+        rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(int64_t), s);
+        if (rc != APM_OK) return rc;
+        d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
+    }
+    // The collecting half was staged on the producer's stream; the sum is ordered after it there,
+    // and the "staged" event moves behind the sum so that the update sees the accumulated values.
+    const int k = pool->cur;
+    APM_HIP(hipStreamWaitEvent(s, pool->ev_staged[k], 0));
+    APM_HIP(launch_grad_accum(pool->gbuf[k], static_cast<const uint16_t*>(g16), pool->d_used, d_list, first,
+                              n_pages, pool->desc.page_elems, s));
+    APM_HIP(hipEventRecord(pool->ev_staged[k], s));
+    return APM_OK;
+}
+
 extern "C" void* apm_delayed_grad_buffer(apm_pool* pool, void* stream) {
     if (!pool || pool->desc.device != APM_DEV_GPU) {
         fail(APM_EINVAL, "NULL or non-GPU pool");

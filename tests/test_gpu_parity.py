@@ -196,6 +196,56 @@ def test_delayed_zero_copy_handover_equals_sync():
     b.destroy()
 
 
+def test_delayed_accumulation_matches_oracle_and_presummed_sync():
+    # three micro-gradients per update: the first starts the collection, two are accumulated
+    E = 16384
+    numels = [3 * E + 5, 100, 2 * E, 9000, E]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=11, sigma_g=5e-3)
+    plan, n, n_t = model.plan, model.plan.n_pages, len(specs)
+    h = oracle.Hyper(max_grad_norm=0.5)
+    hy = to_hyper(h)
+    a = DevicePool(n, E)                       # synchronous, on the pre-summed gradient
+    b = DevicePool(n, E)                       # delayed + accumulate
+    for dp in (a, b):
+        apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    pages = list(range(n))
+    st = oracle.PagedAdamWState(model.host_pages(model.p_flat, pages).view(np.float32), plan.used())
+    d = oracle.DelayedStepper(st)
+    stage = DevicePool(n, E, states=(apm.APM_G16,))
+    for t in range(1, 4):
+        gs = [model.grad_flat(10 * t + k) for k in range(3)]
+        rows = [model.host_pages(g, pages) for g in gs]
+        d.step(rows[0], h)
+        d.accumulate(rows[1])
+        d.accumulate(rows[2])
+        total = (gs[0] + gs[1]) + gs[2]                    # bf16 additions: fp32 sum, nearest even
+        apm.apm_pack_tensors(a.pool, apm.APM_G16, model.tensors(total), n_t)
+        torch.cuda.synchronize()
+        assert np.array_equal(a.rows_b16(apm.APM_G16, pages), d.buffered), "oracle sum != library bf16 sum"
+        apm.apm_page_adamw_step(a.pool, None, n, t, hy)
+        apm.apm_pack_tensors(stage.pool, apm.APM_G16, model.tensors(gs[0]), n_t)
+        apm.apm_step_delayed(b.pool, None, n, stage.reg[apm.APM_G16], hy)
+        for k in (1, 2):
+            apm.apm_pack_tensors(stage.pool, apm.APM_G16, model.tensors(gs[k]), n_t)
+            apm.apm_delayed_accumulate(b.pool, None if k == 1 else pages[::-1], n, stage.reg[apm.APM_G16])
+        torch.cuda.synchronize()
+    apm.apm_step_delayed(b.pool, None, n, None, hy)
+    d.step(None, h)
+    torch.cuda.synchronize()
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_delayed_accumulate(b.pool, None, n, stage.reg[apm.APM_G16])
+    assert e.value.code == apm.APM_ESTATE
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16):
+        assert torch.equal(a.reg[s_].view(torch.int16), b.reg[s_].view(torch.int16)), f"state {s_}"
+    used = plan.used()
+    check_state_close("p32", b.rows_f32(apm.APM_P32, pages), st.p, used)
+    check_state_close("m32", b.rows_f32(apm.APM_M32, pages), st.m, used)
+    check_state_close("v32", b.rows_f32(apm.APM_V32, pages), st.v, used)
+    for dp in (a, b, stage):
+        dp.destroy()
+
+
 def test_edge_ragged_lists_page_lists_clip_and_skip():
     # small pages so that tensors span several tiles with ragged tails; odd numels so that tensor
     # pointers are not 16-byte aligned; zero-size tensors; exact-page tensors

@@ -63,3 +63,32 @@ def test_buffered_gradient_is_a_copy():
     ref = oracle.PagedAdamWState(p32, used)
     ref.step(keep, 1, oracle.Hyper())
     assert state_bytes(st) == state_bytes(ref)
+
+
+def test_accumulate_matches_library_bf16_addition_and_sums_before_the_update():
+    import torch
+    rng = np.random.default_rng(5)
+    p32, used = make(4)
+    st = oracle.PagedAdamWState(p32, used)
+    d = oracle.DelayedStepper(st)
+    shape = p32.shape
+    def rand_bits(scale):
+        a = (rng.standard_normal(shape) * scale).astype(np.float32)
+        return (a.view(np.uint32) >> 16).astype(np.uint16)
+    g1, g2, g3 = rand_bits(1e-3), rand_bits(1e-3), rand_bits(3e-1)
+    g2[0, :4] = [0x0001, 0x8001, 0x7F7F, 0x0080]        # subnormals, largest finite, smallest normal
+    g1[0, :4] = [0x0001, 0x0001, 0x7F7F, 0x8080]
+    d.step(g1, oracle.Hyper())
+    d.accumulate(g2)
+    d.accumulate(g3)
+    tb = lambda bits: torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16)
+    want = ((tb(g1) + tb(g2)) + tb(g3)).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(d.buffered, want)
+    # the accumulated gradient is what the next call applies
+    d.step(None, oracle.Hyper())
+    ref = oracle.PagedAdamWState(p32, used)
+    ref.step(want, 1, oracle.Hyper())
+    assert state_bytes(st) == state_bytes(ref)
+    import pytest
+    with pytest.raises(RuntimeError):
+        d.accumulate(g1)
