@@ -335,6 +335,27 @@ def test_fused_gather_scatter_is_bit_identical_to_pack_step_unpack(gather, scatt
     b.destroy()
 
 
+def test_many_tiny_pages_exercise_grid_chunking_and_minimal_page_size():
+    # 70 000 pages of 64 elements: more listed pages than one grid dimension holds (65 535), so the
+    # launchers split the list; also the smallest slices (a page is a fraction of one tile)
+    E = 64
+    rng = np.random.default_rng(0)
+    numels = [int(x) for x in rng.choice([1, 7, 8, 63, 64, 65, 130, 640, 6400], size=9000)]
+    numels.append(E * 56000 + 5)
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=12, sigma_g=1e-2)
+    n = model.plan.n_pages
+    assert n > 66000
+    sample = sorted(set(range(0, n, 97)) | {0, n - 1, 65534, 65535, 65536})
+    dp, st, worst = run_resident(model, 2, oracle.Hyper(max_grad_norm=0.05, skip_mode=1), sample=sample)
+    dp.destroy()
+    # a permuted list longer than one grid dimension goes through the staged page list
+    listed = list(reversed(range(n)))
+    dp, st, worst = run_resident(model, 1, oracle.Hyper(max_grad_norm=0.05), sample=sample,
+                                 page_list=listed)
+    dp.destroy()
+
+
 def test_no_outputs_no_clip_path_matches_path_with_reduce():
     # without clip/skip/outputs the reduce pass is not launched; results must be identical
     E = 16384
