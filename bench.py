@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt_1p3b",
-                    choices=["cfg1_8pages", "gpt2_small_124m", "gpt_1p3b", "moe_8x64", "gpt_13b"])
+                    choices=["cfg1_8pages", "flat_1024pages", "gpt2_small_124m", "gpt_1p3b", "moe_8x64", "gpt_13b"])
     ap.add_argument("--clip", type=float, default=None,
                     help="per-page max grad norm (default: 1.0 for gpt_1p3b, else off)")
     ap.add_argument("--update-only", action="store_true", help="time reduce+update only (no pack/unpack)")

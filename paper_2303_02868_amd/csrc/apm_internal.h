@@ -73,6 +73,17 @@ struct PageSegs {
     uint16_t* q[2];
 };
 
+// What one listed page needs in the update kernel, gathered into one 32-byte record so that a
+// workgroup fetches it with a single scalar load: written per call by the finalize kernel (after a
+// reduce pass) or by the prepare kernel (no reduce pass).
+struct PageMeta {
+    int32_t used;   // used extent of the page (elements)
+    float scale;    // clip scale; negative = the page is skipped
+    int64_t gpage;  // page index for the 16-bit classes (and the page table)
+    int64_t spage;  // page index for the fp32 classes
+    int64_t pad;
+};
+
 struct AdamwLaunch {
     float* p32;
     float* m32;
@@ -80,7 +91,8 @@ struct AdamwLaunch {
     const uint16_t* g16;
     uint16_t* p16;
     const int32_t* used;          // device, indexed by grad page id
-    const PageSegs* segs;         // device, indexed by grad page id; needed if gather or scatter
+    const PageSegs* segs;         // device, indexed like the page list; needed if gather or scatter
+    PageMeta* meta;               // device scratch, [n_listed], filled by the reduce / prepare pass
     bool gather;                  // read g from the tenant tensors (segs[].g) instead of g16
     bool scatter;                 // write p16 to the tenant tensors (segs[].q) instead of p16
     const int64_t* state_pages;   // device list or nullptr (then state_first + i)
@@ -91,7 +103,6 @@ struct AdamwLaunch {
     int64_t E;
     double* partials;             // [n_listed][S] per-slice sums of squares; nullptr = no reduce pass
     uint32_t* nzflags;            // [n_listed][S] per-slice OR of magnitude bits
-    float* scale;                 // [n_listed] per-page clip scale (< 0: skipped), written by the reduce pass
     int32_t S;                    // slices per page = ceil(E / kReduceTile)
     float* grad_norm;             // device, nullable
     uint8_t* skip_mask;           // device, nullable
@@ -100,7 +111,10 @@ struct AdamwLaunch {
     int32_t skip_mode;
 };
 
+// Reduce pass (fills meta with clip scale / skip); or, when no reduce pass is needed, the prepare
+// pass (fills meta with scale 1).  One of the two must precede launch_adamw on the same stream.
 hipError_t launch_grad_reduce(const AdamwLaunch& a, hipStream_t s);
+hipError_t launch_prepare(const AdamwLaunch& a, hipStream_t s);
 hipError_t launch_adamw(const AdamwLaunch& a, hipStream_t s);
 hipError_t launch_grad_accum(uint16_t* acc, const uint16_t* g16, const int32_t* used,
                              const int64_t* d_pages, int64_t first, int64_t n_listed, int64_t E,
@@ -131,7 +145,7 @@ struct apm_pool {
     int32_t* d_used = nullptr;      // device page table: used extent per page
     double* d_partials = nullptr;   // reduce scratch, n_pages * S
     uint32_t* d_nzflags = nullptr;
-    float* d_scale = nullptr;
+    apm::PageMeta* d_meta = nullptr;  // n_pages entries
     int32_t S = 0;
     apm::StageRing ring;
 

@@ -51,11 +51,11 @@ void StageRing::destroy() {
 }
 
 int ensure_scratch(apm_pool* pool) {
-    if (pool->d_scale) return APM_OK;
+    if (pool->d_meta) return APM_OK;
     const int64_t n = pool->desc.n_pages * pool->S;
     APM_HIP(hipMalloc((void**)&pool->d_partials, (size_t)n * sizeof(double)));
     APM_HIP(hipMalloc((void**)&pool->d_nzflags, (size_t)n * sizeof(uint32_t)));
-    APM_HIP(hipMalloc((void**)&pool->d_scale, (size_t)pool->desc.n_pages * sizeof(float)));
+    APM_HIP(hipMalloc((void**)&pool->d_meta, (size_t)pool->desc.n_pages * sizeof(PageMeta)));
     return APM_OK;
 }
 
@@ -100,7 +100,7 @@ void free_pool(apm_pool* pool) {
     if (pool->d_used) (void)hipFree(pool->d_used);
     if (pool->d_partials) (void)hipFree(pool->d_partials);
     if (pool->d_nzflags) (void)hipFree(pool->d_nzflags);
-    if (pool->d_scale) (void)hipFree(pool->d_scale);
+    if (pool->d_meta) (void)hipFree(pool->d_meta);
     pool->ring.destroy();
     for (auto& t : pool->timed) {
         (void)hipEventDestroy(t.begin);

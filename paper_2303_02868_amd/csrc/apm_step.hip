@@ -97,24 +97,25 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
         if (pages)
             for (int64_t k = 0; k < n_pages; ++k)
                 if (pages[k] >= in_use) return fail(APM_ERANGE, "pages[%lld] = %lld is not in use by the layout", (long long)k, (long long)pages[k]);
-        // One PageSegs entry per page in use, rebuilt per call: the tensors are caller-owned and
+        // One PageSegs entry per listed page, rebuilt per call: the tensors are caller-owned and
         // their addresses may change from step to step.
         const size_t n_in_use = pool->plan.pages.size();
-        int slot;
-        rc = pool->ring.acquire(n_in_use * sizeof(PageSegs), &slot);
-        if (rc != APM_OK) return rc;
-        PageSegs* h = static_cast<PageSegs*>(pool->ring.h[slot]);
-        for (size_t k = 0; k < n_in_use; ++k) h[k] = PageSegs{};
+        std::vector<PageSegs> by_page(n_in_use);
         std::vector<uint8_t> filled(n_in_use, 0);
         for (const apm_segment& sg : pool->plan.segs) {  // a page's tenants appear in offset order
-            PageSegs& e = h[(size_t)sg.page];
+            PageSegs& e = by_page[(size_t)sg.page];
             const int k = filled[(size_t)sg.page]++;
             e.off[k] = (int32_t)sg.page_off;
             e.n[k] = (int32_t)sg.n;
             if (grad_tensors) e.g[k] = static_cast<const uint16_t*>(grad_tensors[sg.tensor].data) + sg.tensor_off;
             if (p16_tensors) e.q[k] = static_cast<uint16_t*>(p16_tensors[sg.tensor].data) + sg.tensor_off;
         }
-        rc = pool->ring.commit(slot, n_in_use * sizeof(PageSegs), stream);
+        int slot;
+        rc = pool->ring.acquire((size_t)n_pages * sizeof(PageSegs), &slot);
+        if (rc != APM_OK) return rc;
+        PageSegs* h = static_cast<PageSegs*>(pool->ring.h[slot]);
+        for (int64_t k = 0; k < n_pages; ++k) h[k] = by_page[(size_t)(pages ? pages[k] : k)];
+        rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(PageSegs), stream);
         if (rc != APM_OK) return rc;
         L.segs = static_cast<const PageSegs*>(pool->ring.d[slot]);
         L.gather = grad_tensors != nullptr;
@@ -134,14 +135,16 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     L.grad_norm = grad_norm;
     L.skip_mask = skip_mask;
     const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
+    rc = ensure_scratch(pool);
+    if (rc != APM_OK) return rc;
+    L.meta = pool->d_meta;
     if (need_reduce) {
-        rc = ensure_scratch(pool);
-        if (rc != APM_OK) return rc;
         L.partials = pool->d_partials;
         L.nzflags = pool->d_nzflags;
-        L.scale = pool->d_scale;
         ScopedTiming t(pool, APM_K_REDUCE, stream);
         APM_HIP(launch_grad_reduce(L, stream));
+    } else {
+        APM_HIP(launch_prepare(L, stream));
     }
     {
         ScopedTiming t(pool, APM_K_UPDATE, stream);

@@ -197,10 +197,10 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     L.m32 = s->stage[1];
     L.v32 = s->stage[2];
     const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
+    L.meta = dev->d_meta;
     if (need_reduce) {
         L.partials = dev->d_partials;
         L.nzflags = dev->d_nzflags;
-        L.scale = dev->d_scale;
     }
     const int states[3] = {APM_P32, APM_M32, APM_V32};
     const int64_t R = s->cache ? (s->R < N ? s->R : N) : 0;
@@ -220,6 +220,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         C.grad_norm = grad_norm ? grad_norm + r_done : nullptr;
         C.skip_mask = skip_mask ? skip_mask + r_done : nullptr;
         if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
+        else APM_HIP(launch_prepare(C, s->s_cmp));
         APM_HIP(launch_adamw(C, s->s_cmp));
         r_done += nr;
         return APM_OK;
@@ -273,6 +274,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         L.skip_mask = skip_mask ? skip_mask + first : nullptr;
         if (what & kDoUpdate) {
             if (need_reduce) APM_HIP(launch_grad_reduce(L, s->s_cmp));
+            else APM_HIP(launch_prepare(L, s->s_cmp));
             APM_HIP(launch_adamw(L, s->s_cmp));
         }
         APM_HIP(hipEventRecord(s->ev_cmp[slot], s->s_cmp));

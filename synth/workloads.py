@@ -99,6 +99,8 @@ def tensor_offsets(tensors: List[TensorSpec]) -> np.ndarray:
 WORKLOADS = {
     # 8 full pages of 262144 elements, one tensor
     "cfg1_8pages": (lambda: [TensorSpec(0, "flat", 8 * 262144)], 262144),
+    # 1024 completely full pages, one tensor: no fragmentation (a kernel-tuning reference point)
+    "flat_1024pages": (lambda: [TensorSpec(0, "flat", 1024 << 20)], 1 << 20),
     "gpt2_small_124m": (lambda: gpt_tensor_list(12, 768, 3072, 50257, 1024), 1 << 20),
     "gpt_1p3b": (lambda: gpt_tensor_list(24, 2048, 8192, 50257, 2048), 1 << 20),
     "gpt_13b": (lambda: gpt_tensor_list(40, 5120, 20480, 50257, 2048), 1 << 20),
