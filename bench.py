@@ -213,6 +213,44 @@ def delayed_leg(args, wl, pool, hyper, n_pages, first_step):
             "applied_updates": apm.apm_delayed_applied(pool)}
 
 
+def moe_active_list_leg(args, wl, pool, hyper, plan, first_step):
+    """The MoE step when the caller already knows which experts received tokens and lists only
+    their pages (plus the dense ones), against the default of listing every page and letting the
+    device find the all-zero ones."""
+    import torch
+    import paper_2303_02868_amd as apm
+    import synth
+    stream = torch.cuda.current_stream()
+    lists, g_tensors, keep = [], [], []
+    for k in range(2):
+        act = synth.moe_active_tensors(wl.specs, k + 1, 0, 64, 8)
+        pages = sorted({pg for (t, _, pg, _, _) in plan.segments if act[t]})
+        lists.append(pages)
+        g = wl.gen(1001 + k, True, 1e-3, act)
+        keep.append(g)
+        g_tensors.append(wl.tensors(g))
+    p16_flat = torch.zeros(wl.total, dtype=torch.bfloat16, device=DEV)
+    p16_tensors = wl.tensors(p16_flat)
+    steps = max(4, args.steps // 2)
+    t = first_step
+    for k in range(2):
+        apm.apm_page_adamw_step_fused(pool, lists[k], len(lists[k]), t, hyper, g_tensors[k], p16_tensors,
+                                      wl.n_t, None, None, stream)
+        t += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        apm.apm_page_adamw_step_fused(pool, lists[k & 1], len(lists[k & 1]), t, hyper, g_tensors[k & 1],
+                                      p16_tensors, wl.n_t, None, None, stream)
+        t += 1
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    active = sum(sum(n for n, a in zip(wl.numels, synth.moe_active_tensors(wl.specs, k + 1, 0, 64, 8)) if a)
+                 for k in range(2)) / 2.0
+    return {"ms_per_step": dt * 1e3, "listed_pages": [len(x) for x in lists],
+            "useful_params_per_s": active / dt}
+
+
 def d2d_copy_ceiling():
     import torch
     n_copy = 1 << 29
@@ -445,6 +483,7 @@ def main():
         out["d2d_copy_GBps"] = d2d_copy_ceiling()
         if args.workload == "moe_8x64" and not args.update_only:
             out["delayed"] = delayed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
+            out["active_page_list"] = moe_active_list_leg(args, wl, pool, hyper, plan, r["next_step"] + 100)
         if not args.no_streamed:
             apm.apm_pack_tensors(pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
             out["streamed"] = streamed_leg(args, wl, pool, hyper, n_pages, r["next_step"])

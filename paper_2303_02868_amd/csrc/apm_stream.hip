@@ -61,7 +61,15 @@ int pick_copy_streams(apm_streamer* s) {
     hipStream_t cand[kNew + 1] = {nullptr};  // cand[0] = the default stream
     for (int k = 1; k <= kNew; ++k) APM_HIP(hipStreamCreateWithFlags(&cand[k], hipStreamNonBlocking));
     char* h = nullptr;
-    APM_HIP(hipHostMalloc((void**)&h, 2 * kProbe, hipHostMallocDefault));
+    if (hipHostMalloc((void**)&h, 2 * kProbe, hipHostMallocDefault) != hipSuccess) {
+        // no pinned memory left for the probe (the host pool may have taken it all): go without
+        (void)hipGetLastError();
+        s->s_in = cand[1];
+        s->s_out = cand[2];
+        s->s_cmp = cand[3];
+        (void)hipStreamDestroy(cand[4]);
+        return APM_OK;
+    }
     const size_t slot_bytes = (size_t)s->B * (size_t)s->dev->desc.page_elems * sizeof(float);
     const size_t n = slot_bytes < kProbe ? slot_bytes : kProbe;
     char* d_in = reinterpret_cast<char*>(s->stage[0]);   // staging is not in use yet
