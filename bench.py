@@ -44,7 +44,7 @@ def parse():
                     help="headline step = separate pack g16 / unpack p16 kernels instead of the fused gather/scatter")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pages", type=int, default=192, help="pages of the workload the oracle is timed on")
-    ap.add_argument("--cpu-steps", type=int, default=2)
+    ap.add_argument("--cpu-steps", type=int, default=10)
     ap.add_argument("--no-streamed", action="store_true", help="skip the host-streamed leg")
     ap.add_argument("--streamed-only", action="store_true", help="run only the host-streamed leg (gpt_13b: always)")
     ap.add_argument("--stream-steps", type=int, default=3)
