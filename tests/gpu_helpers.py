@@ -179,7 +179,8 @@ def run_resident(model: Model, steps: int, h: oracle.Hyper, sample: Optional[Seq
                  stepper: str = "sync"):
     """Runs `steps` AdamW steps through the HIP path on all pages (or `page_list`) and through the
     oracle on the sampled pages (default: all), then applies the parity gates.
-    stepper: "sync" = apm_page_adamw_step, "delayed" = apm_step_delayed + flush."""
+    stepper: "sync" = pack g16 + apm_page_adamw_step, "fused" = apm_page_adamw_step_fused reading g16
+    from and writing p16 to tensors (the form bench.py times), "delayed" = apm_step_delayed + flush."""
     plan = model.plan
     n_pages, E = plan.n_pages, model.E
     sample = list(range(n_pages)) if sample is None else list(sample)
@@ -205,6 +206,7 @@ def run_resident(model: Model, steps: int, h: oracle.Hyper, sample: Optional[Seq
     if stepper == "delayed":
         apm.apm_delayed_set_outputs(dp.pool, norm_d, skip_d)
     last_outputs = None
+    q_flat = torch.zeros(model.total, dtype=torch.bfloat16, device=DEV) if stepper == "fused" else None
     touched = [False] * len(sample)
     for t in range(1, steps + 1):
         g_flat = model.grad_flat(t)
@@ -212,6 +214,9 @@ def run_resident(model: Model, steps: int, h: oracle.Hyper, sample: Optional[Seq
         if stepper == "sync":
             apm.apm_pack_tensors(dp.pool, apm.APM_G16, model.tensors(g_flat), len(model.specs))
             apm.apm_page_adamw_step(dp.pool, pages_arg, len(listed), t, hy, norm_d, skip_d)
+        elif stepper == "fused":
+            apm.apm_page_adamw_step_fused(dp.pool, pages_arg, len(listed), t, hy, model.tensors(g_flat),
+                                          model.tensors(q_flat), len(model.specs), norm_d, skip_d)
         else:
             # the producer writes its gradient in page layout into its own buffer (a second pool
             # over g_pack would do the same; the G16 class of dp serves as that buffer here)
@@ -226,7 +231,7 @@ def run_resident(model: Model, steps: int, h: oracle.Hyper, sample: Optional[Seq
         last_outputs = (upd, norms, skips)
         for r, sk in zip(upd, skips):
             touched[r] = touched[r] or not sk
-        if want_outputs and stepper == "sync":
+        if want_outputs and stepper in ("sync", "fused"):
             check_outputs(norm_d, skip_d, listed, sample, upd, norms, skips)
         del g_flat
     if stepper == "delayed":
@@ -239,7 +244,11 @@ def run_resident(model: Model, steps: int, h: oracle.Hyper, sample: Optional[Seq
     got_p = dp.rows_f32(apm.APM_P32, sample)
     got_m = dp.rows_f32(apm.APM_M32, sample)
     got_v = dp.rows_f32(apm.APM_V32, sample)
-    got_p16 = dp.rows_b16(apm.APM_P16, sample)
+    if stepper == "fused":      # p16 went to the tensors: lay them out like pages for the check
+        got_p16 = model.host_pages(q_flat, sample)
+        assert not dp.reg[apm.APM_P16].view(torch.int16).any() and not dp.reg[apm.APM_G16].view(torch.int16).any()
+    else:
+        got_p16 = dp.rows_b16(apm.APM_P16, sample)
     worst = {
         "p": check_state_close("p32", got_p, st.p, used),
         "m": check_state_close("m32", got_m, st.m, used),
@@ -247,6 +256,7 @@ def run_resident(model: Model, steps: int, h: oracle.Hyper, sample: Optional[Seq
     }
     check_p16(got_p16, got_p, st.p16, used, touched)
     check_padding_zero(dp, plan, sample)
+    dp.q_flat = q_flat
     return dp, st, worst
 
 

@@ -78,13 +78,16 @@ def sampled_pages(plan, every):
     return sorted(s)
 
 
-def test_cfg3_gpt_1p3b_clipped_ten_steps_sampled_oracle():
+@pytest.mark.parametrize("stepper", ["sync", "fused"])
+def test_cfg3_gpt_1p3b_clipped_ten_steps_sampled_oracle(stepper):
+    # "fused" is the launch configuration bench.py times: gradients read from the tensors, bf16
+    # parameters written to the tensors, no G16 / P16 page traffic
     specs, E = specs_of("gpt_1p3b")
     model = Model(specs, E, seed=0)
     sample = sampled_pages(model.plan, 16)
     log(f"cfg3 pages {model.plan.n_pages}, oracle on {len(sample)} pages")
     h = oracle.Hyper(max_grad_norm=1.0)
-    dp, st, worst = run_resident(model, 10, h, sample=sample)
+    dp, st, worst = run_resident(model, 10, h, sample=sample, stepper=stepper)
     log(f"cfg3 worst rel err {worst}")
     assert worst["v"] < 2e-6
     dp.destroy()
