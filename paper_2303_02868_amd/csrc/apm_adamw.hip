@@ -1,6 +1,12 @@
-// Page AdamW kernels for gfx950: per-slice gradient reduction and the fused update.
+// Page AdamW kernels for gfx950:
+//   apm_grad_reduce_kernel    per (page, slice) sum of squares (fp64) and any-nonzero of g16
+//   apm_grad_finalize_kernel  per page: norm, clip scale, skip decision -> the page's record
+//   apm_page_meta_kernel      the page records when no reduce pass is needed
+//   apm_adamw_kernel          the fused update (optionally gathering g16 from / scattering p16 to
+//                             the caller's tensors)
+//   apm_grad_accum_kernel     g' += g for the buffered gradient of the delayed path
 //
-// Both kernels are HBM-bandwidth bound (no reuse, ~20 fp32 operations per element), so the design
+// All are HBM-bandwidth bound (no reuse, ~50 VALU operations per element at most), so the design
 // is about memory access only: every wavefront instruction touches one fully contiguous span
 // (1 KiB for the 128-bit fp32 accesses, 512 B for the 64-bit bf16 accesses), each lane keeps
 // several independent loads in flight, and a workgroup never straddles a page.
