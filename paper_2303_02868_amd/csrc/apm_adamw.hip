@@ -255,6 +255,7 @@ struct FinalizeArgs {
     PageMeta* meta;    // [n_listed]
     float* grad_norm;  // nullable
     uint8_t* skip_mask;  // nullable
+    const int32_t* out_index;  // nullable: list position -> index into grad_norm / skip_mask
 };
 
 // One wavefront per listed page: combines the page's slice partials in a fixed order and turns
@@ -289,8 +290,9 @@ __global__ __launch_bounds__(kThreads) void apm_grad_finalize_kernel(FinalizeArg
     pm.spage = a.state_pages ? a.state_pages[i] : a.state_first + i;
     pm.pad = 0;
     a.meta[i] = pm;
-    if (a.grad_norm) a.grad_norm[i] = skip ? 0.0f : (float)norm;
-    if (a.skip_mask) a.skip_mask[i] = skip ? 1 : 0;
+    const int64_t o = a.out_index ? (int64_t)a.out_index[i] : i;
+    if (a.grad_norm) a.grad_norm[o] = skip ? 0.0f : (float)norm;
+    if (a.skip_mask) a.skip_mask[o] = skip ? 1 : 0;
 }
 
 // No reduce pass: one thread per listed page fills its record with scale 1.
@@ -502,18 +504,38 @@ hipError_t launch_grad_accum(uint16_t* acc, const uint16_t* g16, const int32_t* 
     return hipSuccess;
 }
 
+namespace {
+// Calls f(first list position, pages, largest used extent) for every launch of a pass: per extent
+// class, in pieces of at most kMaxGridY pages.
+template <class F>
+hipError_t for_each_launch(const AdamwLaunch& L, F&& f) {
+    const ExtentClass all{0, L.n_listed, L.E};
+    const ExtentClass* c = L.n_cls > 0 ? L.cls : &all;
+    const int n = L.n_cls > 0 ? L.n_cls : 1;
+    for (int k = 0; k < n; ++k) {
+        for (int64_t off = 0; off < c[k].count; off += kMaxGridY) {
+            const int64_t ny = c[k].count - off < kMaxGridY ? c[k].count - off : kMaxGridY;
+            f(c[k].begin + off, ny, c[k].max_used > 0 ? c[k].max_used : 1);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+}  // namespace
+
 hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
     ReduceArgs a{L.g16, L.segs, L.used, L.grad_pages, L.grad_first, 0, L.E, L.partials, L.nzflags, L.S};
-    for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
-        const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
-        a.list_offset = off;
-        if (L.gather) hipLaunchKernelGGL(apm_grad_reduce_kernel<true>, dim3((unsigned)L.S, (unsigned)ny), dim3(kThreads), 0, s, a);
-        else hipLaunchKernelGGL(apm_grad_reduce_kernel<false>, dim3((unsigned)L.S, (unsigned)ny), dim3(kThreads), 0, s, a);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
+    hipError_t e = for_each_launch(L, [&](int64_t begin, int64_t ny, int64_t max_used) {
+        a.list_offset = begin;
+        const dim3 grid((unsigned)((max_used + kReduceTile - 1) / kReduceTile), (unsigned)ny);
+        if (L.gather) hipLaunchKernelGGL(apm_grad_reduce_kernel<true>, grid, dim3(kThreads), 0, s, a);
+        else hipLaunchKernelGGL(apm_grad_reduce_kernel<false>, grid, dim3(kThreads), 0, s, a);
+    });
+    if (e != hipSuccess) return e;
     FinalizeArgs f{L.used, L.grad_pages, L.state_pages, L.grad_first, L.state_first, L.n_listed,
-                   L.partials, L.nzflags, L.S, L.skip_mode, L.max_norm, L.meta, L.grad_norm, L.skip_mask};
+                   L.partials, L.nzflags, L.S, L.skip_mode, L.max_norm, L.meta, L.grad_norm, L.skip_mask,
+                   L.out_index};
     const int per_wg = kThreads / kWave;
     hipLaunchKernelGGL(apm_grad_finalize_kernel, dim3((unsigned)((L.n_listed + per_wg - 1) / per_wg)),
                        dim3(kThreads), 0, s, f);
@@ -522,7 +544,7 @@ hipError_t launch_grad_reduce(const AdamwLaunch& L, hipStream_t s) {
 
 hipError_t launch_prepare(const AdamwLaunch& L, hipStream_t s) {
     FinalizeArgs f{L.used, L.grad_pages, L.state_pages, L.grad_first, L.state_first, L.n_listed,
-                   nullptr, nullptr, L.S, L.skip_mode, 0.0, L.meta, nullptr, nullptr};
+                   nullptr, nullptr, L.S, L.skip_mode, 0.0, L.meta, nullptr, nullptr, nullptr};
     hipLaunchKernelGGL(apm_page_meta_kernel, dim3((unsigned)((L.n_listed + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, s, f);
     return hipGetLastError();
@@ -538,11 +560,9 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
     a.inv_sqrt_bc2 = L.inv_sqrt_bc2; a.eps = L.eps; a.step_size = L.step_size; a.lr_wd = L.lr_wd;
     const bool may_skip = L.partials && L.skip_mode == APM_SKIP_UNTOUCHED;
     const int64_t wg_span = (int64_t)kUpdTile * (may_skip ? APM_UPDATE_SLICES_SKIP : 1);
-    const unsigned nx = (unsigned)((L.E + wg_span - 1) / wg_span);
-    for (int64_t off = 0; off < L.n_listed; off += kMaxGridY) {
-        const int64_t ny = L.n_listed - off < kMaxGridY ? L.n_listed - off : kMaxGridY;
-        a.list_offset = off;
-        const dim3 grid(nx, (unsigned)ny), block(kUpdThreads);
+    return for_each_launch(L, [&](int64_t begin, int64_t ny, int64_t max_used) {
+        a.list_offset = begin;
+        const dim3 grid((unsigned)((max_used + wg_span - 1) / wg_span), (unsigned)ny), block(kUpdThreads);
 #define APM_LAUNCH_UPDATE(G, Q)                                                                         \
     do {                                                                                               \
         if (may_skip) hipLaunchKernelGGL((apm_adamw_kernel<G, Q, APM_UPDATE_SLICES_SKIP>), grid, block, APM_UPDATE_LDS, s, a); \
@@ -553,10 +573,7 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
         else if (L.scatter) APM_LAUNCH_UPDATE(false, true);
         else APM_LAUNCH_UPDATE(false, false);
 #undef APM_LAUNCH_UPDATE
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    });
 }
 
 }  // namespace apm

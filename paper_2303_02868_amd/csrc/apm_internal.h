@@ -84,6 +84,17 @@ struct PageMeta {
     int64_t pad;
 };
 
+// The listed pages of one call, grouped by used extent: the pages of a class sit at consecutive
+// list positions and are launched together, with a grid sized for the class's largest extent, so
+// that a nearly empty page (a small tensor alone in its page) does not cost a full page's worth
+// of workgroups that only find out they have nothing to do.
+constexpr int kMaxExtentClasses = 4;
+struct ExtentClass {
+    int64_t begin;     // first list position
+    int64_t count;     // pages
+    int64_t max_used;  // largest used extent among them (elements)
+};
+
 struct AdamwLaunch {
     float* p32;
     float* m32;
@@ -100,6 +111,10 @@ struct AdamwLaunch {
     int64_t state_first;
     int64_t grad_first;
     int64_t n_listed;
+    ExtentClass cls[kMaxExtentClasses];  // n_cls == 0: one class, all positions, extent E
+    int n_cls;
+    const int32_t* out_index;     // device: list position -> index into grad_norm / skip_mask;
+                                  // nullptr = the position itself
     int64_t E;
     double* partials;             // [n_listed][S] per-slice sums of squares; nullptr = no reduce pass
     uint32_t* nzflags;            // [n_listed][S] per-slice OR of magnitude bits

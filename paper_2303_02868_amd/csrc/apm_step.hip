@@ -69,35 +69,89 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     if (n_pages == 0) return APM_OK;
     APM_HIP(hipSetDevice(pool->desc.hip_device));
 
-    // A list that is an ascending run needs no indirection; anything else is staged to the device.
-    int64_t first = 0;
-    bool run = true;
-    if (pages) {
-        first = pages[0];
-        for (int64_t k = 0; k < n_pages; ++k) {
+    // List positions are grouped into extent classes (largest extents first, the caller's order
+    // kept inside a class).  order[pos] = the caller's index of the page launched at position pos.
+    const int64_t E = pool->desc.page_elems;
+    const int64_t in_use = pool->has_layout ? (int64_t)pool->plan.pages.size() : 0;
+    auto page_at = [&](int64_t k) { return pages ? pages[k] : k; };
+    auto used_of = [&](int64_t page) { return page < in_use ? pool->plan.pages[(size_t)page].used : (int64_t)0; };
+    if (pages)
+        for (int64_t k = 0; k < n_pages; ++k)
             if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] = %lld out of range [0, %lld)", (long long)k, (long long)pages[k], (long long)pool->desc.n_pages);
-            if (pages[k] != first + k) run = false;
+    auto class_of = [&](int64_t used) { return used * 4 > E ? 0 : used * 32 > E ? 1 : used * 512 > E ? 2 : 3; };
+    int64_t cnt[kMaxExtentClasses] = {}, mx[kMaxExtentClasses] = {};
+    for (int64_t k = 0; k < n_pages; ++k) {
+        const int64_t u = used_of(page_at(k));
+        const int c = class_of(u);
+        ++cnt[c];
+        if (u > mx[c]) mx[c] = u;
+    }
+    // A class is worth its extra launches only if it saves enough idle workgroups (counted in
+    // 1024-element update slices); otherwise it is folded into the next larger one.
+    int into[kMaxExtentClasses];
+    for (int c = 0; c < kMaxExtentClasses; ++c) into[c] = c;
+    constexpr int64_t kUpdateSpan = 1024, kWorthWorkgroups = 16384;
+    for (int c = kMaxExtentClasses - 1; c > 0; --c) {
+        if (cnt[c] == 0) continue;
+        int j = c - 1;
+        while (j > 0 && cnt[j] == 0) --j;
+        if (cnt[j] == 0) continue;
+        if (cnt[c] * ((mx[j] - mx[c]) / kUpdateSpan) < kWorthWorkgroups) {
+            for (int q = c; q < kMaxExtentClasses; ++q) if (into[q] == c) into[q] = j;
+            cnt[j] += cnt[c];
+            cnt[c] = 0;
         }
     }
+    int64_t begin[kMaxExtentClasses];
+    for (int64_t c = 0, at = 0; c < kMaxExtentClasses; ++c) {
+        begin[c] = at;
+        if (cnt[c] > 0) L.cls[L.n_cls++] = ExtentClass{at, cnt[c], mx[c]};
+        at += cnt[c];
+    }
+    std::vector<int64_t> order((size_t)n_pages);
+    bool identity = true;
+    {
+        int64_t fill[kMaxExtentClasses];
+        for (int c = 0; c < kMaxExtentClasses; ++c) fill[c] = begin[c];
+        for (int64_t k = 0; k < n_pages; ++k) {
+            const int c = into[class_of(used_of(page_at(k)))];
+            const int64_t pos = fill[c]++;
+            order[(size_t)pos] = k;
+            if (pos != k) identity = false;
+        }
+    }
+
+    // A list that is an ascending run launched in the caller's order needs no indirection;
+    // anything else is staged to the device: page indices, then the output indices.
+    const int64_t first = page_at(0);
+    bool run = identity;
+    for (int64_t k = 0; run && k < n_pages; ++k)
+        if (page_at(k) != first + k) run = false;
     const int64_t* d_list = nullptr;
     if (!run) {
+        const size_t list_bytes = (size_t)n_pages * sizeof(int64_t);
+        const size_t bytes = list_bytes + (size_t)n_pages * sizeof(int32_t);
         int slot;
-        rc = pool->ring.acquire((size_t)n_pages * sizeof(int64_t), &slot);
+        rc = pool->ring.acquire(bytes, &slot);
         if (rc != APM_OK) return rc;
         int64_t* h = static_cast<int64_t*>(pool->ring.h[slot]);
-        for (int64_t k = 0; k < n_pages; ++k) h[k] = pages[k];
-        rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(int64_t), stream);
+        int32_t* ho = reinterpret_cast<int32_t*>(static_cast<char*>(pool->ring.h[slot]) + list_bytes);
+        for (int64_t k = 0; k < n_pages; ++k) {
+            h[k] = page_at(order[(size_t)k]);
+            ho[k] = (int32_t)order[(size_t)k];
+        }
+        rc = pool->ring.commit(slot, bytes, stream);
         if (rc != APM_OK) return rc;
         d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
+        if (!identity) L.out_index = reinterpret_cast<const int32_t*>(static_cast<const char*>(pool->ring.d[slot]) + list_bytes);
     }
 
     if (grad_tensors || p16_tensors) {
-        const int64_t in_use = (int64_t)pool->plan.pages.size();
         if (!pages && n_pages > in_use) return fail(APM_ERANGE, "page count %lld exceeds the %lld pages in use", (long long)n_pages, (long long)in_use);
         if (pages)
             for (int64_t k = 0; k < n_pages; ++k)
                 if (pages[k] >= in_use) return fail(APM_ERANGE, "pages[%lld] = %lld is not in use by the layout", (long long)k, (long long)pages[k]);
-        // One PageSegs entry per listed page, rebuilt per call: the tensors are caller-owned and
+        // One PageSegs entry per list position, rebuilt per call: the tensors are caller-owned and
         // their addresses may change from step to step.
         const size_t n_in_use = pool->plan.pages.size();
         std::vector<PageSegs> by_page(n_in_use);
@@ -114,7 +168,7 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
         rc = pool->ring.acquire((size_t)n_pages * sizeof(PageSegs), &slot);
         if (rc != APM_OK) return rc;
         PageSegs* h = static_cast<PageSegs*>(pool->ring.h[slot]);
-        for (int64_t k = 0; k < n_pages; ++k) h[k] = by_page[(size_t)(pages ? pages[k] : k)];
+        for (int64_t k = 0; k < n_pages; ++k) h[k] = by_page[(size_t)page_at(order[(size_t)k])];
         rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(PageSegs), stream);
         if (rc != APM_OK) return rc;
         L.segs = static_cast<const PageSegs*>(pool->ring.d[slot]);
@@ -130,7 +184,7 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     L.state_pages = L.grad_pages = d_list;
     L.state_first = L.grad_first = first;
     L.n_listed = n_pages;
-    L.E = pool->desc.page_elems;
+    L.E = E;
     L.S = pool->S;
     L.grad_norm = grad_norm;
     L.skip_mask = skip_mask;

@@ -359,6 +359,35 @@ def test_many_tiny_pages_exercise_grid_chunking_and_minimal_page_size():
     dp.destroy()
 
 
+@pytest.mark.parametrize("stepper", ["sync", "fused"])
+def test_pages_of_very_different_extents_in_a_permuted_list(stepper):
+    # Full pages, pages a tenth full and pages holding a hundred elements, enough of each that the
+    # library launches them as separate groups with their own grid sizes; the list is permuted so
+    # that the per-page outputs must come back in the caller's order.
+    E = 1 << 20
+    numels = [3 * E + 5000]
+    numels += [100000 + 8 * i for i in range(22)]
+    numels += [100 + i for i in range(320)]
+    numels += [2 * E]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    zero_grad = {5, 40, 41, 300}
+    act = lambda t: np.array([i not in zero_grad for i in range(len(numels))])
+    model = Model(specs, E, seed=21, sigma_g=2e-3, active_fn=act, align_elems=8)
+    n = model.plan.n_pages
+    rng = np.random.default_rng(5)
+    listed = [int(p) for p in rng.permutation(n) if p % 11 != 3]
+    sample = sorted(set(range(0, n, 7)) | {0, 1, 2, 3, 4, 5, 6, n - 3, n - 2, n - 1})
+    h = oracle.Hyper(max_grad_norm=0.5, skip_mode=1)
+    dp, st, worst = run_resident(model, 2, h, sample=sample, page_list=listed, stepper=stepper)
+    log(f"mixed extents [{stepper}] worst {worst}")
+    unl = [p for p in range(n) if p % 11 == 3]
+    assert not dp.rows_f32(apm.APM_M32, unl).any()
+    dp.destroy()
+    # all pages in the natural order (no caller list): the reordering is internal only
+    dp, st, worst = run_resident(model, 1, oracle.Hyper(), sample=sample, stepper=stepper)
+    dp.destroy()
+
+
 def test_no_outputs_no_clip_path_matches_path_with_reduce():
     # without clip/skip/outputs the reduce pass is not launched; results must be identical
     E = 16384
