@@ -254,26 +254,44 @@ int apm_page_adamw_step_fused(apm_pool* pool, const int64_t* pages, int64_t n_pa
 int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_page,
                         int64_t n_pages, int state, void* stream);
 
-/* ---- streamed update: FP32 states in pinned host pages, double-buffered through HBM
+/* ---- streamed update: FP32 states in pinned host pages, updated page by page across PCIe
  *      (Sec. 4.2: overlap movement with computation, scheduled per page) -------------------- */
 
 /*
  * host:   HOST pool storing P32, M32, V32 (the layout is taken from `dev`).
  * dev:    GPU pool storing G16 and P16 for the same pages, with an installed layout.
- * batch_pages: pages moved and updated per pipeline stage (>= 1).
- * n_slots: staging slots in HBM (>= 2); each holds batch_pages pages of the three fp32 classes.
- * The streamer owns its staging memory, events and three streams (copy-in, compute, copy-out).
- * Which stream pairs overlap a host-to-device with a device-to-host copy depends on the runtime,
- * so creation times short concurrent copies on a few candidate streams (the default stream among
- * them) and keeps the best pair; this takes some tens of milliseconds and synchronises the device.
+ * batch_pages: pages moved and updated per pipeline stage of the staged mode (>= 1).
+ * n_slots: staging slots in HBM for the staged mode (>= 2); each holds batch_pages pages of the
+ *          three fp32 classes.
+ * The streamer starts in APM_STREAM_DIRECT if the GPU can address the host pool's memory (pinned
+ * memory: always), else in APM_STREAM_STAGED; see apm_streamer_set_mode.
  */
 int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool* dev, int64_t batch_pages,
                         int n_slots);
 int apm_streamer_destroy(apm_streamer* s);
 
 /*
- * One AdamW step over all pages in use: for batch b, H2D(b+1) on the copy-in stream runs beside
- * update(b) on the compute stream and D2H(b-1) on the copy-out stream, ordered by events.
+ * How the fp32 pages cross PCIe (Sec. 4.2 leaves the mechanism open):
+ *   APM_STREAM_DIRECT: no copies and no staging; the update kernel itself reads p, m, v from the
+ *     pinned host pages and writes them back, with `direct_workgroups` wavefronts (0 = a default
+ *     that saturates the link; the rest of the GPU stays free for other work).
+ *   APM_STREAM_STAGED: the pipeline copy-in / update / copy-out through HBM staging slots on
+ *     three streams.  Its staging memory, events and copy streams are set up when the mode is
+ *     first selected: which stream pairs overlap a host-to-device with a device-to-host copy
+ *     depends on the runtime, so short concurrent copies are timed on a few candidate streams
+ *     (the default stream among them) and the best pair is kept; this takes some tens of
+ *     milliseconds and synchronises the device.
+ * Both modes give bit-identical results.  Takes effect from the next apm_streamer_step.
+ * apm_streamer_get_mode returns the current mode (or a negative status).
+ */
+enum apm_stream_mode { APM_STREAM_STAGED = 0, APM_STREAM_DIRECT = 1 };
+int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_workgroups);
+int apm_streamer_get_mode(const apm_streamer* s);
+
+/*
+ * One AdamW step over all pages in use.  Staged mode: for batch b, H2D(b+1) on the copy-in stream
+ * runs beside update(b) on the compute stream and D2H(b-1) on the copy-out stream, ordered by
+ * events.  Direct mode: one reduce pass and one update kernel on the compute stream.
  * The work starts after everything enqueued on `stream` so far, and `stream` is made to wait for
  * the step's completion; the host does not block.  grad_norm / skip_mask as in
  * apm_page_adamw_step (device pointers, one entry per page in use, nullable).
@@ -281,8 +299,9 @@ int apm_streamer_destroy(apm_streamer* s);
 int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, float* grad_norm,
                       uint8_t* skip_mask, void* stream);
 
-/* GB/s the creation-time stream calibration measured on 32 MiB copies: copy-in alone, copy-out
- * alone, and each way with both running on the chosen pair (host pointers, nullable). */
+/* GB/s the staged mode's stream calibration measured on 32 MiB copies (zeros before it ran):
+ * copy-in alone, copy-out alone, and each way with both running on the chosen pair (host
+ * pointers, nullable). */
 int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, double* duplex_each_way);
 
 /*
@@ -295,8 +314,8 @@ int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, do
 int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident);
 
 /*
- * Measurement aid: the same pipeline (streams, events, copy sizes, slot reuse) with the kernels
- * left out.  directions: 1 = copy-in only, 2 = copy-out only, 3 = both.  The data make a round
+ * Measurement aid (staged mode only): the same pipeline (streams, events, copy sizes, slot reuse)
+ * with the kernels left out.  directions: 1 = copy-in only, 2 = copy-out only, 3 = both.  The data make a round
  * trip host -> staging -> host, so the host pool's contents are unchanged (with 2 alone, staging
  * contents left by an earlier step are written back: call it only after 1 or 3, or a full step).
  */

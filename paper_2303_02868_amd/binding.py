@@ -19,6 +19,7 @@ APM_F32, APM_BF16 = 0, 1
 APM_P32, APM_M32, APM_V32, APM_G16, APM_P16, APM_N_STATES = 0, 1, 2, 3, 4, 5
 APM_SKIP_NONE, APM_SKIP_UNTOUCHED = 0, 1
 APM_POOL_NO_ZERO = 1
+APM_STREAM_STAGED, APM_STREAM_DIRECT = 0, 1
 APM_K_REDUCE, APM_K_UPDATE, APM_K_SEGCOPY, APM_N_KERNEL_CLASSES = 0, 1, 2, 3
 ALL_STATES = 0b11111
 FP32_STATES = 0b00111
@@ -29,7 +30,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -108,6 +109,8 @@ def lib() -> C.CDLL:
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_copy_only.argtypes = [vp, i32, vp]
     L.apm_streamer_set_cache.argtypes = [vp, vp, i64]
+    L.apm_streamer_set_mode.argtypes = [vp, i32, i32]
+    L.apm_streamer_get_mode.argtypes = [vp]
     L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
     L.apm_delayed_accumulate.argtypes = [vp, P(i64), i64, vp, vp]
@@ -328,6 +331,16 @@ def apm_streamer_step(s: Streamer, step: int, hyper: apm_hyper, grad_norm=None, 
 def apm_streamer_set_cache(s: Streamer, cache: Optional[Pool], n_resident: int) -> None:
     _check(lib().apm_streamer_set_cache(s.handle, cache.handle if cache else None, n_resident))
     s.cache = cache
+
+
+def apm_streamer_set_mode(s: Streamer, mode: int, direct_workgroups: int = 0) -> None:
+    _check(lib().apm_streamer_set_mode(s.handle, mode, direct_workgroups))
+
+
+def apm_streamer_get_mode(s: Streamer) -> int:
+    m = lib().apm_streamer_get_mode(s.handle)
+    _check(min(m, 0))
+    return m
 
 
 def apm_streamer_probe_rates(s: Streamer):

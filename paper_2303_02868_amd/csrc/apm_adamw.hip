@@ -344,36 +344,14 @@ constexpr int kUpdThreads = APM_UPDATE_THREADS;
 constexpr int kUpdU = APM_UPDATE_U;
 constexpr int kUpdTile = kUpdThreads * 4 * kUpdU;  // elements per workgroup
 
-// Fused update of one slice of one page: 12 B + 2 B read and 12 B + 2 B written per element.
-// Each lane keeps kUpdU 128-bit vectors per fp32 class in flight; every wavefront-wide access is
-// one contiguous 1 KiB (fp32) or 512 B (bf16) span.
-// GATHER / SCATTER: read g from / write p16 to the tenant tensors instead of the page classes.
-template <bool GATHER, bool SCATTER, int SLICES>
-__global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
-    // Prologue: everything a workgroup needs about its page comes with one 32-byte scalar load
-    // (plus the tenant descriptors in gather / scatter mode, fetched alongside).  A workgroup holds
-    // a residency slot without memory traffic until this arrives, so the dependent-load chain is
-    // kept to kernel arguments -> page record.
-    const int64_t i = a.list_offset + blockIdx.y;
-    // the record is fetched as one 32-byte vector so that it stays one load
-    typedef long long i64x4 __attribute__((ext_vector_type(4)));
-    static_assert(sizeof(PageMeta) == sizeof(i64x4), "PageMeta must be 32 bytes");
-    const i64x4 raw = *reinterpret_cast<const i64x4*>(a.meta + i);
-    PageSegs segs{};
-    if (GATHER || SCATTER) segs = a.segs[i];
-    const float scale = __uint_as_float((uint32_t)((uint64_t)raw[0] >> 32));
-    const int used8 = ((int32_t)(uint32_t)raw[0] + 7) & ~7;
-    const int64_t gpage = raw[1];
-    const int64_t spage_ = raw[2];
-    // (Folding the two exits below into the lane predicate, so that all scalar loads of the
-    // prologue issue together, measured 2-3 % slower on the 1.3 B workload and 3 % faster on the
-    // fragmented 124 M one; the early exits stay.)
-    if (scale < 0.0f) return;  // a skipped page
-#pragma unroll 1
-    for (int it = 0; it < SLICES; ++it) {
-    const int start = ((int)blockIdx.x * SLICES + it) * kUpdTile;
-    if (start >= used8) return;  // beyond the extent
-    const int64_t spage = spage_;
+// Fused update of one slice (kUpdTile elements from `start`) of one page by one wavefront:
+// 12 B + 2 B read and 12 B + 2 B written per element.  Each lane keeps kUpdU 128-bit vectors per
+// fp32 class in flight; every wavefront-wide access is one contiguous 1 KiB (fp32) or 512 B (bf16)
+// span.  GATHER / SCATTER: read g from / write p16 to the tenant tensors instead of the page
+// classes.
+template <bool GATHER, bool SCATTER>
+__device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs& segs, float scale,
+                                             int used8, int64_t gpage, int64_t spage, int start) {
     f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
     f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
     f32x4* __restrict__ V = reinterpret_cast<f32x4*>(a.v32 + spage * a.E);
@@ -432,6 +410,56 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
             else __builtin_nontemporal_store(o, P16 + vi);
         }
     }
+}
+
+typedef long long i64x4 __attribute__((ext_vector_type(4)));
+static_assert(sizeof(PageMeta) == sizeof(i64x4), "PageMeta must be 32 bytes");
+
+// The HBM-resident form: grid.y walks the list positions, grid.x the slices (SLICES per
+// workgroup) of a page.
+template <bool GATHER, bool SCATTER, int SLICES>
+__global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
+    // Prologue: everything a workgroup needs about its page comes with one 32-byte scalar load
+    // (plus the tenant descriptors in gather / scatter mode, fetched alongside).  A workgroup holds
+    // a residency slot without memory traffic until this arrives, so the dependent-load chain is
+    // kept to kernel arguments -> page record.
+    const int64_t i = a.list_offset + blockIdx.y;
+    const i64x4 raw = *reinterpret_cast<const i64x4*>(a.meta + i);  // one load for the whole record
+    PageSegs segs{};
+    if (GATHER || SCATTER) segs = a.segs[i];
+    const float scale = __uint_as_float((uint32_t)((uint64_t)raw[0] >> 32));
+    const int used8 = ((int32_t)(uint32_t)raw[0] + 7) & ~7;
+    // (Folding the two exits below into the lane predicate, so that all scalar loads of the
+    // prologue issue together, measured 2-3 % slower on the 1.3 B workload and 3 % faster on the
+    // fragmented 124 M one; the early exits stay.)
+    if (scale < 0.0f) return;  // a skipped page
+#pragma unroll 1
+    for (int it = 0; it < SLICES; ++it) {
+        const int start = ((int)blockIdx.x * SLICES + it) * kUpdTile;
+        if (start >= used8) return;  // beyond the extent
+        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start);
+    }
+}
+
+// The form for fp32 classes that live in pinned host memory and are read and written across
+// PCIe by the kernel itself: a fixed number of wavefronts (the grid) walks all (position, slice)
+// items of `count` list positions with `nx` slices each, consecutive wavefronts taking
+// consecutive slices.  The link needs only some hundred KiB in flight, so a small grid saturates
+// it and leaves the rest of the GPU to other work.
+template <bool GATHER, bool SCATTER>
+__global__ __launch_bounds__(kUpdThreads) void apm_adamw_stride_kernel(UpdateArgs a, int64_t count, int nx) {
+    const int64_t n_items = count * nx;
+#pragma unroll 1
+    for (int64_t w = blockIdx.x; w < n_items; w += gridDim.x) {
+        const int64_t i = a.list_offset + w / nx;
+        const int start = (int)(w % nx) * kUpdTile;
+        const i64x4 raw = *reinterpret_cast<const i64x4*>(a.meta + i);
+        const float scale = __uint_as_float((uint32_t)((uint64_t)raw[0] >> 32));
+        const int used8 = ((int32_t)(uint32_t)raw[0] + 7) & ~7;
+        if (scale < 0.0f || start >= used8) continue;
+        PageSegs segs{};
+        if (GATHER || SCATTER) segs = a.segs[i];
+        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start);
     }
 }
 
@@ -558,6 +586,18 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
     a.E = L.E;
     a.b1 = L.b1; a.omb1 = L.omb1; a.b2 = L.b2; a.omb2 = L.omb2;
     a.inv_sqrt_bc2 = L.inv_sqrt_bc2; a.eps = L.eps; a.step_size = L.step_size; a.lr_wd = L.lr_wd;
+    if (L.stride_workgroups > 0) {
+        return for_each_launch(L, [&](int64_t begin, int64_t ny, int64_t max_used) {
+            a.list_offset = begin;
+            const int nx = (int)((max_used + kUpdTile - 1) / kUpdTile);
+            const int64_t items = ny * nx;
+            const dim3 grid((unsigned)(items < L.stride_workgroups ? items : L.stride_workgroups)), block(kUpdThreads);
+            if (L.gather && L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, true>), grid, block, 0, s, a, ny, nx);
+            else if (L.gather) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, false>), grid, block, 0, s, a, ny, nx);
+            else if (L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<false, true>), grid, block, 0, s, a, ny, nx);
+            else hipLaunchKernelGGL((apm_adamw_stride_kernel<false, false>), grid, block, 0, s, a, ny, nx);
+        });
+    }
     const bool may_skip = L.partials && L.skip_mode == APM_SKIP_UNTOUCHED;
     const int64_t wg_span = (int64_t)kUpdTile * (may_skip ? APM_UPDATE_SLICES_SKIP : 1);
     return for_each_launch(L, [&](int64_t begin, int64_t ny, int64_t max_used) {

@@ -1,11 +1,17 @@
-// Streamed update: fp32 master / momentum / variance pages live in pinned host memory and pass
-// through a small ring of HBM staging slots, copy-in, update and copy-out each on its own stream
-// so that the three overlap (Sec. 4.2: overlap movement with computation; Sec. 5 "Allocator":
-// asynchronous page copies; the update is page-granular by Sec. 4.3's last paragraph).
+// Streamed update: fp32 master / momentum / variance pages live in pinned host memory
+// (Sec. 4.2: overlap movement with computation; Sec. 5 "Allocator": asynchronous page copies; the
+// update is page-granular by Sec. 4.3's last paragraph).  Two ways across PCIe:
+//
+// Staged mode: the pages pass through a small ring of HBM staging slots, copy-in, update and
+// copy-out each on its own stream so that the three overlap.
 //
 // Mixed residency (Sec. 4.2, the GPU cache of optimizer states): the first R pages may keep their
 // fp32 classes in a GPU pool; they are updated in place, in chunks interleaved with the streamed
 // batches on the compute stream, and only pages [R, N) cross PCIe.
+//
+// Direct mode (apm_streamer_set_mode): no staging and no copies at all -- the update kernel reads
+// p, m, v from the pinned host pages and writes them back across PCIe itself, with a small fixed
+// number of wavefronts; the link carries both directions at once inside one kernel.
 //
 // Slot life cycle for batch b (slot = b mod n_slots):
 //   copy-in : wait D2H(b - n_slots) -> H2D p,m,v           -> record h2d[slot]
@@ -30,11 +36,19 @@ struct apm_streamer {
     hipEvent_t ev_start = nullptr, ev_done = nullptr;
     bool in_is_null = false, out_is_null = false;  // a chosen copy stream may be the default stream
     double probe_h2d = 0, probe_d2h = 0, probe_duplex = 0;  // GB/s seen by the stream calibration
+    int mode = APM_STREAM_STAGED;
+    int direct_wgs = 0;         // wavefronts of the direct-mode update kernel
+    float* host_dev[3] = {nullptr, nullptr, nullptr};  // device-side addresses of the host pool's fp32 classes
 };
 
 using namespace apm;
 
 namespace {
+// Wavefronts of the direct-mode kernel when the caller names no number.  Measured on MI355X
+// (PCIe Gen5 x16, GB/s each way, 4 MiB pages): 8 -> 23.7, 16 -> 45.6, 24 -> 42.9, 40 -> 46.1,
+// 56 -> 48.9, 64 -> 49.3, 72 -> 49.3, 96 -> 48.8, 128 -> 48.4, 192 -> 47.4, 256 and more -> 45.4.
+constexpr int kDirectWorkgroups = 64;
+
 void free_streamer(apm_streamer* s) {
     (void)hipDeviceSynchronize();
     if (s->s_in && !s->in_is_null) (void)hipStreamDestroy(s->s_in);
@@ -66,8 +80,7 @@ int pick_copy_streams(apm_streamer* s) {
         (void)hipGetLastError();
         s->s_in = cand[1];
         s->s_out = cand[2];
-        s->s_cmp = cand[3];
-        (void)hipStreamDestroy(cand[4]);
+        for (int k = 3; k <= kNew; ++k) (void)hipStreamDestroy(cand[k]);
         return APM_OK;
     }
     const size_t slot_bytes = (size_t)s->B * (size_t)s->dev->desc.page_elems * sizeof(float);
@@ -109,12 +122,64 @@ int pick_copy_streams(apm_streamer* s) {
     s->s_out = cand[bj];
     s->in_is_null = bi == 0;
     s->out_is_null = bj == 0;
-    for (int k = 1; k <= kNew; ++k) {
-        if (k == bi || k == bj) continue;
-        if (!s->s_cmp) s->s_cmp = cand[k];
-        else (void)hipStreamDestroy(cand[k]);
+    for (int k = 1; k <= kNew; ++k)
+        if (k != bi && k != bj) (void)hipStreamDestroy(cand[k]);
+    return APM_OK;
+}
+
+// Staging slots, the copy streams and the per-slot events: set up when the staged mode is first
+// asked for.
+int ensure_staged(apm_streamer* s) {
+    if (s->stage[0]) return APM_OK;
+    APM_HIP(hipSetDevice(s->dev->desc.hip_device));
+    const size_t bytes = (size_t)s->n_slots * (size_t)s->B * (size_t)s->dev->desc.page_elems * sizeof(float);
+    hipError_t e = hipSuccess;
+    for (int k = 0; k < 3 && e == hipSuccess; ++k) e = hipMalloc((void**)&s->stage[k], bytes);
+    auto undo = [&]() {
+        for (float*& p : s->stage) {
+            if (p) (void)hipFree(p);
+            p = nullptr;
+        }
+    };
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        undo();
+        return fail(APM_ENOMEM, "allocating 3 x %zu bytes of staging slots failed: %s", bytes, hipGetErrorString(e));
+    }
+    if (!s->s_in) {
+        int rc = pick_copy_streams(s);
+        if (rc != APM_OK) { undo(); return rc; }
+    }
+    auto mk_event = [&](hipEvent_t* ev) { return *ev ? hipSuccess : hipEventCreateWithFlags(ev, hipEventDisableTiming); };
+    s->ev_h2d.resize((size_t)s->n_slots, nullptr);
+    s->ev_cmp.resize((size_t)s->n_slots, nullptr);
+    s->ev_d2h.resize((size_t)s->n_slots, nullptr);
+    for (int k = 0; k < s->n_slots && e == hipSuccess; ++k) {
+        e = mk_event(&s->ev_h2d[(size_t)k]);
+        if (e == hipSuccess) e = mk_event(&s->ev_cmp[(size_t)k]);
+        if (e == hipSuccess) e = mk_event(&s->ev_d2h[(size_t)k]);
+    }
+    if (e != hipSuccess) {
+        undo();
+        return fail(APM_EDEVICE, "creating events failed: %s", hipGetErrorString(e));
     }
     return APM_OK;
+}
+
+// Device-side addresses of the host pool's fp32 classes (pinned memory is mapped into the GPU's
+// address space); false if the memory cannot be addressed from the GPU.
+bool map_host_classes(apm_streamer* s) {
+    if (s->host_dev[0]) return true;
+    const int states[3] = {APM_P32, APM_M32, APM_V32};
+    float* p[3];
+    for (int k = 0; k < 3; ++k) {
+        if (hipHostGetDevicePointer((void**)&p[k], s->host->base[states[k]], 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+    }
+    for (int k = 0; k < 3; ++k) s->host_dev[k] = p[k];
+    return true;
 }
 
 }  // namespace
@@ -132,32 +197,19 @@ extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool*
     APM_HIP(hipSetDevice(dev->desc.hip_device));
     apm_streamer* s = new apm_streamer();
     s->host = host; s->dev = dev; s->B = batch_pages; s->n_slots = n_slots;
-    const size_t bytes = (size_t)n_slots * (size_t)batch_pages * (size_t)dev->desc.page_elems * sizeof(float);
-    hipError_t e = hipSuccess;
-    for (int k = 0; k < 3 && e == hipSuccess; ++k) e = hipMalloc((void**)&s->stage[k], bytes);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        free_streamer(s);
-        return fail(APM_ENOMEM, "allocating 3 x %zu bytes of staging slots failed: %s", bytes, hipGetErrorString(e));
-    }
-    auto mk_event = [&](hipEvent_t* ev) { return hipEventCreateWithFlags(ev, hipEventDisableTiming); };
-    int rc_pick = pick_copy_streams(s);
-    if (rc_pick != APM_OK) { free_streamer(s); return rc_pick; }
-    s->ev_h2d.assign((size_t)n_slots, nullptr);
-    s->ev_cmp.assign((size_t)n_slots, nullptr);
-    s->ev_d2h.assign((size_t)n_slots, nullptr);
-    for (int k = 0; k < n_slots && e == hipSuccess; ++k) {
-        e = mk_event(&s->ev_h2d[(size_t)k]);
-        if (e == hipSuccess) e = mk_event(&s->ev_cmp[(size_t)k]);
-        if (e == hipSuccess) e = mk_event(&s->ev_d2h[(size_t)k]);
-    }
-    if (e == hipSuccess) e = mk_event(&s->ev_start);
-    if (e == hipSuccess) e = mk_event(&s->ev_done);
+    s->direct_wgs = kDirectWorkgroups;
+    hipError_t e = hipStreamCreateWithFlags(&s->s_cmp, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_start, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_done, hipEventDisableTiming);
     if (e != hipSuccess) {
         free_streamer(s);
         return fail(APM_EDEVICE, "creating streams/events failed: %s", hipGetErrorString(e));
     }
     int rc = ensure_scratch(dev);
+    if (rc == APM_OK) {
+        if (map_host_classes(s)) s->mode = APM_STREAM_DIRECT;
+        else { s->mode = APM_STREAM_STAGED; rc = ensure_staged(s); }
+    }
     if (rc != APM_OK) { free_streamer(s); return rc; }
     *out = s;
     return APM_OK;
@@ -191,10 +243,14 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     const int64_t E = dev->desc.page_elems;
     const size_t pb = (size_t)E * sizeof(float);
 
+    const bool direct = s->mode == APM_STREAM_DIRECT;
+    if (direct && !(what & kDoUpdate)) return fail(APM_ESTATE, "the copy-only measurement belongs to the staged mode; this streamer is in direct mode");
     APM_HIP(hipEventRecord(s->ev_start, caller));
-    APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
     APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_start, 0));
-    APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
+    if (!direct) {
+        APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
+        APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
+    }
 
     L.g16 = static_cast<const uint16_t*>(dev->base[APM_G16]);
     L.p16 = static_cast<uint16_t*>(dev->base[APM_P16]);
@@ -212,6 +268,34 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     }
     const int states[3] = {APM_P32, APM_M32, APM_V32};
     const int64_t R = s->cache ? (s->R < N ? s->R : N) : 0;
+    if (direct) {
+        for (int part = 0; part < 2; ++part) {  // resident pages first (HBM speed), then the host pages
+            AdamwLaunch C = L;
+            const int64_t first = part == 0 ? 0 : R;
+            const int64_t n = part == 0 ? R : N - R;
+            if (n == 0) continue;
+            if (part == 0) {
+                C.p32 = static_cast<float*>(s->cache->base[APM_P32]);
+                C.m32 = static_cast<float*>(s->cache->base[APM_M32]);
+                C.v32 = static_cast<float*>(s->cache->base[APM_V32]);
+            } else {
+                C.p32 = s->host_dev[0];
+                C.m32 = s->host_dev[1];
+                C.v32 = s->host_dev[2];
+                C.stride_workgroups = s->direct_wgs;
+            }
+            C.state_first = C.grad_first = first;
+            C.n_listed = n;
+            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+            if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
+            else APM_HIP(launch_prepare(C, s->s_cmp));
+            APM_HIP(launch_adamw(C, s->s_cmp));
+        }
+        APM_HIP(hipEventRecord(s->ev_done, s->s_cmp));
+        APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
+        return APM_OK;
+    }
     const int64_t n_batches = (N - R + s->B - 1) / s->B;
     // resident pages are updated in n_batches chunks (one chunk if nothing is streamed)
     const int64_t chunk = n_batches > 0 ? (R + n_batches - 1) / n_batches : R;
@@ -304,6 +388,27 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
                                  float* grad_norm, uint8_t* skip_mask, void* stream) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+}
+
+extern "C" int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_workgroups) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    if (mode != APM_STREAM_STAGED && mode != APM_STREAM_DIRECT) return fail(APM_EINVAL, "unknown streamer mode %d", mode);
+    if (direct_workgroups < 0 || direct_workgroups > (1 << 20)) return fail(APM_EINVAL, "direct_workgroups out of range");
+    APM_HIP(hipSetDevice(s->dev->desc.hip_device));
+    if (mode == APM_STREAM_DIRECT) {
+        if (!map_host_classes(s)) return fail(APM_EDEVICE, "the host pool's memory is not mapped into the GPU's address space (not pinned?)");
+        s->direct_wgs = direct_workgroups > 0 ? direct_workgroups : kDirectWorkgroups;
+    } else {
+        int rc = ensure_staged(s);
+        if (rc != APM_OK) return rc;
+    }
+    s->mode = mode;
+    return APM_OK;
+}
+
+extern "C" int apm_streamer_get_mode(const apm_streamer* s) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    return s->mode;
 }
 
 extern "C" int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, double* duplex_each_way) {

@@ -23,6 +23,19 @@ def host_view(pool, state, n_pages, E):
     return np.frombuffer(buf, dtype=np.float32).reshape(n_pages, E)
 
 
+def set_mode(streamer, mode):
+    """"staged" | "direct" | "direct:<wavefronts>" (a small odd count makes every wavefront stride
+    over many pages and slices)."""
+    if mode.startswith("direct"):
+        n = int(mode.split(":")[1]) if ":" in mode else 0
+        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT, n)
+        assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_DIRECT
+    else:
+        assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_DIRECT   # pinned pool: the default
+        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_STAGED)
+        assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_STAGED
+
+
 def test_page_copy_roundtrip_bit_exact():
     E, n = 8192, 10
     dp = DevicePool(n, E)
@@ -47,8 +60,9 @@ def test_page_copy_roundtrip_bit_exact():
     dp.destroy()
 
 
-@pytest.mark.parametrize("batch,slots,clip", [(4, 2, 0.0), (7, 3, 1.0), (64, 2, 1.0)])
-def test_streamed_equals_resident_bit_exact(batch, slots, clip):
+@pytest.mark.parametrize("batch,slots,clip,mode", [(4, 2, 0.0, "staged"), (7, 3, 1.0, "staged"), (64, 2, 1.0, "staged"),
+                                                   (4, 2, 0.0, "direct"), (4, 2, 1.0, "direct:7")])
+def test_streamed_equals_resident_bit_exact(batch, slots, clip, mode):
     # a GPT-2-small-sized model: resident run vs. fp32 state in pinned host pages streamed through
     # `slots` staging slots of `batch` pages
     f, E = synth.WORKLOADS["gpt2_small_124m"]
@@ -66,6 +80,7 @@ def test_streamed_equals_resident_bit_exact(batch, slots, clip):
     # initial master parameters reach the host pool by page copies from the resident pool
     apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
     st = apm.apm_streamer_create(host, dev.pool, batch, slots)
+    set_mode(st, mode)
     norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     for t in range(1, steps + 1):
@@ -86,8 +101,8 @@ def test_streamed_equals_resident_bit_exact(batch, slots, clip):
     res.destroy()
 
 
-@pytest.mark.parametrize("frac", [0.0, 0.35, 1.0])
-def test_mixed_residency_equals_resident_bit_exact(frac):
+@pytest.mark.parametrize("frac,mode", [(0.0, "staged"), (0.35, "staged"), (1.0, "staged"), (0.35, "direct"), (1.0, "direct")])
+def test_mixed_residency_equals_resident_bit_exact(frac, mode):
     # the first R pages keep their fp32 state in an HBM cache pool, the rest is streamed
     f, E = synth.WORKLOADS["gpt2_small_124m"]
     model = Model(f(), E, seed=2)
@@ -109,6 +124,7 @@ def test_mixed_residency_equals_resident_bit_exact(frac):
         hv[:R] = np.nan
     st = apm.apm_streamer_create(host, dev.pool, 16, 3)
     apm.apm_streamer_set_cache(st, cache.pool if R else None, R)
+    set_mode(st, mode)
     norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     for t in range(1, 4):
@@ -173,6 +189,8 @@ def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
     for t in range(1, 4):
         g = model.grad_flat(t)
         apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        # the middle step crosses PCIe from inside the update kernel, the others through staging
+        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT if t == 2 else apm.APM_STREAM_STAGED)
         apm.apm_streamer_step(streamer, t, hy, norm_d, None)
         norms, _ = st.step(model.host_pages(g, sample), t, h, threads=HOST_THREADS)
         torch.cuda.synchronize()
