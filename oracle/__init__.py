@@ -9,3 +9,4 @@ from .adamw import Hyper, bf16_rne, bf16_bits_to_f64, page_reduce, page_adamw, P
 from .packer import plan_pack, pack, unpack, PackPlan, Segment, PageEntry  # noqa: F401
 from .delayed import DelayedStepper  # noqa: F401
 from .footprint import layer_footprint_bytes, model_state_bytes_per_param  # noqa: F401
+from . import scheduler  # noqa: F401
