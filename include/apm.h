@@ -321,6 +321,46 @@ int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident)
  */
 int apm_streamer_copy_only(apm_streamer* s, int directions, void* stream);
 
+/* ---- life-time based scheduling of page movement (Alg. 1, phase 1) ------------------------- */
+
+/*
+ * A task of the schedule (Alg. 1's {operation, page, trigger_id}): target is a page id for
+ * APM_TASK_MOVE_TO_GPU and a layer index for APM_TASK_COMPUTE; trigger_id is the logical id (layer
+ * index) at which the task is issued.  Tasks run in list order; a movement task that follows a
+ * compute task in the list may use memory that compute released.
+ */
+enum apm_task_op { APM_TASK_MOVE_TO_GPU = 0, APM_TASK_COMPUTE = 1 };
+typedef struct apm_task {
+    int32_t op;
+    int32_t trigger_id;
+    int64_t target;
+} apm_task;
+
+/*
+ * Host-only planner.  The model is n_layers layers in execution order; layer i first accesses the
+ * pages layer_pages[layer_offsets[i] .. layer_offsets[i+1]) (every page id in [0, n_pages) in
+ * exactly one layer) and needs layer_bytes[i] bytes besides its pages while it computes.  The trace
+ * is last_access[page] = index of the layer that accesses the page last, after whose compute the
+ * page's GPU memory is free again (NULL: the page's own layer).
+ * Phase 1 of Alg. 1: all movement tasks are put first; per layer, movement tasks are taken off the
+ * end of the schedule while less than layer_bytes[i] would be left, the compute is appended, and
+ * deferred pages are put back, earliest needed first, while more than one page of memory is left.
+ * Readings where the listing is silent: a page of layer i still deferred when i's turn comes is
+ * moved then (trigger i); a layer that cannot fit even with all later pages deferred is an error.
+ * Phase 2 re-times all_gather tasks only and has nothing to do on one GPU.
+ *
+ * All pointers are host pointers.  tasks: capacity *n_tasks on entry, count (n_pages + n_layers)
+ * on return (NULL with *n_tasks == 0 queries the count); peak_bytes (nullable): the largest
+ * resident pages + layer_bytes over all computes.
+ * Errors: APM_EINVAL (malformed arrays, a page in two layers, last_access before the page's own
+ * layer), APM_ERANGE (page id out of range; task buffer too small), APM_ENOMEM (some layer does
+ * not fit into gpu_memory_bytes; the message names it).
+ */
+int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* layer_pages,
+                      const int64_t* layer_bytes, int64_t n_layers, const int64_t* last_access,
+                      int64_t n_pages, int64_t page_bytes, int64_t gpu_memory_bytes,
+                      apm_task* tasks, int64_t* n_tasks, int64_t* peak_bytes);
+
 /* ---- one-step-stale update (Alg. 2 reduced to one GPU: apply the buffered gradient while the
  *      next one is being staged) -------------------------------------------------------------- */
 

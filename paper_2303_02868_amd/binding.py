@@ -30,7 +30,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_schedule_plan", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -58,6 +58,13 @@ class apm_page_info(C.Structure):
     _fields_ = [("total_elems", C.c_int64), ("used_elems", C.c_int64),
                 ("available_elems", C.c_int64), ("device", C.c_int32), ("n_tensors", C.c_int32),
                 ("tensor_id", C.c_int64 * 2), ("tensor_elems", C.c_int64 * 2)]
+
+
+class apm_task(C.Structure):
+    _fields_ = [("op", C.c_int32), ("trigger_id", C.c_int32), ("target", C.c_int64)]
+
+
+APM_TASK_MOVE_TO_GPU, APM_TASK_COMPUTE = 0, 1
 
 
 class apm_hyper(C.Structure):
@@ -104,6 +111,7 @@ def lib() -> C.CDLL:
     L.apm_page_adamw_step_fused.argtypes = [vp, P(i64), i64, i64, P(apm_hyper), P(apm_tensor),
                                             P(apm_tensor), i64, vp, vp, vp]
     L.apm_page_copy_async.argtypes = [vp, i64, vp, i64, i64, i32, vp]
+    L.apm_schedule_plan.argtypes = [P(i64), P(i64), P(i64), i64, P(i64), i64, i64, i64, P(apm_task), P(i64), P(i64)]
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
@@ -310,6 +318,26 @@ class Streamer:
             self.destroy()
         except Exception:
             pass
+
+
+def apm_schedule_plan(layers: Sequence, last_access: Optional[Sequence[int]], page_bytes: int,
+                      gpu_memory_bytes: int):
+    """layers: sequence of (page_list, bytes).  Returns ([(op, target, trigger_id), ...], peak_bytes)."""
+    offsets, pages, sizes = [0], [], []
+    for page_list, nbytes in layers:
+        pages.extend(int(p) for p in page_list)
+        offsets.append(len(pages))
+        sizes.append(int(nbytes))
+    off_a, _ = _i64_array(offsets)
+    pg_a, n_pages = _i64_array(pages)
+    sz_a, n_layers = _i64_array(sizes)
+    la_a = _i64_array(last_access)[0] if last_access is not None else None
+    cap = n_pages + n_layers
+    tasks = (apm_task * max(1, cap))()
+    n_tasks, peak = C.c_int64(cap), C.c_int64(0)
+    _check(lib().apm_schedule_plan(off_a, pg_a, sz_a, n_layers, la_a, n_pages, page_bytes, gpu_memory_bytes,
+                                   tasks, C.byref(n_tasks), C.byref(peak)))
+    return [(tasks[i].op, tasks[i].target, tasks[i].trigger_id) for i in range(n_tasks.value)], peak.value
 
 
 def apm_streamer_create(host: Pool, dev: Pool, batch_pages: int, n_slots: int) -> Streamer:

@@ -88,3 +88,72 @@ def test_gpu_calls_fail_cleanly_without_a_gpu():
     out = ctypes.c_void_p()
     assert L.apm_pool_create(ctypes.byref(out), ctypes.byref(bad)) == apm.APM_EINVAL   # page_elems 0
     assert out.value is None
+
+
+# ---- the scheduler planner (host-only, Alg. 1 phase 1): bit-exact against the oracle ------------
+
+def _oracle_schedule(layers, last_access, page_bytes, memory):
+    from oracle import scheduler as sch
+    model = [sch.Layer(list(pl), sz) for pl, sz in layers]
+    traces = ({p: i for i, l in enumerate(model) for p in l.page_list} if last_access is None
+              else {p: la for p, la in enumerate(last_access)})
+    S = sch.schedule(model, traces, memory, page_bytes)
+    return [(apm.APM_TASK_MOVE_TO_GPU if t.operation == sch.MOVE_TO_GPU else apm.APM_TASK_COMPUTE,
+             t.target, t.trigger_id) for t in S]
+
+
+@pytest.mark.parametrize("reuse", [False, True])
+def test_schedule_plan_equals_oracle_on_random_traces(reuse):
+    import random
+    from oracle import scheduler as sch
+    rng = random.Random(11 + reuse)
+    n_ok = n_oom = 0
+    for _ in range(400):
+        n_layers = rng.randint(1, 9)
+        ids = list(range(rng.randint(0, 24)))
+        rng.shuffle(ids)                                   # page ids need not be in layer order
+        cuts = sorted(rng.randint(0, len(ids)) for _ in range(n_layers - 1))
+        lists = [ids[a:b] for a, b in zip([0] + cuts, cuts + [len(ids)])]
+        layers = [(pl, rng.randint(0, 9)) for pl in lists]
+        last = None
+        if reuse:
+            own = {p: i for i, (pl, _) in enumerate(layers) for p in pl}
+            last = [rng.randint(own[p], n_layers - 1) if rng.random() < 0.3 else own[p] for p in range(len(ids))]
+        page_bytes, memory = rng.choice([1, 4]), rng.randint(0, 60)
+        try:
+            want = _oracle_schedule(layers, last, page_bytes, memory)
+        except sch.OutOfMemory:
+            with pytest.raises(apm.ApmError) as e:
+                apm.apm_schedule_plan(layers, last, page_bytes, memory)
+            assert e.value.code == apm.APM_ENOMEM
+            n_oom += 1
+            continue
+        got, peak = apm.apm_schedule_plan(layers, last, page_bytes, memory)
+        assert got == want
+        assert peak <= memory
+        n_ok += 1
+    assert n_ok > 80 and n_oom > 80
+
+
+def test_schedule_plan_on_a_model_sized_trace_and_its_errors():
+    from oracle import scheduler as sch
+    # the 1.3 B shape, one "layer" per transformer block: 1449 pages of 12 MiB (p, m, v)
+    f, E = synth.WORKLOADS["gpt_1p3b"]
+    plan = oracle.plan_pack([t.numel for t in f()], E)
+    n = plan.n_pages
+    per = -(-n // 26)
+    layers = [(list(range(a, min(a + per, n))), 0) for a in range(0, n, per)]
+    page_bytes = 12 * E
+    got, peak = apm.apm_schedule_plan(layers, None, page_bytes, 192 * page_bytes)
+    assert got == _oracle_schedule(layers, None, page_bytes, 192 * page_bytes)
+    assert peak <= 192 * page_bytes and len(got) == n + len(layers)
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_schedule_plan(layers, None, page_bytes, (per - 1) * page_bytes)
+    assert e.value.code == apm.APM_ENOMEM and "layer 0" in str(e.value)
+    with pytest.raises(apm.ApmError) as e:                      # a page in two layers
+        apm.apm_schedule_plan([([0, 1], 0), ([1], 0)], None, 1, 10)
+    assert e.value.code == apm.APM_EINVAL
+    with pytest.raises(apm.ApmError) as e:                      # last access before the first
+        apm.apm_schedule_plan([([0], 0), ([1], 0)], [0, 0], 1, 10)
+    assert e.value.code == apm.APM_EINVAL
+    assert apm.apm_schedule_plan([], None, 1, 0) == ([], 0)
