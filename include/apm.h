@@ -361,6 +361,28 @@ int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* layer_pages,
                       int64_t n_pages, int64_t page_bytes, int64_t gpu_memory_bytes,
                       apm_task* tasks, int64_t* n_tasks, int64_t* peak_bytes);
 
+/*
+ * One AdamW step over all pages in use, with the page movement driven by a schedule (the task
+ * list of apm_schedule_plan, or any list that passes the checks below) instead of the staged
+ * mode's fixed slot ring.  The model's layers are consecutive page ranges: layer i owns pages
+ * [layer_first_page[i], layer_first_page[i+1]) (n_layers + 1 host entries, from 0 to the number of
+ * pages in use), and every page is accessed by its own layer only (the optimizer pass).  The GPU
+ * memory of the schedule is the streamer's staging memory: n_slots * batch_pages page slots of
+ * 12 * page_elems bytes (p, m, v).  APM_TASK_MOVE_TO_GPU copies a page's fp32 classes from the
+ * host pool into the lowest free slot; APM_TASK_COMPUTE runs the reduce and update kernels on its
+ * layer's pages, copies them back to the host pool and frees their slots.  Movement tasks over
+ * consecutive pages and slots are merged into one copy per class.
+ * The schedule is replayed on the host first and nothing is enqueued if it is unsound:
+ * APM_ENOMEM (a movement task finds no free slot), APM_ESTATE (a layer computes before all its
+ * pages were moved; a resident cache is set), APM_EINVAL (layers out of order, a page moved twice,
+ * pages or layers left over).  Results are bit-identical to the other modes.  Stream semantics as
+ * apm_streamer_step; does not depend on the streamer's mode.
+ */
+int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
+                                const int64_t* layer_first_page, int64_t n_layers, int64_t step,
+                                const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,
+                                void* stream);
+
 /* ---- one-step-stale update (Alg. 2 reduced to one GPU: apply the buffered gradient while the
  *      next one is being staged) -------------------------------------------------------------- */
 

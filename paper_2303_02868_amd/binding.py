@@ -30,7 +30,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_schedule_plan", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_schedule_plan", "apm_streamer_step_scheduled", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -112,6 +112,7 @@ def lib() -> C.CDLL:
                                             P(apm_tensor), i64, vp, vp, vp]
     L.apm_page_copy_async.argtypes = [vp, i64, vp, i64, i64, i32, vp]
     L.apm_schedule_plan.argtypes = [P(i64), P(i64), P(i64), i64, P(i64), i64, i64, i64, P(apm_task), P(i64), P(i64)]
+    L.apm_streamer_step_scheduled.argtypes = [vp, P(apm_task), i64, P(i64), i64, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
@@ -354,6 +355,17 @@ def apm_streamer_step(s: Streamer, step: int, hyper: apm_hyper, grad_norm=None, 
                       stream=None) -> None:
     _check(lib().apm_streamer_step(s.handle, step, C.byref(hyper), _ptr(grad_norm),
                                    _ptr(skip_mask), _stream(stream)))
+
+
+def apm_streamer_step_scheduled(s: Streamer, tasks: Sequence, layer_first_page: Sequence[int], step: int,
+                                hyper: apm_hyper, grad_norm=None, skip_mask=None, stream=None) -> None:
+    """tasks: [(op, target, trigger_id), ...] as apm_schedule_plan returns them."""
+    arr = (apm_task * max(1, len(tasks)))()
+    for i, (op, target, trig) in enumerate(tasks):
+        arr[i].op, arr[i].target, arr[i].trigger_id = op, target, trig
+    lf, n1 = _i64_array(layer_first_page)
+    _check(lib().apm_streamer_step_scheduled(s.handle, arr, len(tasks), lf, n1 - 1, step, C.byref(hyper),
+                                             _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
 
 
 def apm_streamer_set_cache(s: Streamer, cache: Optional[Pool], n_resident: int) -> None:

@@ -19,6 +19,7 @@
 //   copy-out: wait cmp[slot]        -> D2H p,m,v            -> record d2h[slot]
 // Streams are in order, so these three edges are the only synchronisation needed.  The host
 // enqueues copy-in one batch ahead of the matching update and copy-out.
+#include <algorithm>
 #include <chrono>
 
 #include "apm_internal.h"
@@ -39,6 +40,7 @@ struct apm_streamer {
     int mode = APM_STREAM_STAGED;
     int direct_wgs = 0;         // wavefronts of the direct-mode update kernel
     float* host_dev[3] = {nullptr, nullptr, nullptr};  // device-side addresses of the host pool's fp32 classes
+    std::vector<hipEvent_t> sched_ev;  // events of the scheduled step, grown on demand and reused
 };
 
 using namespace apm;
@@ -54,7 +56,7 @@ void free_streamer(apm_streamer* s) {
     if (s->s_in && !s->in_is_null) (void)hipStreamDestroy(s->s_in);
     if (s->s_out && !s->out_is_null) (void)hipStreamDestroy(s->s_out);
     if (s->s_cmp) (void)hipStreamDestroy(s->s_cmp);
-    for (auto* v : {&s->ev_h2d, &s->ev_cmp, &s->ev_d2h})
+    for (auto* v : {&s->ev_h2d, &s->ev_cmp, &s->ev_d2h, &s->sched_ev})
         for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     if (s->ev_start) (void)hipEventDestroy(s->ev_start);
     if (s->ev_done) (void)hipEventDestroy(s->ev_done);
@@ -432,6 +434,193 @@ extern "C" int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t 
     if (n_resident < 0 || n_resident > cache->desc.n_pages) return fail(APM_ERANGE, "n_resident %lld exceeds the cache pool's %lld pages", (long long)n_resident, (long long)cache->desc.n_pages);
     s->cache = cache;
     s->R = n_resident;
+    return APM_OK;
+}
+
+// One step driven by a schedule (Alg. 1's task list) instead of the fixed slot ring.  The staging
+// memory is the GPU memory the schedule was planned for, one page slot per page; a movement task
+// takes the lowest free slot, a compute task updates its layer's pages where they sit, writes them
+// back and frees their slots.  The whole schedule is checked on the host before anything is
+// enqueued.  Cross-stream edges: a copy-in waits for the write-back that freed its slots, a
+// compute for the copy-ins of its pages, a write-back for its compute.
+extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
+                                           const int64_t* layer_first_page, int64_t n_layers,
+                                           int64_t step, const apm_hyper* hyper, float* grad_norm,
+                                           uint8_t* skip_mask, void* stream) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    if (n_tasks < 0 || n_layers < 0 || (n_tasks > 0 && !tasks) || !layer_first_page) return fail(APM_EINVAL, "bad task or layer arrays");
+    apm_pool* dev = s->dev;
+    apm_pool* host = s->host;
+    if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+    const int64_t N = (int64_t)dev->plan.pages.size();
+    if (layer_first_page[0] != 0 || layer_first_page[n_layers] != N) return fail(APM_EINVAL, "the layers must cover pages [0, %lld) in order", (long long)N);
+    for (int64_t i = 0; i < n_layers; ++i)
+        if (layer_first_page[i + 1] < layer_first_page[i]) return fail(APM_EINVAL, "layer_first_page must not decrease");
+    if (s->cache) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache");
+    AdamwLaunch L{};
+    int rc = prepare_hyper(hyper, step, &L);
+    if (rc != APM_OK) return rc;
+    rc = ensure_staged(s);
+    if (rc != APM_OK) return rc;
+    APM_HIP(hipSetDevice(dev->desc.hip_device));
+
+    // ---- pass 1 (host only): replay the schedule against the slots -------------------------
+    const int64_t n_slots = (int64_t)s->n_slots * s->B;
+    std::vector<int64_t> slot_of((size_t)N, -1);
+    std::vector<uint8_t> moved((size_t)N, 0);
+    std::vector<int64_t> free_slots((size_t)n_slots);  // min-heap: the lowest free slot first keeps runs together
+    for (int64_t k = 0; k < n_slots; ++k) free_slots[(size_t)k] = k;
+    auto cmp = [](int64_t a, int64_t b) { return a > b; };
+    std::make_heap(free_slots.begin(), free_slots.end(), cmp);
+    std::vector<int64_t> slot_seq((size_t)N, -1);  // slot given to each movement task, by page
+    int64_t next_layer = 0, n_moves = 0;
+    for (int64_t k = 0; k < n_tasks; ++k) {
+        const apm_task& t = tasks[k];
+        if (t.op == APM_TASK_MOVE_TO_GPU) {
+            if (t.target < 0 || t.target >= N) return fail(APM_ERANGE, "task %lld moves page %lld, out of range", (long long)k, (long long)t.target);
+            if (moved[(size_t)t.target]) return fail(APM_EINVAL, "task %lld moves page %lld a second time", (long long)k, (long long)t.target);
+            if (free_slots.empty()) return fail(APM_ENOMEM, "task %lld: the schedule needs more than the %lld staging page slots", (long long)k, (long long)n_slots);
+            std::pop_heap(free_slots.begin(), free_slots.end(), cmp);
+            slot_seq[(size_t)t.target] = slot_of[(size_t)t.target] = free_slots.back();
+            free_slots.pop_back();
+            moved[(size_t)t.target] = 1;
+            ++n_moves;
+        } else if (t.op == APM_TASK_COMPUTE) {
+            if (t.target != next_layer) return fail(APM_EINVAL, "task %lld computes layer %lld, expected layer %lld", (long long)k, (long long)t.target, (long long)next_layer);
+            for (int64_t p = layer_first_page[next_layer]; p < layer_first_page[next_layer + 1]; ++p) {
+                if (slot_of[(size_t)p] < 0) return fail(APM_ESTATE, "task %lld computes layer %lld before its page %lld was moved", (long long)k, (long long)next_layer, (long long)p);
+                free_slots.push_back(slot_of[(size_t)p]);
+                std::push_heap(free_slots.begin(), free_slots.end(), cmp);
+                slot_of[(size_t)p] = -1;
+            }
+            ++next_layer;
+        } else {
+            return fail(APM_EINVAL, "task %lld has unknown operation %d", (long long)k, t.op);
+        }
+    }
+    if (next_layer != n_layers || n_moves != N) return fail(APM_EINVAL, "the schedule computes %lld of %lld layers and moves %lld of %lld pages", (long long)next_layer, (long long)n_layers, (long long)n_moves, (long long)N);
+
+    // ---- pass 2: enqueue --------------------------------------------------------------------
+    hipStream_t caller = static_cast<hipStream_t>(stream);
+    const int64_t E = dev->desc.page_elems;
+    const size_t pb = (size_t)E * sizeof(float);
+    const int states[3] = {APM_P32, APM_M32, APM_V32};
+    size_t ev_used = 0;
+    auto new_event = [&](hipEvent_t* out) -> int {
+        if (ev_used == s->sched_ev.size()) {
+            hipEvent_t e = nullptr;
+            APM_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            s->sched_ev.push_back(e);
+        }
+        *out = s->sched_ev[ev_used++];
+        return APM_OK;
+    };
+    APM_HIP(hipEventRecord(s->ev_start, caller));
+    APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
+    APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_start, 0));
+    APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
+
+    // the slot of every page, for the kernels (fp32 classes are addressed by slot, 16-bit ones by page)
+    {
+        int slot;
+        rc = dev->ring.acquire((size_t)N * sizeof(int64_t), &slot);
+        if (rc != APM_OK) return rc;
+        int64_t* h = static_cast<int64_t*>(dev->ring.h[slot]);
+        for (int64_t p = 0; p < N; ++p) h[p] = slot_seq[(size_t)p];
+        rc = dev->ring.commit(slot, (size_t)N * sizeof(int64_t), s->s_cmp);
+        if (rc != APM_OK) return rc;
+        L.state_pages = static_cast<const int64_t*>(dev->ring.d[slot]);
+    }
+    L.g16 = static_cast<const uint16_t*>(dev->base[APM_G16]);
+    L.p16 = static_cast<uint16_t*>(dev->base[APM_P16]);
+    L.used = dev->d_used;
+    L.E = E;
+    L.S = dev->S;
+    L.p32 = s->stage[0];
+    L.m32 = s->stage[1];
+    L.v32 = s->stage[2];
+    L.meta = dev->d_meta;
+    const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
+    if (need_reduce) {
+        L.partials = dev->d_partials;
+        L.nzflags = dev->d_nzflags;
+    }
+    const int64_t* d_slots = L.state_pages;
+
+    std::vector<hipEvent_t> slot_free((size_t)n_slots, nullptr);  // write-back that last freed the slot
+    std::vector<hipEvent_t> page_in((size_t)N, nullptr);          // copy-in that brought the page
+    int64_t k = 0;
+    while (k < n_tasks) {
+        if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
+            // a run of movement tasks over consecutive pages and consecutive slots is one copy per class
+            const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
+            int64_t n = 1;
+            while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
+                   slot_seq[(size_t)(p0 + n)] == s0 + n)
+                ++n;
+            hipEvent_t last_wait = nullptr;
+            for (int64_t j = 0; j < n; ++j) {
+                hipEvent_t w = slot_free[(size_t)(s0 + j)];
+                if (w && w != last_wait) {
+                    APM_HIP(hipStreamWaitEvent(s->s_in, w, 0));
+                    last_wait = w;
+                }
+            }
+            for (int c = 0; c < 3; ++c) {
+                const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
+                APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s->s_in));
+            }
+            hipEvent_t done;
+            rc = new_event(&done);
+            if (rc != APM_OK) return rc;
+            APM_HIP(hipEventRecord(done, s->s_in));
+            for (int64_t j = 0; j < n; ++j) page_in[(size_t)(p0 + j)] = done;
+            k += n;
+            continue;
+        }
+        const int64_t i = tasks[k].target;
+        const int64_t first = layer_first_page[i], n = layer_first_page[i + 1] - first;
+        ++k;
+        if (n == 0) continue;
+        hipEvent_t last_wait = nullptr;
+        for (int64_t j = 0; j < n; ++j) {
+            hipEvent_t w = page_in[(size_t)(first + j)];
+            if (w != last_wait) {
+                APM_HIP(hipStreamWaitEvent(s->s_cmp, w, 0));
+                last_wait = w;
+            }
+        }
+        AdamwLaunch C = L;
+        C.state_pages = d_slots + first;
+        C.grad_first = first;
+        C.n_listed = n;
+        C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+        C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+        if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
+        else APM_HIP(launch_prepare(C, s->s_cmp));
+        APM_HIP(launch_adamw(C, s->s_cmp));
+        hipEvent_t computed, written;
+        rc = new_event(&computed);
+        if (rc == APM_OK) rc = new_event(&written);
+        if (rc != APM_OK) return rc;
+        APM_HIP(hipEventRecord(computed, s->s_cmp));
+        APM_HIP(hipStreamWaitEvent(s->s_out, computed, 0));
+        for (int64_t j = 0; j < n;) {  // write back in runs of consecutive slots
+            const int64_t s0 = slot_seq[(size_t)(first + j)];
+            int64_t m = 1;
+            while (j + m < n && slot_seq[(size_t)(first + j + m)] == s0 + m) ++m;
+            for (int c = 0; c < 3; ++c) {
+                char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)(first + j) * pb;
+                APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * (size_t)m, hipMemcpyDeviceToHost, s->s_out));
+            }
+            j += m;
+        }
+        APM_HIP(hipEventRecord(written, s->s_out));
+        for (int64_t j = 0; j < n; ++j) slot_free[(size_t)slot_seq[(size_t)(first + j)]] = written;
+    }
+    // every copy-in feeds a compute and every compute a write-back: the copy-out stream ends last
+    APM_HIP(hipEventRecord(s->ev_done, s->s_out));
+    APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
     return APM_OK;
 }
 

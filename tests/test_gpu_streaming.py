@@ -208,3 +208,77 @@ def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
     host.destroy()
     dev.destroy()
     tmp.destroy()
+
+
+def layer_ranges(model):
+    """First page of every transformer block (plus the embedding / final blocks): a page belongs
+    to the block of its first tenant.  Returns the n_layers + 1 boundaries."""
+    first_tensor = {}
+    for s in model.plan.segments:
+        first_tensor.setdefault(s.page, s.tensor)
+    bounds, prev = [0], None
+    for page in range(model.plan.n_pages):
+        blk = model.specs[first_tensor[page]].layer
+        if prev is not None and blk != prev:
+            bounds.append(page)
+        prev = blk
+    bounds.append(model.plan.n_pages)
+    return bounds
+
+
+@pytest.mark.parametrize("budget_layers", [1.0, 2.5, 100.0])
+def test_scheduled_step_equals_resident_bit_exact(budget_layers):
+    # the page movement follows the life-time based schedule (Alg. 1 phase 1) planned for a GPU
+    # memory of `budget_layers` times the largest layer; results must not depend on it
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=4)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    bounds = layer_ranges(model)
+    assert len(bounds) - 1 >= 12
+    largest = max(b - a for a, b in zip(bounds, bounds[1:]))
+    slots = min(n_pages, int(budget_layers * largest))
+    page_bytes = 12 * E
+    layers = [(range(a, b), 0) for a, b in zip(bounds, bounds[1:])]
+    tasks, peak = apm.apm_schedule_plan(layers, None, page_bytes, slots * page_bytes)
+    assert peak <= slots * page_bytes
+    moves_at_start = next(i for i, t in enumerate(tasks) if t[0] == apm.APM_TASK_COMPUTE)
+    assert moves_at_start <= slots and (budget_layers < 50 or moves_at_start == n_pages)
+
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    st = apm.apm_streamer_create(host, dev.pool, (slots + 1) // 2, 2)   # staging: at least the planned slots
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, None)
+        apm.apm_streamer_step_scheduled(st, tasks, bounds, t, hy, norm_s, None)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s)
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        hv = host_view(host, s_, n_pages, E)
+        assert np.array_equal(hv.view(np.uint32), res.reg[s_].cpu().numpy().view(np.uint32)), f"state {s_}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+
+    # unsound schedules are refused before anything runs
+    with pytest.raises(apm.ApmError) as e:      # a layer computes before its last page arrived
+        bad = [t for t in tasks if not (t[0] == apm.APM_TASK_MOVE_TO_GPU and t[1] == bounds[1] - 1)]
+        apm.apm_streamer_step_scheduled(st, bad, bounds, 4, hy)
+    assert e.value.code == apm.APM_ESTATE
+    with pytest.raises(apm.ApmError) as e:      # everything moved up front into too few slots
+        if budget_layers > 50:
+            raise apm.ApmError(apm.APM_ENOMEM, "n/a: every page has a slot")
+        greedy = [(apm.APM_TASK_MOVE_TO_GPU, p, 0) for p in range(n_pages)] + [(apm.APM_TASK_COMPUTE, i, i) for i in range(len(bounds) - 1)]
+        apm.apm_streamer_step_scheduled(st, greedy, bounds, 4, hy)
+    assert e.value.code == apm.APM_ENOMEM
+    st.destroy()
+    host.destroy()
+    dev.destroy()
+    res.destroy()
