@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-streamed", action="store_true", help="skip the host-streamed leg")
     ap.add_argument("--streamed-only", action="store_true", help="run only the host-streamed leg (gpt_13b: always)")
     ap.add_argument("--stream-steps", type=int, default=3)
+    ap.add_argument("--sched-layers", type=float, default=3.0,
+                    help="GPU memory of the scheduled streaming leg, in units of the largest block")
     ap.add_argument("--direct-wavefronts", type=int, default=0,
                     help="wavefronts of the direct streaming mode's kernel (0 = library default)")
     ap.add_argument("--batch-pages", type=int, default=32)
@@ -378,6 +380,56 @@ def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_para
     return out
 
 
+def layer_bounds(wl):
+    """Page ranges of the model's blocks (a page belongs to the block of its first tenant)."""
+    import paper_2303_02868_amd as apm
+    plan = apm.apm_pack_plan(wl.E, wl.numels)
+    first = {}
+    for tensor, _, page, _, _ in plan.segments:
+        first.setdefault(page, tensor)
+    bounds, prev = [0], None
+    for page in range(plan.n_pages):
+        blk = (wl.specs[first[page]].layer, wl.specs[first[page]].expert)
+        if prev is not None and blk != prev:
+            bounds.append(page)
+        prev = blk
+    bounds.append(plan.n_pages)
+    return bounds
+
+
+def scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step):
+    """The streamed step with its page movement planned by the life-time based scheduler for a GPU
+    memory of --sched-layers times the largest block."""
+    import torch
+    import paper_2303_02868_amd as apm
+    E = wl.E
+    bounds = layer_bounds(wl)
+    largest = max(b - a for a, b in zip(bounds, bounds[1:]))
+    budget = min(n_pages, int(args.sched_layers * largest))
+    page_bytes = 12 * E
+    t0 = time.perf_counter()
+    tasks, peak = apm.apm_schedule_plan([(range(a, b), 0) for a, b in zip(bounds, bounds[1:])], None,
+                                        page_bytes, budget * page_bytes)
+    t_plan = time.perf_counter() - t0
+    streamer = apm.apm_streamer_create(host, dev_pool, (budget + 1) // 2, 2)
+    stream = torch.cuda.current_stream()
+    apm.apm_streamer_step_scheduled(streamer, tasks, bounds, first_step, hyper, None, None, stream)
+    ts = []
+    for k in range(args.stream_steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        apm.apm_streamer_step_scheduled(streamer, tasks, bounds, first_step + 1 + k, hyper, None, None, stream)
+        torch.cuda.synchronize()
+        ts.append(time.perf_counter() - t0)
+    streamer.destroy()
+    each_way = n_pages * E * 12
+    return {"blocks": len(bounds) - 1, "largest_block_pages": largest, "gpu_memory_pages": budget,
+            "planned_peak_pages": peak // page_bytes,
+            "pages_moved_before_first_compute": next(i for i, t in enumerate(tasks) if t[0] == apm.APM_TASK_COMPUTE),
+            "plan_ms": t_plan * 1e3, "ms_per_step": min(ts) * 1e3, "ms_per_step_all": [t * 1e3 for t in ts],
+            "pcie_GBps_each_way": each_way / min(ts) / 1e9, "bytes_each_way": each_way}
+
+
 def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
     """fp32 state in pinned host pages; dev_pool supplies G16/P16 and the layout."""
     import torch
@@ -398,6 +450,7 @@ def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
         torch.cuda.synchronize()
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
     out = time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, wl.total)
+    out["scheduled"] = scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step + 50)
     if has_fp32:
         # mixed residency: half of the pages keep their fp32 state in HBM (the pool's own fp32
         # classes serve as the cache), the other half is streamed
@@ -574,6 +627,7 @@ def streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages):
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
     out = time_streamer(args, streamer, hyper, 1, n_pages, E, raw, wl.total)
     streamer.destroy()
+    out["scheduled"] = scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, 50)
     host.destroy()
     tmp.destroy()
     return out
