@@ -56,6 +56,9 @@ struct StageRing {
     int acquire(size_t bytes, int* slot);
     // Copies the first `bytes` of the slot's host buffer to its device buffer on `s`.
     int commit(int slot, size_t bytes, hipStream_t s);
+    // To be called after the kernels that read the slot's device buffer have been enqueued on `s`:
+    // the slot is not handed out again before they have run (commit alone only covers the copy).
+    int seal(int slot, hipStream_t s);
     void destroy();
 };
 

@@ -37,6 +37,12 @@ int StageRing::commit(int k, size_t bytes, hipStream_t s) {
     return APM_OK;
 }
 
+int StageRing::seal(int k, hipStream_t s) {
+    APM_HIP(hipEventRecord(ev[k], s));
+    busy[k] = true;
+    return APM_OK;
+}
+
 void StageRing::destroy() {
     for (int k = 0; k < K; ++k) {
         if (busy[k]) (void)hipEventSynchronize(ev[k]);
@@ -51,12 +57,20 @@ void StageRing::destroy() {
 }
 
 int ensure_scratch(apm_pool* pool) {
-    if (pool->d_meta) return APM_OK;
-    const int64_t n = pool->desc.n_pages * pool->S;
-    APM_HIP(hipMalloc((void**)&pool->d_partials, (size_t)n * sizeof(double)));
-    APM_HIP(hipMalloc((void**)&pool->d_nzflags, (size_t)n * sizeof(uint32_t)));
-    APM_HIP(hipMalloc((void**)&pool->d_meta, (size_t)pool->desc.n_pages * sizeof(PageMeta)));
-    return APM_OK;
+    if (pool->d_partials && pool->d_nzflags && pool->d_meta) return APM_OK;
+    const size_t n = (size_t)pool->desc.n_pages * (size_t)pool->S;
+    auto get = [](void** p, size_t bytes) -> int {  // a buffer an earlier, failed attempt got is kept
+        if (*p) return APM_OK;
+        hipError_t e = hipMalloc(p, bytes);
+        if (e == hipSuccess) return APM_OK;
+        (void)hipGetLastError();
+        *p = nullptr;
+        return fail(APM_ENOMEM, "allocating %zu bytes of per-page scratch failed: %s", bytes, hipGetErrorString(e));
+    };
+    int rc = get((void**)&pool->d_partials, n * sizeof(double));
+    if (rc == APM_OK) rc = get((void**)&pool->d_nzflags, n * sizeof(uint32_t));
+    if (rc == APM_OK) rc = get((void**)&pool->d_meta, (size_t)pool->desc.n_pages * sizeof(PageMeta));
+    return rc;
 }
 
 namespace {
@@ -190,7 +204,7 @@ int move_segments(apm_pool* pool, int state, const apm_tensor* tensors, int64_t 
         ScopedTiming t(pool, APM_K_SEGCOPY, s);
         APM_HIP(launch_seg_copy(static_cast<const SegDesc*>(pool->ring.d[slot]), (int64_t)segs.size(), max_bytes, s));
     }
-    return APM_OK;
+    return pool->ring.seal(slot, s);
 }
 
 }  // namespace

@@ -127,6 +127,7 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     bool run = identity;
     for (int64_t k = 0; run && k < n_pages; ++k)
         if (page_at(k) != first + k) run = false;
+    int ring_slots[2], n_ring_slots = 0;  // sealed once the kernels that read them are enqueued
     const int64_t* d_list = nullptr;
     if (!run) {
         const size_t list_bytes = (size_t)n_pages * sizeof(int64_t);
@@ -142,6 +143,7 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
         }
         rc = pool->ring.commit(slot, bytes, stream);
         if (rc != APM_OK) return rc;
+        ring_slots[n_ring_slots++] = slot;
         d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
         if (!identity) L.out_index = reinterpret_cast<const int32_t*>(static_cast<const char*>(pool->ring.d[slot]) + list_bytes);
     }
@@ -171,6 +173,7 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
         for (int64_t k = 0; k < n_pages; ++k) h[k] = by_page[(size_t)page_at(order[(size_t)k])];
         rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(PageSegs), stream);
         if (rc != APM_OK) return rc;
+        ring_slots[n_ring_slots++] = slot;
         L.segs = static_cast<const PageSegs*>(pool->ring.d[slot]);
         L.gather = grad_tensors != nullptr;
         L.scatter = p16_tensors != nullptr;
@@ -203,6 +206,10 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     {
         ScopedTiming t(pool, APM_K_UPDATE, stream);
         APM_HIP(launch_adamw(L, stream));
+    }
+    for (int k = 0; k < n_ring_slots; ++k) {
+        rc = pool->ring.seal(ring_slots[k], stream);
+        if (rc != APM_OK) return rc;
     }
     return APM_OK;
 }
@@ -340,8 +347,8 @@ extern "C" int apm_delayed_accumulate(apm_pool* pool, const int64_t* pages, int6
         }
     }
     const int64_t* d_list = nullptr;
+    int slot = -1;
     if (!run) {
-        int slot;
         int rc = pool->ring.acquire((size_t)n_pages * sizeof(int64_t), &slot);
         if (rc != APM_OK) return rc;
         int64_t* h = static_cast<int64_t*>(pool->ring.h[slot]);
@@ -357,6 +364,7 @@ extern "C" int apm_delayed_accumulate(apm_pool* pool, const int64_t* pages, int6
     APM_HIP(launch_grad_accum(pool->gbuf[k], static_cast<const uint16_t*>(g16), pool->d_used, d_list, first,
                               n_pages, pool->desc.page_elems, s));
     APM_HIP(hipEventRecord(pool->ev_staged[k], s));
+    if (slot >= 0) return pool->ring.seal(slot, s);
     return APM_OK;
 }
 

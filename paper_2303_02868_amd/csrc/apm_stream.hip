@@ -521,6 +521,7 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
     APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
 
     // the slot of every page, for the kernels (fp32 classes are addressed by slot, 16-bit ones by page)
+    int slots_ring_slot = -1;
     {
         int slot;
         rc = dev->ring.acquire((size_t)N * sizeof(int64_t), &slot);
@@ -529,6 +530,7 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         for (int64_t p = 0; p < N; ++p) h[p] = slot_seq[(size_t)p];
         rc = dev->ring.commit(slot, (size_t)N * sizeof(int64_t), s->s_cmp);
         if (rc != APM_OK) return rc;
+        slots_ring_slot = slot;
         L.state_pages = static_cast<const int64_t*>(dev->ring.d[slot]);
     }
     L.g16 = static_cast<const uint16_t*>(dev->base[APM_G16]);
@@ -618,6 +620,8 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         APM_HIP(hipEventRecord(written, s->s_out));
         for (int64_t j = 0; j < n; ++j) slot_free[(size_t)slot_seq[(size_t)(first + j)]] = written;
     }
+    rc = dev->ring.seal(slots_ring_slot, s->s_cmp);
+    if (rc != APM_OK) return rc;
     // every copy-in feeds a compute and every compute a write-back: the copy-out stream ends last
     APM_HIP(hipEventRecord(s->ev_done, s->s_out));
     APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
