@@ -402,6 +402,18 @@ int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages, cons
                      const apm_hyper* hyper, void* stream);
 
 /*
+ * The same hand-over with the fp32 state in host memory (Alg. 2's setting: the updating side works
+ * on states that do not live on the GPU): what is applied is one apm_streamer_step over all pages
+ * in use, on the GPU pool's update stream, reading the buffered gradient; what is staged is
+ * new_g16 (page layout, as above; NULL flushes).  In direct mode the update occupies 64
+ * wavefronts, so the producer's kernels on `stream` keep the rest of the GPU.  The ping-pong
+ * halves, the applied counter, apm_delayed_grad_buffer, apm_delayed_accumulate and
+ * apm_delayed_set_outputs are those of the streamer's GPU pool.
+ */
+int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, const apm_hyper* hyper,
+                              void* stream);
+
+/*
  * Adds one more gradient into the gradient buffered by the last apm_step_delayed call, before the
  * next call applies it (Alg. 2, buffering thread: g'16 <- g'16 + g16): element-wise
  * bf16_rne(fp32(g') + fp32(g)), the fp32 sum rounded to nearest, over the used extents of the

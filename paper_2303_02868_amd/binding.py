@@ -30,7 +30,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_schedule_plan", "apm_streamer_step_scheduled", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_schedule_plan", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -113,6 +113,7 @@ def lib() -> C.CDLL:
     L.apm_page_copy_async.argtypes = [vp, i64, vp, i64, i64, i32, vp]
     L.apm_schedule_plan.argtypes = [P(i64), P(i64), P(i64), i64, P(i64), i64, i64, i64, P(apm_task), P(i64), P(i64)]
     L.apm_streamer_step_scheduled.argtypes = [vp, P(apm_task), i64, P(i64), i64, i64, P(apm_hyper), vp, vp, vp]
+    L.apm_streamer_step_delayed.argtypes = [vp, vp, P(apm_hyper), vp]
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
@@ -366,6 +367,10 @@ def apm_streamer_step_scheduled(s: Streamer, tasks: Sequence, layer_first_page: 
     lf, n1 = _i64_array(layer_first_page)
     _check(lib().apm_streamer_step_scheduled(s.handle, arr, len(tasks), lf, n1 - 1, step, C.byref(hyper),
                                              _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
+
+
+def apm_streamer_step_delayed(s: Streamer, new_g16, hyper: apm_hyper, stream=None) -> None:
+    _check(lib().apm_streamer_step_delayed(s.handle, _ptr(new_g16), C.byref(hyper), _stream(stream)))
 
 
 def apm_streamer_set_cache(s: Streamer, cache: Optional[Pool], n_resident: int) -> None:

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <functional>
 #include <vector>
 
 #include "apm.h"
@@ -198,6 +199,14 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
                  uint8_t* skip_mask, hipStream_t stream, const apm_tensor* grad_tensors = nullptr,
                  const apm_tensor* p16_tensors = nullptr, int64_t n_tensors = 0);
 int ensure_scratch(apm_pool* pool);
+
+// The one-step-stale hand-over shared by apm_step_delayed and the streamer's delayed step:
+// applies the buffered gradient through `apply` (which enqueues one update reading the gradient
+// half it is given, with the step number it is given, on the pool's update stream), then stages
+// new_g16 into the other half on `caller` (nullptr = flush).
+using DelayedApply = std::function<int(const uint16_t* g16, int64_t step, hipStream_t upd_stream)>;
+int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
+                 hipStream_t caller, const DelayedApply& apply);
 
 // Brackets one kernel launch with events when the pool's timing is on.
 struct ScopedTiming {

@@ -242,12 +242,13 @@ int ensure_delayed(apm_pool* pool) {
     return APM_OK;
 }
 
+}  // namespace
+
 // Applies the buffered gradient (half `cur`) on the update stream.
-int apply_buffered(apm_pool* pool, const int64_t* pages, int64_t n_pages, const apm_hyper* hyper) {
+static int apply_buffered(apm_pool* pool, const DelayedApply& apply) {
     const int k = pool->cur;
     APM_HIP(hipStreamWaitEvent(pool->upd_stream, pool->ev_staged[k], 0));
-    int rc = enqueue_step(pool, pages, n_pages, pool->applied + 1, hyper, pool->gbuf[k],
-                          pool->delayed_norm, pool->delayed_skip, pool->upd_stream);
+    int rc = apply(pool->gbuf[k], pool->applied + 1, pool->upd_stream);
     if (rc != APM_OK) return rc;
     pool->applied += 1;
     APM_HIP(hipEventRecord(pool->ev_applied[k], pool->upd_stream));
@@ -255,7 +256,45 @@ int apply_buffered(apm_pool* pool, const int64_t* pages, int64_t n_pages, const 
     return APM_OK;
 }
 
-}  // namespace
+int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
+                 hipStream_t s, const DelayedApply& apply) {
+    APM_HIP(hipSetDevice(pool->desc.hip_device));
+    int rc = ensure_delayed(pool);
+    if (rc != APM_OK) return rc;
+    if (pool->buffered) {
+        rc = apply_buffered(pool, apply);
+        if (rc != APM_OK) return rc;
+        pool->buffered = false;
+    }
+    if (!new_g16) {  // flush: the caller's stream joins the update stream
+        APM_HIP(hipEventRecord(pool->ev_flush, pool->upd_stream));
+        APM_HIP(hipStreamWaitEvent(s, pool->ev_flush, 0));
+        return APM_OK;
+    }
+    // Stage the new gradient into the other half; that half was last read by the update enqueued
+    // two calls ago, which must have finished before it is overwritten.
+    const int nxt = pool->cur ^ 1;
+    const size_t pb = (size_t)pool->desc.page_elems * 2u;
+    const char* src = static_cast<const char*>(new_g16);
+    char* dst = reinterpret_cast<char*>(pool->gbuf[nxt]);
+    // A producer that wrote its gradient straight into the half handed out by
+    // apm_delayed_grad_buffer has already staged it (and waited for the half to be free there).
+    const bool in_place = src == dst;
+    if (!in_place && pool->applied_valid[nxt]) APM_HIP(hipStreamWaitEvent(s, pool->ev_applied[nxt], 0));
+    int64_t k = in_place ? n_pages : 0;
+    while (k < n_pages) {  // one copy per run of consecutive pages
+        const int64_t p0 = pages ? pages[k] : k;
+        int64_t len = 1;
+        while (k + len < n_pages && (pages ? pages[k + len] : k + len) == p0 + len) ++len;
+        APM_HIP(hipMemcpyAsync(dst + (size_t)p0 * pb, src + (size_t)p0 * pb, pb * (size_t)len, hipMemcpyDeviceToDevice, s));
+        k += len;
+    }
+    APM_HIP(hipEventRecord(pool->ev_staged[nxt], s));
+    pool->cur = nxt;
+    pool->buffered = true;
+    return APM_OK;
+}
+
 }  // namespace apm
 
 using namespace apm;
@@ -289,43 +328,11 @@ extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_
     if (pages)
         for (int64_t k = 0; k < n_pages; ++k)
             if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
-    APM_HIP(hipSetDevice(pool->desc.hip_device));
-    rc = ensure_delayed(pool);
-    if (rc != APM_OK) return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-
-    if (pool->buffered) {
-        rc = apply_buffered(pool, pages, n_pages, hyper);
-        if (rc != APM_OK) return rc;
-        pool->buffered = false;
-    }
-    if (!new_g16) {  // flush: the caller's stream joins the update stream
-        APM_HIP(hipEventRecord(pool->ev_flush, pool->upd_stream));
-        APM_HIP(hipStreamWaitEvent(s, pool->ev_flush, 0));
-        return APM_OK;
-    }
-    // Stage the new gradient into the other half; that half was last read by the update enqueued
-    // two calls ago, which must have finished before it is overwritten.
-    const int nxt = pool->cur ^ 1;
-    const size_t pb = (size_t)pool->desc.page_elems * 2u;
-    const char* src = static_cast<const char*>(new_g16);
-    char* dst = reinterpret_cast<char*>(pool->gbuf[nxt]);
-    // A producer that wrote its gradient straight into the half handed out by
-    // apm_delayed_grad_buffer has already staged it (and waited for the half to be free there).
-    const bool in_place = src == dst;
-    if (!in_place && pool->applied_valid[nxt]) APM_HIP(hipStreamWaitEvent(s, pool->ev_applied[nxt], 0));
-    int64_t k = in_place ? n_pages : 0;
-    while (k < n_pages) {  // one copy per run of consecutive pages
-        const int64_t p0 = pages ? pages[k] : k;
-        int64_t len = 1;
-        while (k + len < n_pages && (pages ? pages[k + len] : k + len) == p0 + len) ++len;
-        APM_HIP(hipMemcpyAsync(dst + (size_t)p0 * pb, src + (size_t)p0 * pb, pb * (size_t)len, hipMemcpyDeviceToDevice, s));
-        k += len;
-    }
-    APM_HIP(hipEventRecord(pool->ev_staged[nxt], s));
-    pool->cur = nxt;
-    pool->buffered = true;
-    return APM_OK;
+    return delayed_call(pool, pages, n_pages, new_g16, static_cast<hipStream_t>(stream),
+                        [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
+                            return enqueue_step(pool, pages, n_pages, step, hyper, g16, pool->delayed_norm,
+                                                pool->delayed_skip, upd);
+                        });
 }
 
 extern "C" int apm_delayed_accumulate(apm_pool* pool, const int64_t* pages, int64_t n_pages,

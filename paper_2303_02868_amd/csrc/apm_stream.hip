@@ -231,7 +231,7 @@ enum { kDoH2D = 1, kDoD2H = 2, kDoUpdate = 4 };
 // measurement entry point drops the kernels (and optionally one direction) but keeps the streams,
 // the event structure and the copy sizes.
 int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper, float* grad_norm,
-                 uint8_t* skip_mask, void* stream) {
+                 uint8_t* skip_mask, void* stream, const uint16_t* g16_override = nullptr) {
     apm_pool* dev = s->dev;
     apm_pool* host = s->host;
     if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
@@ -254,7 +254,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
     }
 
-    L.g16 = static_cast<const uint16_t*>(dev->base[APM_G16]);
+    L.g16 = g16_override ? g16_override : static_cast<const uint16_t*>(dev->base[APM_G16]);
     L.p16 = static_cast<uint16_t*>(dev->base[APM_P16]);
     L.used = dev->d_used;
     L.E = E;
@@ -390,6 +390,25 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
                                  float* grad_norm, uint8_t* skip_mask, void* stream) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+}
+
+// Alg. 2 with the optimizer states off the GPU: the updating side is the streamed step (in direct
+// mode a 64-wavefront kernel working through the host pages), the buffering side the caller's
+// stream handing over the next gradient.
+extern "C" int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, const apm_hyper* hyper,
+                                         void* stream) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    apm_pool* dev = s->dev;
+    if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+    AdamwLaunch probe{};
+    int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
+    if (rc != APM_OK) return rc;
+    const int64_t N = (int64_t)dev->plan.pages.size();
+    return delayed_call(dev, nullptr, N, new_g16, static_cast<hipStream_t>(stream),
+                        [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
+                            return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, dev->delayed_norm,
+                                                dev->delayed_skip, upd, g16);
+                        });
 }
 
 extern "C" int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_workgroups) {

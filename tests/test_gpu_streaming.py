@@ -282,3 +282,55 @@ def test_scheduled_step_equals_resident_bit_exact(budget_layers):
     host.destroy()
     dev.destroy()
     res.destroy()
+
+
+@pytest.mark.parametrize("mode", ["direct", "staged"])
+def test_streamer_delayed_calls_plus_flush_equal_synchronous_steps(mode):
+    # Alg. 2 with the fp32 state in host memory: N one-step-stale calls + flush must leave exactly
+    # the state of N synchronous streamed steps, and the applied counter must run one behind
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=6)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    init = DevicePool(n_pages, E, states=(apm.APM_P32,))
+    apm.apm_pack_tensors(init.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    sides = []
+    for _ in range(2):
+        dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+        apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+        host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+        apm.apm_page_copy_async(host, 0, init.pool, 0, n_pages, apm.APM_P32)
+        st = apm.apm_streamer_create(host, dev.pool, 16, 3)
+        set_mode(st, mode)
+        sides.append((dev, host, st))
+    (dev_a, host_a, st_a), (dev_b, host_b, st_b) = sides
+    produce = DevicePool(n_pages, E, states=(apm.APM_G16,))       # the producer's own gradient pages
+    apm.apm_pool_set_layout(produce.pool, model.tensors(model.p_flat), n_t)
+    norm_a = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_b = torch.full((n_pages,), -1.0, dtype=torch.float32, device=DEV)
+    apm.apm_delayed_set_outputs(dev_b.pool, norm_b, None)
+    steps = 4
+    for t in range(1, steps + 1):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(dev_a.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_streamer_step(st_a, t, hy, norm_a, None)
+        apm.apm_pack_tensors(produce.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_streamer_step_delayed(st_b, produce.reg[apm.APM_G16], hy)
+        assert apm.apm_delayed_applied(dev_b.pool) == t - 1
+        torch.cuda.synchronize()
+    apm.apm_streamer_step_delayed(st_b, None, hy)
+    torch.cuda.synchronize()
+    assert apm.apm_delayed_applied(dev_b.pool) == steps
+    assert torch.equal(norm_a, norm_b)
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        a = host_view(host_a, s_, n_pages, E).view(np.uint32)
+        b = host_view(host_b, s_, n_pages, E).view(np.uint32)
+        assert np.array_equal(a, b), f"state {s_}"
+    assert torch.equal(dev_a.reg[apm.APM_P16].view(torch.int16), dev_b.reg[apm.APM_P16].view(torch.int16))
+    assert not dev_b.reg[apm.APM_G16].view(torch.int16).any()     # the pool's own G16 class was never used
+    for dev, host, st in sides:
+        st.destroy()
+        host.destroy()
+        dev.destroy()
+    produce.destroy()
+    init.destroy()
