@@ -430,6 +430,78 @@ def scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step):
             "pcie_GBps_each_way": each_way / min(ts) / 1e9, "bytes_each_way": each_way}
 
 
+def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
+    """Alg. 2's point on one GPU: the update of host-resident state runs beside the producer of the
+    next gradient instead of after it.  The producer here is a stand-in for forward/backward (which
+    this build does not have): dense bf16 matrix products through the BLAS library, sized to take
+    about as long as one streamed update.  Synchronous: products, then apm_streamer_step.
+    One-step-stale: apm_streamer_step_delayed (applies the previous gradient on the update stream),
+    then the products.  Measured for three ways of streaming."""
+    import torch
+    import paper_2303_02868_amd as apm
+    stream = torch.cuda.current_stream()
+    n = 8192
+    a = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
+    b = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
+    c = torch.empty(n, n, device=DEV, dtype=torch.bfloat16)
+
+    def products(reps):
+        for _ in range(reps):
+            torch.matmul(a, b, out=c)
+
+    products(10)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    products(50)
+    torch.cuda.synchronize()
+    per = (time.perf_counter() - t0) / 50
+    reps = max(1, int(round(update_ms * 1e-3 / per)))
+    g16 = apm.apm_pool_state_ptr(dev_pool, apm.APM_G16)
+    iters = max(3, args.stream_steps)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters
+
+    t_compute = timed(lambda: products(reps))
+    step = [1000]
+
+    def update_only():
+        apm.apm_streamer_step(streamer, step[0], hyper, None, None, stream)
+        step[0] += 1
+
+    def sync_iter():
+        products(reps)
+        update_only()
+
+    def delayed_iter():
+        apm.apm_streamer_step_delayed(streamer, g16, hyper, stream)
+        products(reps)
+
+    out = {"producer": f"{reps} bf16 {n}^3 matrix products per iteration (stand-in for forward/backward)",
+           "producer_TFLOPs_alone": 2.0 * n ** 3 * reps / t_compute / 1e12, "producer_ms": t_compute * 1e3}
+    ways = (("direct_64_wavefronts_on_64_CUs", apm.APM_STREAM_DIRECT, 64, 1),
+            ("direct_128_wavefronts_on_8_CUs", apm.APM_STREAM_DIRECT, 128, 16),
+            ("staged", apm.APM_STREAM_STAGED, 0, 0))
+    for name, mode, waves, per_wg in ways:
+        apm.apm_streamer_set_mode(streamer, mode, waves, per_wg)
+        update_only()
+        t_update = timed(update_only)
+        t_sync = timed(sync_iter)
+        apm.apm_streamer_step_delayed(streamer, g16, hyper, stream)      # fill the pipeline
+        t_delayed = timed(delayed_iter)
+        apm.apm_streamer_step_delayed(streamer, None, hyper, stream)     # flush
+        torch.cuda.synchronize()
+        out[name] = {"update_ms": t_update * 1e3, "synchronous_ms_per_iter": t_sync * 1e3,
+                     "one_step_stale_ms_per_iter": t_delayed * 1e3, "speedup": t_sync / t_delayed,
+                     "hidden_fraction_of_the_shorter": (t_sync - t_delayed) / min(t_compute, t_update)}
+    return out
+
+
 def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
     """fp32 state in pinned host pages; dev_pool supplies G16/P16 and the layout."""
     import torch
@@ -451,6 +523,9 @@ def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
     out = time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, wl.total)
     out["scheduled"] = scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step + 50)
+    out["lock_free"] = lockfree_leg(args, streamer, dev_pool, hyper, out["ms_per_step"])
+    apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT if out["mode"] == "direct" else apm.APM_STREAM_STAGED,
+                              args.direct_wavefronts)
     if has_fp32:
         # mixed residency: half of the pages keep their fp32 state in HBM (the pool's own fp32
         # classes serve as the cache), the other half is streamed
@@ -626,6 +701,7 @@ def streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages):
     raw = pcie_raw(host, tmp, n_pages, E, apm.APM_P32)
     streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_pages), args.slots)
     out = time_streamer(args, streamer, hyper, 1, n_pages, E, raw, wl.total)
+    out["lock_free"] = lockfree_leg(args, streamer, dev_pool, hyper, out["ms_per_step"])
     streamer.destroy()
     out["scheduled"] = scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, 50)
     host.destroy()

@@ -273,8 +273,11 @@ int apm_streamer_destroy(apm_streamer* s);
 /*
  * How the fp32 pages cross PCIe (Sec. 4.2 leaves the mechanism open):
  *   APM_STREAM_DIRECT: no copies and no staging; the update kernel itself reads p, m, v from the
- *     pinned host pages and writes them back, with `direct_workgroups` wavefronts (0 = a default
- *     that saturates the link; the rest of the GPU stays free for other work).
+ *     pinned host pages and writes them back, with `direct_wavefronts` wavefronts (0 = 64, which
+ *     saturates the link) of which `wavefronts_per_workgroup` (0 = 1, at most 16) share a
+ *     workgroup and so a CU.  One per workgroup moves data fastest; more per workgroup occupy
+ *     fewer CUs for the duration of the step, which disturbs concurrent kernels of the caller
+ *     less (measured beside dense matrix products: 128 wavefronts, 16 per workgroup).
  *   APM_STREAM_STAGED: the pipeline copy-in / update / copy-out through HBM staging slots on
  *     three streams.  Its staging memory, events and copy streams are set up when the mode is
  *     first selected: which stream pairs overlap a host-to-device with a device-to-host copy
@@ -285,7 +288,8 @@ int apm_streamer_destroy(apm_streamer* s);
  * apm_streamer_get_mode returns the current mode (or a negative status).
  */
 enum apm_stream_mode { APM_STREAM_STAGED = 0, APM_STREAM_DIRECT = 1 };
-int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_workgroups);
+int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_wavefronts,
+                          int wavefronts_per_workgroup);
 int apm_streamer_get_mode(const apm_streamer* s);
 
 /*

@@ -119,7 +119,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_copy_only.argtypes = [vp, i32, vp]
     L.apm_streamer_set_cache.argtypes = [vp, vp, i64]
-    L.apm_streamer_set_mode.argtypes = [vp, i32, i32]
+    L.apm_streamer_set_mode.argtypes = [vp, i32, i32, i32]
     L.apm_streamer_get_mode.argtypes = [vp]
     L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
@@ -378,8 +378,9 @@ def apm_streamer_set_cache(s: Streamer, cache: Optional[Pool], n_resident: int) 
     s.cache = cache
 
 
-def apm_streamer_set_mode(s: Streamer, mode: int, direct_workgroups: int = 0) -> None:
-    _check(lib().apm_streamer_set_mode(s.handle, mode, direct_workgroups))
+def apm_streamer_set_mode(s: Streamer, mode: int, direct_wavefronts: int = 0,
+                          wavefronts_per_workgroup: int = 0) -> None:
+    _check(lib().apm_streamer_set_mode(s.handle, mode, direct_wavefronts, wavefronts_per_workgroup))
 
 
 def apm_streamer_get_mode(s: Streamer) -> int:

@@ -351,7 +351,7 @@ constexpr int kUpdTile = kUpdThreads * 4 * kUpdU;  // elements per workgroup
 // classes.
 template <bool GATHER, bool SCATTER>
 __device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs& segs, float scale,
-                                             int used8, int64_t gpage, int64_t spage, int start) {
+                                             int used8, int64_t gpage, int64_t spage, int start, int lane) {
     f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
     f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
     f32x4* __restrict__ V = reinterpret_cast<f32x4*>(a.v32 + spage * a.E);
@@ -373,7 +373,7 @@ __device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs
     }
 
     const int nvec = used8 >> 2;
-    const int v0 = (start >> 2) + (int)threadIdx.x;
+    const int v0 = (start >> 2) + lane;
     f32x4 p[kUpdU], m[kUpdU], v[kUpdU];
     u32x2 g[kUpdU];
 #pragma unroll
@@ -437,20 +437,30 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     for (int it = 0; it < SLICES; ++it) {
         const int start = ((int)blockIdx.x * SLICES + it) * kUpdTile;
         if (start >= used8) return;  // beyond the extent
-        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start);
+        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start, (int)threadIdx.x);
     }
 }
 
 // The form for fp32 classes that live in pinned host memory and are read and written across
-// PCIe by the kernel itself: a fixed number of wavefronts (the grid) walks all (position, slice)
-// items of `count` list positions with `nx` slices each, consecutive wavefronts taking
-// consecutive slices.  The link needs only some hundred KiB in flight, so a small grid saturates
-// it and leaves the rest of the GPU to other work.
+// PCIe by the kernel itself: a fixed number of wavefronts walks all (position, slice) items of
+// `count` list positions with `nx` slices each, consecutive wavefronts taking consecutive slices.
+// The link needs only some hundred KiB in flight, so a few dozen wavefronts saturate it.  The
+// launch chooses how many of them share a workgroup (and with it a CU): one per workgroup gives
+// the highest transfer rate; packed 8 or 16 to a workgroup they occupy few CUs, which matters
+// beside kernels whose workgroups need a CU's whole register file or LDS (dense matrix
+// products), because a wavefront that lives as long as the whole transfer keeps those off its CU.
+constexpr int kStrideMaxThreads = 1024;
+
 template <bool GATHER, bool SCATTER>
-__global__ __launch_bounds__(kUpdThreads) void apm_adamw_stride_kernel(UpdateArgs a, int64_t count, int nx) {
+__global__ __launch_bounds__(kStrideMaxThreads) void apm_adamw_stride_kernel(UpdateArgs a, int64_t count, int nx,
+                                                                             int n_workers) {
+    const int lane = (int)threadIdx.x & (kWave - 1);
+    const int waves_per_wg = (int)blockDim.x / kWave;
+    const int worker = (int)blockIdx.x * waves_per_wg + __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    if (worker >= n_workers) return;
     const int64_t n_items = count * nx;
 #pragma unroll 1
-    for (int64_t w = blockIdx.x; w < n_items; w += gridDim.x) {
+    for (int64_t w = worker; w < n_items; w += n_workers) {
         const int64_t i = a.list_offset + w / nx;
         const int start = (int)(w % nx) * kUpdTile;
         const i64x4 raw = *reinterpret_cast<const i64x4*>(a.meta + i);
@@ -459,7 +469,7 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_stride_kernel(UpdateArg
         if (scale < 0.0f || start >= used8) continue;
         PageSegs segs{};
         if (GATHER || SCATTER) segs = a.segs[i];
-        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start);
+        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start, lane);
     }
 }
 
@@ -586,16 +596,18 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
     a.E = L.E;
     a.b1 = L.b1; a.omb1 = L.omb1; a.b2 = L.b2; a.omb2 = L.omb2;
     a.inv_sqrt_bc2 = L.inv_sqrt_bc2; a.eps = L.eps; a.step_size = L.step_size; a.lr_wd = L.lr_wd;
-    if (L.stride_workgroups > 0) {
+    if (L.stride_wavefronts > 0) {
         return for_each_launch(L, [&](int64_t begin, int64_t ny, int64_t max_used) {
             a.list_offset = begin;
             const int nx = (int)((max_used + kUpdTile - 1) / kUpdTile);
             const int64_t items = ny * nx;
-            const dim3 grid((unsigned)(items < L.stride_workgroups ? items : L.stride_workgroups)), block(kUpdThreads);
-            if (L.gather && L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, true>), grid, block, 0, s, a, ny, nx);
-            else if (L.gather) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, false>), grid, block, 0, s, a, ny, nx);
-            else if (L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<false, true>), grid, block, 0, s, a, ny, nx);
-            else hipLaunchKernelGGL((apm_adamw_stride_kernel<false, false>), grid, block, 0, s, a, ny, nx);
+            const int workers = (int)(items < L.stride_wavefronts ? items : L.stride_wavefronts);
+            const int per_wg = L.stride_waves_per_wg >= 1 && L.stride_waves_per_wg <= kStrideMaxThreads / kWave ? L.stride_waves_per_wg : 1;
+            const dim3 grid((unsigned)((workers + per_wg - 1) / per_wg)), block((unsigned)(per_wg * kWave));
+            if (L.gather && L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, true>), grid, block, 0, s, a, ny, nx, workers);
+            else if (L.gather) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, false>), grid, block, 0, s, a, ny, nx, workers);
+            else if (L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<false, true>), grid, block, 0, s, a, ny, nx, workers);
+            else hipLaunchKernelGGL((apm_adamw_stride_kernel<false, false>), grid, block, 0, s, a, ny, nx, workers);
         });
     }
     const bool may_skip = L.partials && L.skip_mode == APM_SKIP_UNTOUCHED;

@@ -128,8 +128,9 @@ struct AdamwLaunch {
     float b1, omb1, b2, omb2, inv_sqrt_bc2, eps, step_size, lr_wd;
     double max_norm;
     int32_t skip_mode;
-    int32_t stride_workgroups;    // > 0: the update runs as that many wavefronts striding over all
+    int32_t stride_wavefronts;    // > 0: the update runs as that many wavefronts striding over all
                                   // page slices (fp32 classes in host memory); 0: one per slice
+    int32_t stride_waves_per_wg;  // how many of them share a workgroup, 1..16
 };
 
 // Reduce pass (fills meta with clip scale / skip); or, when no reduce pass is needed, the prepare

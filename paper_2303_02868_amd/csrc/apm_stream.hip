@@ -38,7 +38,8 @@ struct apm_streamer {
     bool in_is_null = false, out_is_null = false;  // a chosen copy stream may be the default stream
     double probe_h2d = 0, probe_d2h = 0, probe_duplex = 0;  // GB/s seen by the stream calibration
     int mode = APM_STREAM_STAGED;
-    int direct_wgs = 0;         // wavefronts of the direct-mode update kernel
+    int direct_waves = 0;       // wavefronts of the direct-mode update kernel
+    int direct_per_wg = 1;      // how many of them share a workgroup
     float* host_dev[3] = {nullptr, nullptr, nullptr};  // device-side addresses of the host pool's fp32 classes
     std::vector<hipEvent_t> sched_ev;  // events of the scheduled step, grown on demand and reused
 };
@@ -47,9 +48,11 @@ using namespace apm;
 
 namespace {
 // Wavefronts of the direct-mode kernel when the caller names no number.  Measured on MI355X
-// (PCIe Gen5 x16, GB/s each way, 4 MiB pages): 8 -> 23.7, 16 -> 45.6, 24 -> 42.9, 40 -> 46.1,
-// 56 -> 48.9, 64 -> 49.3, 72 -> 49.3, 96 -> 48.8, 128 -> 48.4, 192 -> 47.4, 256 and more -> 45.4.
-constexpr int kDirectWorkgroups = 64;
+// (PCIe Gen5 x16, GB/s each way, 4 MiB pages, one wavefront per workgroup): 8 -> 23.7, 16 -> 45.6,
+// 24 -> 42.9, 40 -> 46.1, 56 -> 48.9, 64 -> 49.3, 72 -> 49.3, 96 -> 48.8, 128 -> 48.4, 192 -> 47.4,
+// 256 and more -> 45.4.  Packed onto fewer CUs a CU's own memory pipeline becomes the limit:
+// 64 wavefronts reach 47 GB/s at 8 per workgroup and 35 GB/s at 16; 128 at 16 reach 48.
+constexpr int kDirectWavefronts = 64;
 
 void free_streamer(apm_streamer* s) {
     (void)hipDeviceSynchronize();
@@ -199,7 +202,7 @@ extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool*
     APM_HIP(hipSetDevice(dev->desc.hip_device));
     apm_streamer* s = new apm_streamer();
     s->host = host; s->dev = dev; s->B = batch_pages; s->n_slots = n_slots;
-    s->direct_wgs = kDirectWorkgroups;
+    s->direct_waves = kDirectWavefronts;
     hipError_t e = hipStreamCreateWithFlags(&s->s_cmp, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_start, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_done, hipEventDisableTiming);
@@ -284,7 +287,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
                 C.p32 = s->host_dev[0];
                 C.m32 = s->host_dev[1];
                 C.v32 = s->host_dev[2];
-                C.stride_workgroups = s->direct_wgs;
+                C.stride_wavefronts = s->direct_waves;
+                C.stride_waves_per_wg = s->direct_per_wg;
             }
             C.state_first = C.grad_first = first;
             C.n_listed = n;
@@ -411,14 +415,17 @@ extern "C" int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, c
                         });
 }
 
-extern "C" int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_workgroups) {
+extern "C" int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_wavefronts,
+                                     int wavefronts_per_workgroup) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     if (mode != APM_STREAM_STAGED && mode != APM_STREAM_DIRECT) return fail(APM_EINVAL, "unknown streamer mode %d", mode);
-    if (direct_workgroups < 0 || direct_workgroups > (1 << 20)) return fail(APM_EINVAL, "direct_workgroups out of range");
+    if (direct_wavefronts < 0 || direct_wavefronts > (1 << 20)) return fail(APM_EINVAL, "direct_wavefronts out of range");
+    if (wavefronts_per_workgroup < 0 || wavefronts_per_workgroup > 16) return fail(APM_EINVAL, "wavefronts_per_workgroup must be in [0, 16]");
     APM_HIP(hipSetDevice(s->dev->desc.hip_device));
     if (mode == APM_STREAM_DIRECT) {
         if (!map_host_classes(s)) return fail(APM_EDEVICE, "the host pool's memory is not mapped into the GPU's address space (not pinned?)");
-        s->direct_wgs = direct_workgroups > 0 ? direct_workgroups : kDirectWorkgroups;
+        s->direct_waves = direct_wavefronts > 0 ? direct_wavefronts : kDirectWavefronts;
+        s->direct_per_wg = wavefronts_per_workgroup > 0 ? wavefronts_per_workgroup : 1;
     } else {
         int rc = ensure_staged(s);
         if (rc != APM_OK) return rc;

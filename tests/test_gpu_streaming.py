@@ -24,11 +24,13 @@ def host_view(pool, state, n_pages, E):
 
 
 def set_mode(streamer, mode):
-    """"staged" | "direct" | "direct:<wavefronts>" (a small odd count makes every wavefront stride
-    over many pages and slices)."""
+    """"staged" | "direct" | "direct:<wavefronts>[:<per workgroup>]" (a small odd count makes every
+    wavefront stride over many pages and slices)."""
     if mode.startswith("direct"):
-        n = int(mode.split(":")[1]) if ":" in mode else 0
-        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT, n)
+        parts = mode.split(":")
+        n = int(parts[1]) if len(parts) > 1 else 0
+        per = int(parts[2]) if len(parts) > 2 else 0
+        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT, n, per)
         assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_DIRECT
     else:
         assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_DIRECT   # pinned pool: the default
@@ -61,7 +63,8 @@ def test_page_copy_roundtrip_bit_exact():
 
 
 @pytest.mark.parametrize("batch,slots,clip,mode", [(4, 2, 0.0, "staged"), (7, 3, 1.0, "staged"), (64, 2, 1.0, "staged"),
-                                                   (4, 2, 0.0, "direct"), (4, 2, 1.0, "direct:7")])
+                                                   (4, 2, 0.0, "direct"), (4, 2, 1.0, "direct:7"), (4, 2, 1.0, "direct:37:16"),
+                                                   (4, 2, 0.0, "direct:128:8")])
 def test_streamed_equals_resident_bit_exact(batch, slots, clip, mode):
     # a GPT-2-small-sized model: resident run vs. fp32 state in pinned host pages streamed through
     # `slots` staging slots of `batch` pages
