@@ -33,6 +33,7 @@ extern "C" {
 
 typedef struct apm_pool apm_pool;
 typedef struct apm_streamer apm_streamer;
+typedef struct apm_tiered apm_tiered;
 
 enum apm_status {
     APM_OK = 0,
@@ -43,9 +44,9 @@ enum apm_status {
     APM_ESTATE = -5   /* call not valid in the pool's current state */
 };
 
-/* Where a pool's pages live.  The paper's device map is {0: GPU, 1: CPU, 2: SSD} (Page listing,
- * Sec. 4.1); the SSD tier is not built. */
-enum apm_device { APM_DEV_GPU = 0, APM_DEV_HOST = 1 };
+/* Where a pool's pages live, numbered like the paper's device map {0: GPU, 1: CPU, 2: SSD} (Page
+ * listing, Sec. 4.1).  A FILE pool keeps each state class in one file (apm_file_pool_create). */
+enum apm_device { APM_DEV_GPU = 0, APM_DEV_HOST = 1, APM_DEV_FILE = 2 };
 
 enum apm_dtype { APM_F32 = 0, APM_BF16 = 1 };
 
@@ -59,8 +60,10 @@ enum apm_skip_mode {
 };
 
 enum apm_pool_flags {
-    APM_POOL_NO_ZERO = 1u /* do not zero-fill at creation; the caller guarantees that unused page
-                             elements (padding, alignment gaps) are zero in every state class */
+    APM_POOL_NO_ZERO = 1u, /* do not zero-fill at creation; the caller guarantees that unused page
+                              elements (padding, alignment gaps) are zero in every state class.
+                              FILE pools: existing files keep their contents */
+    APM_POOL_FILE_DIRECT = 2u /* FILE pools: unbuffered I/O (O_DIRECT), bypassing the page cache */
 };
 
 /*
@@ -386,6 +389,61 @@ int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t 
                                 const int64_t* layer_first_page, int64_t n_layers, int64_t step,
                                 const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,
                                 void* stream);
+
+/* ---- third tier: FP32 states in files (the device map's SSD, Sec. 4.1; Alg. 2 fetches the
+ *      states from SSD, updates them and offloads them back) ---------------------------------- */
+
+/*
+ * A pool whose state classes live in files <path_prefix>.p32 / .m32 / .v32 / .g16 / .p16 (one per
+ * class in state_mask), each n_pages * page_elems elements, page k at byte offset k * page bytes.
+ * Without APM_POOL_NO_ZERO the files are created anew and read as zeros; with it, existing files
+ * are opened as they are (and extended with zeros to full size).  APM_POOL_FILE_DIRECT needs
+ * pages of a multiple of 4096 bytes.  The files are not removed by apm_pool_destroy.
+ * A FILE pool has no layout of its own and exchanges pages with HOST pools only:
+ * apm_page_copy_async between a FILE and a HOST pool synchronises `stream`, then reads or writes
+ * the pages before it returns (file I/O is not stream-ordered).  No GPU is needed to create one.
+ * Errors: APM_EINVAL, APM_EDEVICE (the file cannot be created; the message has the reason).
+ */
+int apm_file_pool_create(apm_pool** out, const char* path_prefix, int32_t hip_device,
+                         int64_t page_elems, int64_t n_pages, uint32_t state_mask, uint32_t flags);
+
+/*
+ * Streamed update over file-resident state.  file: FILE pool storing P32, M32, V32; dev: GPU pool
+ * storing G16 and P16 with an installed layout (same page size).  The only staging is a window of
+ * pinned host memory, n_slots slots of batch_pages pages x 3 classes: io_threads I/O threads read
+ * the next batches into free slots and write finished ones back, in pieces of 8 MiB, while the
+ * update kernel works on the current batch directly in the window across PCIe (as in
+ * APM_STREAM_DIRECT).  n_slots >= 2, io_threads in [1, 64].
+ */
+int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev, int64_t batch_pages,
+                      int n_slots, int io_threads);
+int apm_tiered_destroy(apm_tiered* t); /* before the pools it uses */
+
+/*
+ * One AdamW step over all pages in use.  The kernels start after everything enqueued on `stream`
+ * so far; the call blocks the calling thread until the last page has been written back (so,
+ * unlike the other step calls, it is synchronous).  grad_norm / skip_mask as in
+ * apm_page_adamw_step.  Results are bit-identical to the resident update.
+ * Errors: as apm_page_adamw_step, and APM_EDEVICE if a read or write fails (the step still drains;
+ * the files may then hold a partly updated state).
+ */
+int apm_tiered_step(apm_tiered* t, int64_t step, const apm_hyper* hyper, float* grad_norm,
+                    uint8_t* skip_mask, void* stream);
+
+/*
+ * Alg. 2 with its two actors as two host threads.  The call (1) waits for the update started by
+ * the previous call, (2) if a gradient is buffered, counts it as applied and starts the library's
+ * updater thread on it (the step above, reading the buffered gradient, once its staging has
+ * completed), (3) stages new_g16 (device pointer, page layout, all pages in use) into the other
+ * half of the GPU pool's ping-pong buffer on `stream` and returns; the caller produces the next
+ * gradient while the updater fetches, updates and offloads the states.  new_g16 == NULL flushes:
+ * the buffered gradient is applied and the call returns when that update is complete.
+ * N calls + flush leave exactly the state of N apm_tiered_step calls.  While an update runs, the
+ * GPU pool's per-page scratch is in use: no other step call on that pool.  The applied counter
+ * and apm_delayed_set_outputs are those of the GPU pool; apm_delayed_grad_buffer is not available
+ * here (APM_EINVAL).  An error of the background update is reported by the next call.
+ */
+int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const apm_hyper* hyper, void* stream);
 
 /* ---- one-step-stale update (Alg. 2 reduced to one GPU: apply the buffered gradient while the
  *      next one is being staged) -------------------------------------------------------------- */

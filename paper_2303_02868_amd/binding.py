@@ -14,11 +14,12 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("APM_LIBRARY") or os.path.join(_PKG, "libapm.so")
 
 APM_OK, APM_EINVAL, APM_ENOMEM, APM_ERANGE, APM_EDEVICE, APM_ESTATE = 0, -1, -2, -3, -4, -5
-APM_DEV_GPU, APM_DEV_HOST = 0, 1
+APM_DEV_GPU, APM_DEV_HOST, APM_DEV_FILE = 0, 1, 2
 APM_F32, APM_BF16 = 0, 1
 APM_P32, APM_M32, APM_V32, APM_G16, APM_P16, APM_N_STATES = 0, 1, 2, 3, 4, 5
 APM_SKIP_NONE, APM_SKIP_UNTOUCHED = 0, 1
 APM_POOL_NO_ZERO = 1
+APM_POOL_FILE_DIRECT = 2
 APM_STREAM_STAGED, APM_STREAM_DIRECT = 0, 1
 APM_K_REDUCE, APM_K_UPDATE, APM_K_SEGCOPY, APM_N_KERNEL_CLASSES = 0, 1, 2, 3
 ALL_STATES = 0b11111
@@ -30,7 +31,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_schedule_plan", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -114,6 +115,11 @@ def lib() -> C.CDLL:
     L.apm_schedule_plan.argtypes = [P(i64), P(i64), P(i64), i64, P(i64), i64, i64, i64, P(apm_task), P(i64), P(i64)]
     L.apm_streamer_step_scheduled.argtypes = [vp, P(apm_task), i64, P(i64), i64, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_step_delayed.argtypes = [vp, vp, P(apm_hyper), vp]
+    L.apm_file_pool_create.argtypes = [P(vp), C.c_char_p, i32, i64, i64, C.c_uint32, C.c_uint32]
+    L.apm_tiered_create.argtypes = [P(vp), vp, vp, i64, i32, i32]
+    L.apm_tiered_destroy.argtypes = [vp]
+    L.apm_tiered_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
+    L.apm_tiered_step_delayed.argtypes = [vp, vp, P(apm_hyper), vp]
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
     L.apm_streamer_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
@@ -304,6 +310,51 @@ def apm_page_copy_async(dst: Pool, dst_page: int, src: Pool, src_page: int, n_pa
                         state: int, stream=None) -> None:
     _check(lib().apm_page_copy_async(dst.handle, dst_page, src.handle, src_page, n_pages, state,
                                      _stream(stream)))
+
+
+def apm_file_pool_create(path_prefix: str, page_elems: int, n_pages: int, state_mask: int = FP32_STATES,
+                         flags: int = 0, hip_device: int = 0) -> Pool:
+    d = apm_pool_desc()
+    d.device, d.hip_device, d.page_elems, d.n_pages = APM_DEV_FILE, hip_device, page_elems, n_pages
+    d.state_mask, d.flags = state_mask, flags
+    out = C.c_void_p()
+    _check(lib().apm_file_pool_create(C.byref(out), path_prefix.encode(), hip_device, page_elems, n_pages,
+                                      state_mask, flags))
+    return Pool(out.value, d)
+
+
+class Tiered:
+    def __init__(self, handle, file: Pool, dev: Pool):
+        self.handle, self.file, self.dev = handle, file, dev
+
+    def destroy(self):
+        if self.handle:
+            h, self.handle = self.handle, None
+            _check(lib().apm_tiered_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def apm_tiered_create(file: Pool, dev: Pool, batch_pages: int, n_slots: int, io_threads: int) -> Tiered:
+    out = C.c_void_p()
+    _check(lib().apm_tiered_create(C.byref(out), file.handle, dev.handle, batch_pages, n_slots, io_threads))
+    return Tiered(out.value, file, dev)
+
+
+def apm_tiered_destroy(t: Tiered) -> None:
+    t.destroy()
+
+
+def apm_tiered_step(t: Tiered, step: int, hyper: apm_hyper, grad_norm=None, skip_mask=None, stream=None) -> None:
+    _check(lib().apm_tiered_step(t.handle, step, C.byref(hyper), _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
+
+
+def apm_tiered_step_delayed(t: Tiered, new_g16, hyper: apm_hyper, stream=None) -> None:
+    _check(lib().apm_tiered_step_delayed(t.handle, _ptr(new_g16), C.byref(hyper), _stream(stream)))
 
 
 class Streamer:

@@ -164,6 +164,8 @@ struct apm_pool {
     std::vector<int64_t> layout_ids;
     apm::Plan plan;
 
+    int fd[APM_N_STATES] = {-1, -1, -1, -1, -1};  // FILE pools: one file per stored class
+
     int32_t* d_used = nullptr;      // device page table: used extent per page
     double* d_partials = nullptr;   // reduce scratch, n_pages * S
     uint32_t* d_nzflags = nullptr;
@@ -200,6 +202,11 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
                  uint8_t* skip_mask, hipStream_t stream, const apm_tensor* grad_tensors = nullptr,
                  const apm_tensor* p16_tensors = nullptr, int64_t n_tensors = 0);
 int ensure_scratch(apm_pool* pool);
+// Allocates the ping-pong gradient halves, the events and the update stream of the delayed path.
+int ensure_delayed(apm_pool* pool);
+// FILE <-> HOST page copy (synchronous).
+int file_page_copy(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_page, int64_t n_pages,
+                   int state, hipStream_t stream);
 
 // The one-step-stale hand-over shared by apm_step_delayed and the streamer's delayed step:
 // applies the buffered gradient through `apply` (which enqueues one update reading the gradient

@@ -2,6 +2,8 @@
 #include <cstring>
 #include <thread>
 
+#include <unistd.h>
+
 #include "apm_internal.h"
 
 namespace apm {
@@ -105,6 +107,8 @@ int zero_regions(apm_pool* pool, hipStream_t s, bool at_create) {
 }
 
 void free_pool(apm_pool* pool) {
+    for (int st = 0; st < APM_N_STATES; ++st)
+        if (pool->fd[st] >= 0) (void)close(pool->fd[st]);
     for (int st = 0; st < APM_N_STATES; ++st) {
         if (pool->owned[st] && pool->base[st]) {
             if (pool->desc.device == APM_DEV_HOST) (void)hipHostFree(pool->base[st]);
@@ -263,6 +267,10 @@ extern "C" int apm_pool_create(apm_pool** out, const apm_pool_desc* desc) {
 
 extern "C" int apm_pool_destroy(apm_pool* pool) {
     if (!pool) return APM_OK;
+    if (pool->desc.device == APM_DEV_FILE) {  // holds file descriptors only: no HIP call
+        free_pool(pool);
+        return APM_OK;
+    }
     (void)hipSetDevice(pool->desc.hip_device);
     if (pool->upd_stream) (void)hipStreamSynchronize(pool->upd_stream);
     hipError_t e = hipDeviceSynchronize();
@@ -298,6 +306,7 @@ extern "C" int apm_pool_page_info(const apm_pool* pool, int64_t page, apm_page_i
 
 extern "C" void* apm_pool_state_ptr(const apm_pool* pool, int state, int64_t page) {
     if (!pool || !pool->stores(state) || page < 0 || page >= pool->desc.n_pages) return nullptr;
+    if (pool->desc.device == APM_DEV_FILE) return nullptr;
     return static_cast<char*>(pool->base[state]) + page * pool->desc.page_elems * elem_bytes(state);
 }
 
@@ -305,6 +314,7 @@ extern "C" int apm_pool_set_layout(apm_pool* pool, const apm_tensor* tensors, in
                                    apm_segment* segs, int64_t* n_segs, int64_t* n_pages,
                                    double* fragmentation, void* stream) {
     if (!pool) return fail(APM_EINVAL, "NULL pool");
+    if (pool->desc.device == APM_DEV_FILE) return fail(APM_EDEVICE, "a FILE pool takes its layout from the GPU pool it is used with");
     int rc = check_list(tensors, n);
     if (rc != APM_OK) return rc;
     APM_HIP(hipSetDevice(pool->desc.hip_device));
@@ -324,6 +334,7 @@ extern "C" int apm_pack_tensors(apm_pool* pool, int state, const apm_tensor* ten
                                 apm_segment* segs, int64_t* n_segs, int64_t* n_pages,
                                 double* fragmentation, void* stream) {
     if (!pool) return fail(APM_EINVAL, "NULL pool");
+    if (pool->desc.device == APM_DEV_FILE) return fail(APM_EDEVICE, "pack / unpack work on GPU and HOST pools");
     if (!pool->stores(state)) return fail(APM_ERANGE, "pool does not store state class %d", state);
     int rc = check_list(tensors, n);
     if (rc != APM_OK) return rc;
@@ -345,6 +356,7 @@ extern "C" int apm_pack_tensors(apm_pool* pool, int state, const apm_tensor* ten
 
 extern "C" int apm_unpack(apm_pool* pool, int state, const apm_tensor* dst, int64_t n, void* stream) {
     if (!pool) return fail(APM_EINVAL, "NULL pool");
+    if (pool->desc.device == APM_DEV_FILE) return fail(APM_EDEVICE, "pack / unpack work on GPU and HOST pools");
     if (!pool->stores(state)) return fail(APM_ERANGE, "pool does not store state class %d", state);
     int rc = check_list(dst, n);
     if (rc != APM_OK) return rc;
@@ -362,6 +374,10 @@ extern "C" int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* sr
     if (dst_page < 0 || dst_page + n_pages > dst->desc.n_pages || src_page < 0 || src_page + n_pages > src->desc.n_pages)
         return fail(APM_ERANGE, "page range out of bounds");
     if (n_pages == 0) return APM_OK;
+    if (dst->desc.device == APM_DEV_FILE || src->desc.device == APM_DEV_FILE) {
+        if (dst->desc.device == src->desc.device) return fail(APM_EDEVICE, "a FILE pool exchanges pages with HOST pools only");
+        return file_page_copy(dst, dst_page, src, src_page, n_pages, state, static_cast<hipStream_t>(stream));
+    }
     const size_t pb = (size_t)dst->desc.page_elems * (size_t)elem_bytes(state);
     char* d = static_cast<char*>(dst->base[state]) + (size_t)dst_page * pb;
     const char* s = static_cast<const char*>(src->base[state]) + (size_t)src_page * pb;

@@ -214,8 +214,6 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     return APM_OK;
 }
 
-namespace {
-
 int ensure_delayed(apm_pool* pool) {
     if (pool->upd_stream) return APM_OK;
     const size_t bytes = (size_t)pool->desc.n_pages * (size_t)pool->desc.page_elems * 2u;
@@ -241,8 +239,6 @@ int ensure_delayed(apm_pool* pool) {
     APM_HIP(hipStreamCreateWithFlags(&pool->upd_stream, hipStreamNonBlocking));
     return APM_OK;
 }
-
-}  // namespace
 
 // Applies the buffered gradient (half `cur`) on the update stream.
 static int apply_buffered(apm_pool* pool, const DelayedApply& apply) {

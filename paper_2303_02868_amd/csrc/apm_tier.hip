@@ -1,0 +1,472 @@
+// Third tier: fp32 master / momentum / variance pages live in files (the Page listing's device
+// map names SSD, Sec. 4.1; Alg. 2's updating actor fetches the states from SSD and offloads them
+// back).  A small window of pinned host memory is the only staging: I/O threads read batch b+1..
+// into free window slots and write finished batches back while the update kernel works on batch b
+// directly in the window, across PCIe (the streamer's direct mode; no HBM staging, no copies).
+//
+// File I/O is not stream-ordered, so a step is driven from the host: the calling thread (or, for
+// the one-step-stale form, the library's updater thread -- Alg. 2's two actors as two host
+// threads) waits for a slot's reads, enqueues the kernels, waits for their event and hands the
+// slot to the writers; the last write of a slot starts the reads of the batch that reuses it.
+#include <fcntl.h>
+#include <unistd.h>
+
+#include <cerrno>
+#include <condition_variable>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <string>
+#include <thread>
+
+#include "apm_internal.h"
+
+using namespace apm;
+
+namespace {
+
+constexpr size_t kIoPiece = (size_t)8 << 20;  // bytes per pread / pwrite task
+
+class IoPool {
+ public:
+    explicit IoPool(int n) {
+        for (int k = 0; k < n; ++k) thr_.emplace_back([this] { run(); });
+    }
+    ~IoPool() {
+        {
+            std::lock_guard<std::mutex> g(m_);
+            stop_ = true;
+        }
+        cv_.notify_all();
+        for (auto& t : thr_) t.join();
+    }
+    void submit(std::function<void()> f) {
+        {
+            std::lock_guard<std::mutex> g(m_);
+            q_.push_back(std::move(f));
+        }
+        cv_.notify_one();
+    }
+
+ private:
+    void run() {
+        for (;;) {
+            std::function<void()> f;
+            {
+                std::unique_lock<std::mutex> g(m_);
+                cv_.wait(g, [this] { return stop_ || !q_.empty(); });
+                if (q_.empty()) return;  // stop requested and nothing left
+                f = std::move(q_.front());
+                q_.pop_front();
+            }
+            f();
+        }
+    }
+    std::vector<std::thread> thr_;
+    std::deque<std::function<void()>> q_;
+    std::mutex m_;
+    std::condition_variable cv_;
+    bool stop_ = false;
+};
+
+// Reads or writes exactly `len` bytes at `off`; 0 or an errno value.
+int io_full(int fd, char* buf, size_t len, off_t off, bool write) {
+    while (len > 0) {
+        const ssize_t r = write ? pwrite(fd, buf, len, off) : pread(fd, buf, len, off);
+        if (r < 0) {
+            if (errno == EINTR) continue;
+            return errno;
+        }
+        if (r == 0) return EIO;  // a short file: the pool's files are created at full size
+        buf += r;
+        off += r;
+        len -= (size_t)r;
+    }
+    return 0;
+}
+
+// Unbuffered I/O cannot address GPU-pinned host memory directly (the kernel refuses to pin the
+// driver's mapping: EFAULT), so with APM_POOL_FILE_DIRECT every piece passes through an ordinary
+// page-aligned buffer of the calling thread.
+int io_piece(int fd, char* buf, size_t len, off_t off, bool write, bool direct) {
+    if (!direct) return io_full(fd, buf, len, off, write);
+    struct Bounce {
+        void* p = nullptr;
+        ~Bounce() { free(p); }
+    };
+    static thread_local Bounce bounce;
+    if (!bounce.p && posix_memalign(&bounce.p, 4096, kIoPiece) != 0) {
+        bounce.p = nullptr;
+        return ENOMEM;
+    }
+    char* b = static_cast<char*>(bounce.p);
+    while (len > 0) {
+        const size_t n = len < kIoPiece ? len : kIoPiece;
+        if (write) std::memcpy(b, buf, n);
+        const int err = io_full(fd, b, n, off, write);
+        if (err) return err;
+        if (!write) std::memcpy(buf, b, n);
+        buf += n;
+        off += (off_t)n;
+        len -= n;
+    }
+    return 0;
+}
+
+}  // namespace
+
+struct apm_tiered {
+    apm_pool* file = nullptr;
+    apm_pool* dev = nullptr;
+    int64_t B = 0;
+    int n_slots = 0;
+    char* win[3] = {nullptr, nullptr, nullptr};      // pinned window, n_slots * B pages per class
+    float* win_dev[3] = {nullptr, nullptr, nullptr};  // the same memory as the GPU addresses it
+    hipStream_t s_cmp = nullptr;
+    hipEvent_t ev_start = nullptr;
+    std::vector<hipEvent_t> ev_done;  // per slot
+    IoPool* io = nullptr;
+
+    // progress of the running step (guarded by m)
+    std::mutex m;
+    std::condition_variable cv;
+    std::vector<int64_t> loaded;    // per slot: batch whose pages are in the window, -1 = none
+    std::vector<int> pending;       // per slot: outstanding pieces of the current read or write
+    int64_t batches_written = 0;
+    int io_errno = 0;
+    int64_t n_batches = 0, n_pages = 0;
+
+    // one-step-stale form
+    std::thread updater;
+    bool updater_running = false;
+    int updater_rc = APM_OK;
+    std::string updater_err;
+    apm_hyper updater_hyper{};
+};
+
+namespace {
+
+void free_tiered(apm_tiered* t) {
+    if (t->updater.joinable()) t->updater.join();
+    delete t->io;  // drains and joins the I/O threads
+    (void)hipDeviceSynchronize();
+    for (char* p : t->win) if (p) (void)hipHostFree(p);
+    for (hipEvent_t e : t->ev_done) if (e) (void)hipEventDestroy(e);
+    if (t->ev_start) (void)hipEventDestroy(t->ev_start);
+    if (t->s_cmp) (void)hipStreamDestroy(t->s_cmp);
+    delete t;
+}
+
+// Queues the reads (write == false) or writes of batch b through the I/O threads.  When the last
+// piece of a write completes, the reads of the batch that reuses the slot are queued.
+void queue_io(apm_tiered* t, int64_t b, bool write) {
+    const int64_t E = t->dev->desc.page_elems;
+    const size_t pb = (size_t)E * sizeof(float);
+    const int slot = (int)(b % t->n_slots);
+    const int64_t first = b * t->B;
+    const int64_t nb = t->n_pages - first < t->B ? t->n_pages - first : t->B;
+    const size_t bytes = pb * (size_t)nb;
+    const int pieces_per_class = (int)((bytes + kIoPiece - 1) / kIoPiece);
+    {
+        std::lock_guard<std::mutex> g(t->m);
+        t->pending[(size_t)slot] = 3 * pieces_per_class;
+    }
+    const int states[3] = {APM_P32, APM_M32, APM_V32};
+    for (int c = 0; c < 3; ++c) {
+        for (int k = 0; k < pieces_per_class; ++k) {
+            const size_t o = (size_t)k * kIoPiece;
+            const size_t len = bytes - o < kIoPiece ? bytes - o : kIoPiece;
+            char* buf = t->win[c] + (size_t)slot * (size_t)t->B * pb + o;
+            const off_t off = (off_t)((size_t)first * pb + o);
+            const int fd = t->file->fd[states[c]];
+            const bool direct = (t->file->desc.flags & APM_POOL_FILE_DIRECT) != 0;
+            t->io->submit([t, b, slot, write, fd, buf, len, off, direct] {
+                const int err = io_piece(fd, buf, len, off, write, direct);
+                bool last = false;
+                {
+                    std::lock_guard<std::mutex> g(t->m);
+                    if (err && !t->io_errno) t->io_errno = err;
+                    last = --t->pending[(size_t)slot] == 0;
+                    if (last) {
+                        if (write) ++t->batches_written;
+                        else t->loaded[(size_t)slot] = b;
+                    }
+                }
+                if (!last) return;
+                if (write && b + t->n_slots < t->n_batches) queue_io(t, b + t->n_slots, false);
+                t->cv.notify_all();
+            });
+        }
+    }
+}
+
+// One step; blocks until the last write has completed.  caller != nullptr: the kernels start after
+// everything enqueued on that stream so far.
+int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16_t* g16_override,
+               float* grad_norm, uint8_t* skip_mask, bool have_caller, hipStream_t caller) {
+    apm_pool* dev = t->dev;
+    AdamwLaunch L{};
+    int rc = prepare_hyper(hyper, step, &L);
+    if (rc != APM_OK) return rc;
+    APM_HIP(hipSetDevice(dev->desc.hip_device));
+    const int64_t N = (int64_t)dev->plan.pages.size();
+    const int64_t E = dev->desc.page_elems;
+    if (have_caller) {
+        APM_HIP(hipEventRecord(t->ev_start, caller));
+        APM_HIP(hipStreamWaitEvent(t->s_cmp, t->ev_start, 0));
+    }
+    L.g16 = g16_override ? g16_override : static_cast<const uint16_t*>(dev->base[APM_G16]);
+    L.p16 = static_cast<uint16_t*>(dev->base[APM_P16]);
+    L.used = dev->d_used;
+    L.E = E;
+    L.S = dev->S;
+    L.p32 = t->win_dev[0];
+    L.m32 = t->win_dev[1];
+    L.v32 = t->win_dev[2];
+    L.meta = dev->d_meta;
+    L.stride_wavefronts = 64;
+    L.stride_waves_per_wg = 1;
+    const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
+    if (need_reduce) {
+        L.partials = dev->d_partials;
+        L.nzflags = dev->d_nzflags;
+    }
+    {
+        std::lock_guard<std::mutex> g(t->m);
+        t->n_pages = N;
+        t->n_batches = (N + t->B - 1) / t->B;
+        t->batches_written = 0;
+        t->io_errno = 0;
+        for (auto& x : t->loaded) x = -1;
+        for (auto& x : t->pending) x = 0;
+    }
+    const int64_t nbatches = t->n_batches;
+    for (int64_t b = 0; b < nbatches && b < t->n_slots; ++b) queue_io(t, b, false);
+    hipError_t gpu_err = hipSuccess;
+    for (int64_t b = 0; b < nbatches; ++b) {
+        const int slot = (int)(b % t->n_slots);
+        {
+            std::unique_lock<std::mutex> g(t->m);
+            t->cv.wait(g, [&] { return t->loaded[(size_t)slot] == b; });
+        }
+        const int64_t first = b * t->B;
+        const int64_t nb = N - first < t->B ? N - first : t->B;
+        // Kernels are skipped after a failure, but every batch still passes through the writers so
+        // that the slot chain keeps moving and the step drains.
+        bool failed;
+        {
+            std::lock_guard<std::mutex> g(t->m);
+            failed = t->io_errno != 0;
+        }
+        if (!failed && gpu_err == hipSuccess) {
+            AdamwLaunch C = L;
+            C.state_first = (int64_t)slot * t->B;
+            C.grad_first = first;
+            C.n_listed = nb;
+            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+            gpu_err = need_reduce ? launch_grad_reduce(C, t->s_cmp) : launch_prepare(C, t->s_cmp);
+            if (gpu_err == hipSuccess) gpu_err = launch_adamw(C, t->s_cmp);
+            if (gpu_err == hipSuccess) gpu_err = hipEventRecord(t->ev_done[(size_t)slot], t->s_cmp);
+            if (gpu_err == hipSuccess) gpu_err = hipEventSynchronize(t->ev_done[(size_t)slot]);
+        }
+        if (!failed && gpu_err == hipSuccess) {
+            queue_io(t, b, true);
+        } else {
+            // nothing valid to write: account for the batch and keep the chain going
+            {
+                std::lock_guard<std::mutex> g(t->m);
+                ++t->batches_written;
+            }
+            if (b + t->n_slots < nbatches) queue_io(t, b + t->n_slots, false);
+        }
+    }
+    {
+        std::unique_lock<std::mutex> g(t->m);
+        t->cv.wait(g, [&] { return t->batches_written == nbatches; });
+        if (t->io_errno) return fail(APM_EDEVICE, "file I/O failed during the step: %s (the files may hold a partly updated state)", strerror(t->io_errno));
+    }
+    if (gpu_err != hipSuccess) return fail(APM_EDEVICE, "a kernel launch of the step failed: %s", hipGetErrorString(gpu_err));
+    return APM_OK;
+}
+
+int join_updater(apm_tiered* t) {
+    if (!t->updater_running) return APM_OK;
+    t->updater.join();
+    t->updater_running = false;
+    if (t->updater_rc != APM_OK) return fail(t->updater_rc, "the background update failed: %s", t->updater_err.c_str());
+    return APM_OK;
+}
+
+}  // namespace
+
+extern "C" int apm_file_pool_create(apm_pool** out, const char* path_prefix, int32_t hip_device,
+                                    int64_t page_elems, int64_t n_pages, uint32_t state_mask,
+                                    uint32_t flags) {
+    if (!out || !path_prefix || !*path_prefix) return fail(APM_EINVAL, "NULL argument or empty path prefix");
+    if (page_elems <= 0 || page_elems % kAlign != 0 || page_elems > (int64_t)1 << 30) return fail(APM_EINVAL, "page_elems must be a positive multiple of %lld, at most 2^30", (long long)kAlign);
+    if (n_pages <= 0) return fail(APM_EINVAL, "n_pages must be positive");
+    if (state_mask == 0 || state_mask >> APM_N_STATES) return fail(APM_EINVAL, "bad state_mask 0x%x", state_mask);
+    if (flags & ~(uint32_t)(APM_POOL_NO_ZERO | APM_POOL_FILE_DIRECT)) return fail(APM_EINVAL, "unknown flags 0x%x", flags);
+    apm_pool* pool = new apm_pool();
+    pool->desc.device = APM_DEV_FILE;
+    pool->desc.hip_device = hip_device;
+    pool->desc.page_elems = page_elems;
+    pool->desc.n_pages = n_pages;
+    pool->desc.state_mask = state_mask;
+    pool->desc.flags = flags;
+    static const char* const suffix[APM_N_STATES] = {".p32", ".m32", ".v32", ".g16", ".p16"};
+    for (int st = 0; st < APM_N_STATES; ++st) {
+        if (!pool->stores(st)) continue;
+        const size_t page_bytes = (size_t)page_elems * (size_t)elem_bytes(st);
+        if ((flags & APM_POOL_FILE_DIRECT) && page_bytes % 4096 != 0) {
+            apm_pool_destroy(pool);
+            return fail(APM_EINVAL, "unbuffered file I/O needs pages of a multiple of 4096 bytes (class %d has %zu)", st, page_bytes);
+        }
+        const std::string path = std::string(path_prefix) + suffix[st];
+        int oflags = O_RDWR | O_CREAT | O_CLOEXEC;
+        if (!(flags & APM_POOL_NO_ZERO)) oflags |= O_TRUNC;  // recreated at full size below: reads as zeros
+        if (flags & APM_POOL_FILE_DIRECT) oflags |= O_DIRECT;
+        const int fd = open(path.c_str(), oflags, 0600);
+        if (fd < 0 || ftruncate(fd, (off_t)(page_bytes * (size_t)n_pages)) != 0) {
+            const int err = errno;
+            if (fd >= 0) close(fd);
+            apm_pool_destroy(pool);
+            return fail(APM_EDEVICE, "cannot create %s: %s", path.c_str(), strerror(err));
+        }
+        pool->fd[st] = fd;
+    }
+    *out = pool;
+    return APM_OK;
+}
+
+namespace apm {
+// FILE <-> HOST page copy, done before returning (file I/O is not stream-ordered; the caller's
+// stream is synchronised first so that the host pages are what the stream left there).
+int file_page_copy(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_page, int64_t n_pages,
+                   int state, hipStream_t stream) {
+    apm_pool* file = dst->desc.device == APM_DEV_FILE ? dst : src;
+    apm_pool* host = dst->desc.device == APM_DEV_FILE ? src : dst;
+    if (host->desc.device != APM_DEV_HOST) return fail(APM_EDEVICE, "a FILE pool exchanges pages with HOST pools only");
+    const bool write = file == dst;
+    APM_HIP(hipSetDevice(host->desc.hip_device));
+    APM_HIP(hipStreamSynchronize(stream));
+    const size_t pb = (size_t)file->desc.page_elems * (size_t)elem_bytes(state);
+    char* buf = static_cast<char*>(host->base[state]) + (size_t)(write ? src_page : dst_page) * pb;
+    const off_t off = (off_t)((size_t)(write ? dst_page : src_page) * pb);
+    const int err = io_piece(file->fd[state], buf, pb * (size_t)n_pages, off, write,
+                             (file->desc.flags & APM_POOL_FILE_DIRECT) != 0);
+    if (err) return fail(APM_EDEVICE, "file %s of %lld pages failed: %s", write ? "write" : "read", (long long)n_pages, strerror(err));
+    return APM_OK;
+}
+}  // namespace apm
+
+extern "C" int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev, int64_t batch_pages,
+                                 int n_slots, int io_threads) {
+    if (!out || !file || !dev) return fail(APM_EINVAL, "NULL argument");
+    if (file->desc.device != APM_DEV_FILE || dev->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "expected a FILE pool and a GPU pool");
+    for (int st : {APM_P32, APM_M32, APM_V32}) if (!file->stores(st)) return fail(APM_ESTATE, "file pool lacks fp32 class %d", st);
+    for (int st : {APM_G16, APM_P16}) if (!dev->stores(st)) return fail(APM_ESTATE, "GPU pool lacks 16-bit class %d", st);
+    if (file->desc.page_elems != dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
+    if (file->desc.n_pages < dev->desc.n_pages) return fail(APM_EINVAL, "file pool has fewer pages than the GPU pool");
+    if (batch_pages < 1 || batch_pages > dev->desc.n_pages) return fail(APM_EINVAL, "batch_pages out of range");
+    if (n_slots < 2 || n_slots > 64) return fail(APM_EINVAL, "n_slots must be in [2, 64]");
+    if (io_threads < 1 || io_threads > 64) return fail(APM_EINVAL, "io_threads must be in [1, 64]");
+    APM_HIP(hipSetDevice(dev->desc.hip_device));
+    apm_tiered* t = new apm_tiered();
+    t->file = file; t->dev = dev; t->B = batch_pages; t->n_slots = n_slots;
+    const size_t bytes = (size_t)n_slots * (size_t)batch_pages * (size_t)dev->desc.page_elems * sizeof(float);
+    hipError_t e = hipSuccess;
+    for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+        e = hipHostMalloc((void**)&t->win[k], bytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&t->win_dev[k], t->win[k], 0);
+    }
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        free_tiered(t);
+        return fail(APM_ENOMEM, "allocating 3 x %zu bytes of pinned window failed: %s", bytes, hipGetErrorString(e));
+    }
+    e = hipStreamCreateWithFlags(&t->s_cmp, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&t->ev_start, hipEventDisableTiming);
+    t->ev_done.assign((size_t)n_slots, nullptr);
+    for (int k = 0; k < n_slots && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&t->ev_done[(size_t)k], hipEventDisableTiming);
+    if (e != hipSuccess) {
+        free_tiered(t);
+        return fail(APM_EDEVICE, "creating the stream / events failed: %s", hipGetErrorString(e));
+    }
+    int rc = ensure_scratch(dev);
+    if (rc != APM_OK) { free_tiered(t); return rc; }
+    t->loaded.assign((size_t)n_slots, -1);
+    t->pending.assign((size_t)n_slots, 0);
+    t->io = new IoPool(io_threads);
+    *out = t;
+    return APM_OK;
+}
+
+extern "C" int apm_tiered_destroy(apm_tiered* t) {
+    if (!t) return APM_OK;
+    (void)hipSetDevice(t->dev->desc.hip_device);
+    free_tiered(t);
+    return APM_OK;
+}
+
+extern "C" int apm_tiered_step(apm_tiered* t, int64_t step, const apm_hyper* hyper, float* grad_norm,
+                               uint8_t* skip_mask, void* stream) {
+    if (!t) return fail(APM_EINVAL, "NULL handle");
+    if (!t->dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+    int rc = join_updater(t);
+    if (rc != APM_OK) return rc;
+    return tiered_run(t, step, hyper, nullptr, grad_norm, skip_mask, true, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const apm_hyper* hyper,
+                                       void* stream) {
+    if (!t) return fail(APM_EINVAL, "NULL handle");
+    apm_pool* dev = t->dev;
+    if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+    AdamwLaunch probe{};
+    int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
+    if (rc != APM_OK) return rc;
+    APM_HIP(hipSetDevice(dev->desc.hip_device));
+    rc = ensure_delayed(dev);
+    if (rc != APM_OK) return rc;
+    for (int k = 0; k < 2 && new_g16; ++k)  // the updater reads the halves with no stream-side guard
+        if (new_g16 == static_cast<const void*>(dev->gbuf[k])) return fail(APM_EINVAL, "the zero-copy hand-over (apm_delayed_grad_buffer) is not available with file-resident state: pass the producer's own buffer");
+    // One updater at a time: the update handed over by the previous call must have finished
+    // before the next one starts (and before the half it read is staged into again).
+    rc = join_updater(t);
+    if (rc != APM_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dev->buffered) {
+        const int k = dev->cur;
+        dev->applied += 1;
+        dev->buffered = false;
+        t->updater_hyper = *hyper;
+        const int64_t step_no = dev->applied;
+        const uint16_t* g16 = dev->gbuf[k];
+        hipEvent_t staged = dev->ev_staged[k];
+        float* norm = dev->delayed_norm;
+        uint8_t* skip = dev->delayed_skip;
+        t->updater_running = true;
+        t->updater = std::thread([t, step_no, g16, staged, norm, skip] {
+            // Alg. 2's updating actor: waits for the handed-over gradient, then fetches, updates
+            // and offloads the states batch by batch.
+            int rc2 = APM_OK;
+            if (hipSetDevice(t->dev->desc.hip_device) != hipSuccess || hipEventSynchronize(staged) != hipSuccess)
+                rc2 = fail(APM_EDEVICE, "waiting for the staged gradient failed");
+            if (rc2 == APM_OK) rc2 = tiered_run(t, step_no, &t->updater_hyper, g16, norm, skip, false, nullptr);
+            t->updater_rc = rc2;
+            if (rc2 != APM_OK) t->updater_err = apm_last_error();
+        });
+    }
+    if (!new_g16) return join_updater(t);  // flush: the update has completed when this returns
+    const int nxt = dev->cur ^ 1;
+    const int64_t N = (int64_t)dev->plan.pages.size();
+    const size_t bytes = (size_t)N * (size_t)dev->desc.page_elems * 2u;
+    APM_HIP(hipMemcpyAsync(dev->gbuf[nxt], new_g16, bytes, hipMemcpyDeviceToDevice, s));
+    APM_HIP(hipEventRecord(dev->ev_staged[nxt], s));
+    dev->cur = nxt;
+    dev->buffered = true;
+    return APM_OK;
+}

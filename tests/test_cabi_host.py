@@ -157,3 +157,36 @@ def test_schedule_plan_on_a_model_sized_trace_and_its_errors():
         apm.apm_schedule_plan([([0], 0), ([1], 0)], [0, 0], 1, 10)
     assert e.value.code == apm.APM_EINVAL
     assert apm.apm_schedule_plan([], None, 1, 0) == ([], 0)
+
+
+def test_file_pool_files_sizes_flags_and_refusals(tmp_path):
+    # a FILE pool needs no GPU: one file per stored class, full size, zeros; reopening keeps contents
+    E, n = 2048, 5
+    prefix = str(tmp_path / "state")
+    pool = apm.apm_file_pool_create(prefix, E, n, state_mask=apm.FP32_STATES | (1 << apm.APM_P16))
+    for suffix, eb in ((".p32", 4), (".m32", 4), (".v32", 4), (".p16", 2)):
+        assert os.path.getsize(prefix + suffix) == n * E * eb
+    assert not os.path.exists(prefix + ".g16")
+    assert open(prefix + ".m32", "rb").read() == bytes(n * E * 4)
+    assert apm.apm_pool_state_ptr(pool, apm.APM_P32) is None
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_pack_tensors(pool, apm.APM_P32, apm.make_tensors([10], apm.APM_F32), 1)
+    assert e.value.code == apm.APM_EDEVICE
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_page_copy_async(pool, 0, pool, 1, 1, apm.APM_P32)
+    assert e.value.code in (apm.APM_EDEVICE, apm.APM_EINVAL)
+    pool.destroy()
+    with open(prefix + ".p32", "r+b") as f:
+        f.write(b"\x01\x02\x03\x04")
+    again = apm.apm_file_pool_create(prefix, E, n, flags=apm.APM_POOL_NO_ZERO)
+    again.destroy()
+    assert open(prefix + ".p32", "rb").read(4) == b"\x01\x02\x03\x04"
+    fresh = apm.apm_file_pool_create(prefix, E, n)
+    fresh.destroy()
+    assert open(prefix + ".p32", "rb").read(4) == bytes(4)
+    with pytest.raises(apm.ApmError) as e:                      # 8-element pages of 32 bytes cannot be unbuffered
+        apm.apm_file_pool_create(prefix, 8, n, flags=apm.APM_POOL_FILE_DIRECT)
+    assert e.value.code == apm.APM_EINVAL
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_file_pool_create(str(tmp_path / "no_such_dir" / "x"), E, n)
+    assert e.value.code == apm.APM_EDEVICE

@@ -337,3 +337,106 @@ def test_streamer_delayed_calls_plus_flush_equal_synchronous_steps(mode):
         dev.destroy()
     produce.destroy()
     init.destroy()
+
+
+def file_rows(prefix, suffix, n_pages, E):
+    return np.fromfile(prefix + suffix, dtype=np.uint32).reshape(n_pages, E)
+
+
+@pytest.mark.parametrize("batch,slots,threads,flags", [(5, 2, 3, 0), (16, 3, 8, "direct"), (300, 2, 4, 0)])
+def test_file_tier_step_equals_resident_bit_exact(tmp_path, batch, slots, threads, flags):
+    # fp32 state in files, a pinned window as the only staging; results must equal the resident path
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=8)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    prefix = str(tmp_path / "state")
+    fl = apm.APM_POOL_FILE_DIRECT if flags == "direct" else 0
+    filep = apm.apm_file_pool_create(prefix, E, n_pages, flags=fl)
+    # initial master parameters reach the files through a host pool
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    apm.apm_page_copy_async(filep, 0, host, 0, n_pages, apm.APM_P32)
+    tier = apm.apm_tiered_create(filep, dev.pool, min(batch, n_pages), slots, threads)
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, None)
+        apm.apm_tiered_step(tier, t, hy, norm_s, None)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s)
+    tier.destroy()
+    filep.destroy()
+    for s_, suffix in ((apm.APM_P32, ".p32"), (apm.APM_M32, ".m32"), (apm.APM_V32, ".v32")):
+        want = res.reg[s_].cpu().numpy().view(np.uint32)
+        assert np.array_equal(file_rows(prefix, suffix, n_pages, E), want), f"state {s_}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    # the read-back path: file -> host pool
+    filep = apm.apm_file_pool_create(prefix, E, n_pages, flags=apm.APM_POOL_NO_ZERO)
+    apm.apm_page_copy_async(host, 3, filep, 3, n_pages - 3, apm.APM_P32)
+    assert np.array_equal(host_view(host, apm.APM_P32, n_pages, E)[3:].view(np.uint32),
+                          res.reg[apm.APM_P32][3:].cpu().numpy().view(np.uint32))
+    filep.destroy()
+    host.destroy()
+    dev.destroy()
+    res.destroy()
+
+
+def test_file_tier_delayed_calls_plus_flush_equal_synchronous_steps(tmp_path):
+    # Alg. 2 with its two actors as host threads: the updater thread works through the files while
+    # the caller hands over the next gradient
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=9)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    init = DevicePool(n_pages, E, states=(apm.APM_P32,))
+    apm.apm_pack_tensors(init.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
+    apm.apm_page_copy_async(host, 0, init.pool, 0, n_pages, apm.APM_P32)
+    sides = []
+    for name in ("sync", "stale"):
+        dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+        apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+        prefix = str(tmp_path / name)
+        filep = apm.apm_file_pool_create(prefix, E, n_pages)
+        apm.apm_page_copy_async(filep, 0, host, 0, n_pages, apm.APM_P32)
+        sides.append((dev, filep, apm.apm_tiered_create(filep, dev.pool, 16, 3, 6), prefix))
+    (dev_a, file_a, tier_a, pre_a), (dev_b, file_b, tier_b, pre_b) = sides
+    produce = DevicePool(n_pages, E, states=(apm.APM_G16,))
+    apm.apm_pool_set_layout(produce.pool, model.tensors(model.p_flat), n_t)
+    norm_a = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_b = torch.full((n_pages,), -1.0, dtype=torch.float32, device=DEV)
+    apm.apm_delayed_set_outputs(dev_b.pool, norm_b, None)
+    steps = 4
+    for t in range(1, steps + 1):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(dev_a.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_tiered_step(tier_a, t, hy, norm_a, None)
+        apm.apm_pack_tensors(produce.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_tiered_step_delayed(tier_b, produce.reg[apm.APM_G16], hy)
+        assert apm.apm_delayed_applied(dev_b.pool) == t - 1
+    with pytest.raises(apm.ApmError) as e:          # the ping-pong halves are not handed out here
+        apm.apm_tiered_step_delayed(tier_b, apm.apm_delayed_grad_buffer(dev_b.pool), hy)
+    assert e.value.code == apm.APM_EINVAL
+    apm.apm_tiered_step_delayed(tier_b, None, hy)
+    torch.cuda.synchronize()
+    assert apm.apm_delayed_applied(dev_b.pool) == steps
+    assert torch.equal(norm_a, norm_b)
+    for dev, filep, tier, prefix in sides:
+        tier.destroy()
+        filep.destroy()
+    for suffix in (".p32", ".m32", ".v32"):
+        assert np.array_equal(file_rows(pre_a, suffix, n_pages, E), file_rows(pre_b, suffix, n_pages, E)), suffix
+    assert torch.equal(dev_a.reg[apm.APM_P16].view(torch.int16), dev_b.reg[apm.APM_P16].view(torch.int16))
+    for dev, *_ in sides:
+        dev.destroy()
+    produce.destroy()
+    host.destroy()
+    init.destroy()
