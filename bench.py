@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--no-streamed", action="store_true", help="skip the host-streamed leg")
     ap.add_argument("--streamed-only", action="store_true", help="run only the host-streamed leg (gpt_13b: always)")
     ap.add_argument("--stream-steps", type=int, default=3)
+    ap.add_argument("--file-tier", default=None, metavar="DIR",
+                    help="run only the file-tier leg, with the fp32 state in files under DIR")
+    ap.add_argument("--io-threads", type=int, default=8)
     ap.add_argument("--sched-layers", type=float, default=3.0,
                     help="GPU memory of the scheduled streaming leg, in units of the largest block")
     ap.add_argument("--direct-wavefronts", type=int, default=0,
@@ -502,6 +505,87 @@ def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
     return out
 
 
+def file_tier_leg(args, wl, hyper, n_pages):
+    """fp32 state in files under --file-tier DIR, streamed through a pinned window (buffered and
+    unbuffered I/O), and the one-step-stale form beside a matrix-product producer."""
+    import torch
+    import paper_2303_02868_amd as apm
+    E = wl.E
+    dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=apm.B16_STATES)
+    apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
+    tmp = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=1 << apm.APM_P32)
+    apm.apm_pack_tensors(tmp, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    apm.apm_page_copy_async(host, 0, tmp, 0, n_pages, apm.APM_P32)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    each_way = n_pages * E * 12
+    out = {"dir": args.file_tier, "bytes_each_way": each_way, "batch_pages": min(args.batch_pages, n_pages),
+           "slots": args.slots, "io_threads": args.io_threads}
+    for name, flags in (("buffered", 0), ("unbuffered", apm.APM_POOL_FILE_DIRECT)):
+        prefix = os.path.join(args.file_tier, f"apm_bench_{os.getpid()}_{name}")
+        filep = apm.apm_file_pool_create(prefix, E, n_pages, flags=flags)
+        t0 = time.perf_counter()
+        apm.apm_page_copy_async(filep, 0, host, 0, n_pages, apm.APM_P32)
+        t_init = time.perf_counter() - t0
+        tier = apm.apm_tiered_create(filep, dev_pool, min(args.batch_pages, n_pages), args.slots, args.io_threads)
+        apm.apm_tiered_step(tier, 1, hyper, None, None, stream)
+        ts = []
+        for k in range(args.stream_steps):
+            t0 = time.perf_counter()
+            apm.apm_tiered_step(tier, 2 + k, hyper, None, None, stream)
+            ts.append(time.perf_counter() - t0)
+        res = {"write_p32_GBps": n_pages * E * 4 / t_init / 1e9, "ms_per_step": min(ts) * 1e3,
+               "ms_per_step_all": [t * 1e3 for t in ts], "io_GBps_each_way": each_way / min(ts) / 1e9,
+               "params_per_s": wl.total / min(ts)}
+        if name == "unbuffered":
+            # Alg. 2: products (stand-in for forward/backward) sized to one update, then the update;
+            # against the update running on the library's updater thread beside the products
+            n = 8192
+            a = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
+            b = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
+            c = torch.empty(n, n, device=DEV, dtype=torch.bfloat16)
+            for _ in range(10):
+                torch.matmul(a, b, out=c)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(50):
+                torch.matmul(a, b, out=c)
+            torch.cuda.synchronize()
+            reps = max(1, int(round(min(ts) / ((time.perf_counter() - t0) / 50))))
+            g16 = apm.apm_pool_state_ptr(dev_pool, apm.APM_G16)
+
+            def products():
+                for _ in range(reps):
+                    torch.matmul(a, b, out=c)
+                torch.cuda.synchronize()          # the producer's gradient is complete
+
+            iters = 3
+            t0 = time.perf_counter()
+            for k in range(iters):
+                products()
+                apm.apm_tiered_step(tier, 10 + k, hyper, None, None, stream)
+            t_sync = (time.perf_counter() - t0) / iters
+            apm.apm_tiered_step_delayed(tier, g16, hyper, stream)
+            t0 = time.perf_counter()
+            for k in range(iters):
+                apm.apm_tiered_step_delayed(tier, g16, hyper, stream)
+                products()
+            t_stale = (time.perf_counter() - t0) / iters
+            apm.apm_tiered_step_delayed(tier, None, hyper, stream)
+            res["lock_free"] = {"producer": f"{reps} bf16 {n}^3 matrix products per iteration",
+                                "synchronous_ms_per_iter": t_sync * 1e3, "one_step_stale_ms_per_iter": t_stale * 1e3,
+                                "speedup": t_sync / t_stale}
+        tier.destroy()
+        filep.destroy()
+        for suffix in (".p32", ".m32", ".v32"):
+            os.remove(prefix + suffix)
+        out[name] = res
+    for p in (tmp, host, dev_pool):
+        p.destroy()
+    return out
+
+
 def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
     """fp32 state in pinned host pages; dev_pool supplies G16/P16 and the layout."""
     import torch
@@ -603,6 +687,15 @@ def main():
            "config": {"workload": args.workload, "params": wl.total, "pages": n_pages, "page_elems": E,
                       "fragmentation": plan.fragmentation, "clip": clip, "skip_mode": skip}}
 
+    if args.file_tier:
+        out["file_tier"] = file_tier_leg(args, wl, hyper, n_pages)
+        out["value"] = out["file_tier"]["unbuffered"]["params_per_s"]
+        out["ms_per_step"] = out["file_tier"]["unbuffered"]["ms_per_step"]
+        out["steps"], out["warmup"] = args.stream_steps, 1
+        out["config"]["step"] = "files -> pinned window -> AdamW kernel across PCIe -> files (unbuffered I/O)"
+        out["config"]["state"] = "fp32 p/m/v in files, bf16 g/p16 resident in HBM"
+        print(json.dumps(out))
+        return
     if not streamed_only:
         pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages)
         p_flat = wl.gen(1, False, 0.02)
