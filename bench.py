@@ -3,13 +3,19 @@
 
 Resident leg (the headline `value`): a step is one pass of the whole path over one batch of
 synthetic gradients,
-  pack g16 (tensors -> pages) -> per-page grad reduce -> fused page AdamW -> unpack p16,
+  per-page grad reduce -> fused page AdamW, both reading g16 from the gradient tensors, p16
+  written to the parameter tensors (`--unfused`: separate pack g16 / unpack p16 kernels),
 with the pool and the packing plan set up once (the method pre-allocates them) and every input
 resident in HBM before the timed region.
 
 Streamed leg (reported under "streamed"): the fp32 master / momentum / variance pages live in
-pinned host memory and pass through HBM staging slots, copy-in, update and copy-out overlapped on
-three streams; the PCIe rate is compared with plain pinned copies measured in the same run.
+pinned host memory.  Measured: the direct mode (the update kernel reads and writes the host pages
+across PCIe itself), the staged mode (pages pass through HBM staging slots; copy-in, update and
+copy-out on three streams) with its copy-only pipeline, the schedule-driven mode ("scheduled"),
+mixed residency, and the one-step-stale update beside a matrix-product producer ("lock_free").
+The PCIe rates are held against plain pinned copies measured in the same run.
+
+`--file-tier DIR` runs only the third-tier leg (fp32 state in files under DIR).
 """
 from __future__ import annotations
 
