@@ -1,6 +1,7 @@
 """Page copies and the streamed (host-resident fp32 state) update: copies are bit-exact, and the
 streamed step is bit-identical to the resident step."""
 import ctypes
+import os
 
 import numpy as np
 import pytest
@@ -440,3 +441,34 @@ def test_file_tier_delayed_calls_plus_flush_equal_synchronous_steps(tmp_path):
     produce.destroy()
     host.destroy()
     init.destroy()
+
+
+def test_file_tier_reports_a_failed_read_and_drains(tmp_path):
+    # a state file cut short behind the pool's back: reads beyond its end fail; the step must
+    # come back with an error (no hang, every queued batch accounted for) and work again afterwards
+    E = 4096
+    specs = [synth.TensorSpec(0, "a", 40 * E)]
+    model = Model(specs, E, seed=1)
+    n_pages = model.plan.n_pages
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), 1)
+    prefix = str(tmp_path / "cut")
+    filep = apm.apm_file_pool_create(prefix, E, n_pages)
+    tier = apm.apm_tiered_create(filep, dev.pool, 4, 2, 3)
+    hy = to_hyper(oracle.Hyper())
+    apm.apm_tiered_step(tier, 1, hy)
+    os.truncate(prefix + ".m32", 10 * E * 4)
+    with pytest.raises(apm.ApmError) as e:
+        apm.apm_tiered_step(tier, 2, hy)
+    assert e.value.code == apm.APM_EDEVICE and "I/O" in str(e.value)
+    with pytest.raises(apm.ApmError) as e:          # the background form reports it on the next call
+        apm.apm_tiered_step_delayed(tier, dev.reg[apm.APM_G16], hy)
+        apm.apm_tiered_step_delayed(tier, dev.reg[apm.APM_G16], hy)
+        apm.apm_tiered_step_delayed(tier, None, hy)
+    assert e.value.code == apm.APM_EDEVICE
+    os.truncate(prefix + ".m32", n_pages * E * 4)
+    apm.apm_tiered_step(tier, 3, hy)
+    torch.cuda.synchronize()
+    tier.destroy()
+    filep.destroy()
+    dev.destroy()
