@@ -190,3 +190,41 @@ def test_file_pool_files_sizes_flags_and_refusals(tmp_path):
     with pytest.raises(apm.ApmError) as e:
         apm.apm_file_pool_create(str(tmp_path / "no_such_dir" / "x"), E, n)
     assert e.value.code == apm.APM_EDEVICE
+
+
+def test_header_is_plain_c_and_callable_from_a_c_program(tmp_path):
+    # include/apm.h under a strict C99 compiler, linked against the built library; the program
+    # calls the two host-only planners
+    import subprocess
+    src = tmp_path / "cabi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "apm.h"
+int main(void) {
+    int64_t numels[3] = {3000000, 17, 1048576};
+    apm_segment segs[16];
+    int64_t n_segs = 16, n_pages = 0, n_tasks = 8, peak = 0;
+    double frag = 0;
+    int64_t offsets[3] = {0, 2, 3}, pages[3] = {0, 1, 2}, sizes[2] = {0, 0};
+    apm_task tasks[8];
+    int rc = apm_pack_plan(1048576, numels, 3, segs, &n_segs, &n_pages, &frag);
+    if (rc != APM_OK) return 1;
+    printf("%lld %lld %.9f\n", (long long)n_segs, (long long)n_pages, frag);
+    rc = apm_schedule_plan(offsets, pages, sizes, 2, NULL, 3, 4, 8, tasks, &n_tasks, &peak);
+    if (rc != APM_OK) return 2;
+    printf("%lld %lld", (long long)n_tasks, (long long)peak);
+    for (int k = 0; k < (int)n_tasks; ++k) printf(" %d:%lld@%d", tasks[k].op, (long long)tasks[k].target, tasks[k].trigger_id);
+    printf("\n%s|\n", apm_last_error());
+    return 0;
+}
+''')
+    exe = tmp_path / "cabi"
+    libdir = os.path.dirname(apm.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), apm.LIB_PATH, f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines()
+    plan = oracle.plan_pack([3000000, 17, 1048576], 1048576)
+    assert out[0] == f"{len(plan.segments)} {plan.n_pages} {plan.fragmentation:.9f}"
+    # two pages fit: the move of page 2 is taken off for layer 0 and put back right after its compute
+    assert out[1] == "5 8 0:0@0 0:1@0 1:0@0 0:2@0 1:1@1"
+    assert out[2] == "|"
