@@ -280,8 +280,10 @@ __global__ __launch_bounds__(kThreads) void apm_grad_finalize_kernel(FinalizeArg
     const double norm = sqrt(s);
     float scale = 1.0f;
     if (a.max_norm > 0.0) {
+        // min(1, c / (norm + 1e-6)) with plain IEEE propagation: an infinite norm gives 0, a NaN
+        // norm a NaN scale (the comparison below is false for NaN), as the library optimizers do
         const double sc = a.max_norm / (norm + 1e-6);
-        if (sc < 1.0) scale = (float)sc;
+        scale = sc > 1.0 ? 1.0f : (float)sc;
     }
     PageMeta pm;
     pm.used = used;

@@ -388,6 +388,52 @@ def test_pages_of_very_different_extents_in_a_permuted_list(stepper):
     dp.destroy()
 
 
+@pytest.mark.parametrize("clip", [0.0, 0.5])
+def test_non_finite_gradients_propagate_as_in_the_oracle(clip):
+    # inf and NaN gradients get no special treatment: the same elements become NaN on both sides
+    # (a NaN page norm poisons its whole page when clipping is on, an infinite one zeroes the
+    # page's finite gradients), and everything that stays finite passes the usual gate
+    E, n_pages = 4096, 4
+    dp = DevicePool(n_pages, E)
+    p = synth.normal_f32(0, 1, 0, n_pages * E, 0.02, device=DEV)
+    tens_p = apm.make_tensors([n_pages * E], apm.APM_F32, [p])
+    apm.apm_pack_tensors(dp.pool, apm.APM_P32, tens_p, 1)
+    st = oracle.PagedAdamWState(p.view(n_pages, E).cpu().numpy(), [E] * n_pages)
+    hy_o = oracle.Hyper(max_grad_norm=clip)
+    hy = to_hyper(hy_o)
+    norm_d = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in (1, 2):
+        g = synth.normal_bf16(0, 1000 + t, 0, n_pages * E, 0.05, device=DEV).view(n_pages, E).clone()
+        if t == 1:
+            g[0, 5] = float("inf")
+            g[1, 7] = float("nan")
+            g[2, 9] = float("-inf")
+            g[2, 4000] = float("nan")
+        dp.reg[apm.APM_G16].copy_(g)
+        apm.apm_page_adamw_step(dp.pool, None, n_pages, t, hy, norm_d, None)
+        torch.cuda.synchronize()
+        with np.errstate(all="ignore"):
+            norms, _ = st.step(bf16_bits(g), t, hy_o)
+        got = norm_d.cpu().numpy()
+        assert np.array_equal(np.isnan(got), np.isnan(norms)) and np.array_equal(np.isinf(got), np.isinf(norms))
+        fin = np.isfinite(norms)
+        assert np.all(np.abs(got[fin] - norms[fin]) <= 1e-6 * np.abs(norms[fin]))
+    pages = list(range(n_pages))
+    n_nan = 0
+    for name, state, want in (("p", apm.APM_P32, st.p), ("m", apm.APM_M32, st.m), ("v", apm.APM_V32, st.v)):
+        got = dp.rows_f32(state, pages).astype(np.float64)
+        assert np.array_equal(np.isnan(got), np.isnan(want)), f"{name}: NaN in different places"
+        assert np.array_equal(np.isinf(got), np.isinf(want)) and np.array_equal(got[np.isinf(got)], want[np.isinf(want)])
+        ok = np.isfinite(want)
+        assert np.all(np.abs(got[ok] - want[ok]) <= np.maximum(1e-6 * np.abs(want[ok]), 1e-9)), name
+        n_nan += int(np.isnan(want).sum())
+    assert n_nan > 0 and np.isfinite(st.p[3]).all()
+    p16 = dp.rows_b16(apm.APM_P16, pages)
+    is_nan16 = ((p16 & 0x7F80) == 0x7F80) & ((p16 & 0x7F) != 0)
+    assert np.array_equal(is_nan16, np.isnan(st.p))
+    dp.destroy()
+
+
 def test_no_outputs_no_clip_path_matches_path_with_reduce():
     # without clip/skip/outputs the reduce pass is not launched; results must be identical
     E = 16384

@@ -259,3 +259,36 @@ def test_update_is_elementwise_independent_of_paging():
     parts = [run_steps(p0[a:b], [g[a:b] for g in grads], Hyper()) for a, b in [(0, 40), (40, 96)]]
     for k in range(4):
         assert np.concatenate([parts[0][k], parts[1][k]]).tobytes() == whole[k].tobytes()
+
+
+@pytest.mark.parametrize("clip", [0.0, 0.5])
+@pytest.mark.parametrize("bad", [np.inf, -np.inf, np.nan])
+def test_non_finite_gradients_propagate_like_the_library_optimizer(clip, bad):
+    # No special handling of inf / NaN gradients: plain IEEE propagation, as in torch's AdamW and
+    # clip_grad_norm_ (an infinite norm gives scale 0, so inf * 0 = NaN and finite gradients vanish;
+    # a NaN norm gives a NaN scale, which poisons the whole page).
+    n = 64
+    p0 = (np.random.default_rng(2).standard_normal(n) * 0.02).astype(np.float32)
+    g1 = some_bf16_values(n, 3, 0.05)
+    g1[5] = bad
+    g2 = some_bf16_values(n, 4, 0.05)
+    h = Hyper(max_grad_norm=clip)
+    with np.errstate(all="ignore"):
+        p, m, v, p16, outs = run_steps(p0, [g1, g2], h)
+    tp = torch.nn.Parameter(torch.tensor(p0, dtype=torch.float64))
+    opt = torch.optim.AdamW([tp], lr=h.lr, betas=(h.beta1, h.beta2), eps=h.eps,
+                            weight_decay=h.weight_decay, amsgrad=False)
+    for g in (g1, g2):
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        if clip > 0:
+            torch.nn.utils.clip_grad_norm_([tp], clip)
+        opt.step()
+    want = tp.detach().numpy()
+    assert np.array_equal(np.isnan(p), np.isnan(want))
+    ok = ~np.isnan(want)
+    assert not ok.any() or relerr(p[ok], want[ok]) < 1e-12
+    n_nan = int(np.isnan(want).sum())
+    assert n_nan == (n if (clip > 0 and np.isnan(bad)) else 1)
+    # the 16-bit copy of a NaN master is a NaN
+    nan16 = (p16 & 0x7F80) == 0x7F80
+    assert np.array_equal(nan16 & ((p16 & 0x7F) != 0), np.isnan(want))
