@@ -261,7 +261,8 @@ int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t 
  *      (Sec. 4.2: overlap movement with computation, scheduled per page) -------------------- */
 
 /*
- * host:   HOST pool storing P32, M32, V32 (the layout is taken from `dev`).
+ * host:   HOST pool storing P32, M32, V32 (the layout is taken from `dev`); it must hold every
+ *         page in use unless apm_streamer_set_host_first_page says otherwise (checked per step).
  * dev:    GPU pool storing G16 and P16 for the same pages, with an installed layout.
  * batch_pages: pages moved and updated per pipeline stage of the staged mode (>= 1).
  * n_slots: staging slots in HBM for the staged mode (>= 2); each holds batch_pages pages of the
@@ -319,6 +320,15 @@ int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, do
  * host pool, done between steps.  cache == NULL or n_resident == 0 switches the cache off.
  */
 int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident);
+
+/*
+ * With a cache, the host pool need not hold the resident pages: after this call page j of the host
+ * pool is model page first_model_page + j (default 0), so a host pool of N - first_model_page
+ * pages serves a model of N pages whose first n_resident >= first_model_page pages are cached --
+ * the way to run a model whose fp32 state exceeds what the machine can pin.  Checked at each step
+ * (APM_ESTATE if pages are covered by neither pool or the host pool is too small).
+ */
+int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page);
 
 /*
  * Measurement aid (staged mode only): the same pipeline (streams, events, copy sizes, slot reuse)

@@ -29,6 +29,7 @@ struct apm_streamer {
     apm_pool* dev = nullptr;
     apm_pool* cache = nullptr;  // optional GPU pool holding the fp32 classes of pages [0, R)
     int64_t R = 0;              // number of leading pages whose fp32 state is HBM-resident
+    int64_t host_first = 0;     // model page held by page 0 of the host pool
     int64_t B = 0;
     int n_slots = 0;
     float* stage[3] = {nullptr, nullptr, nullptr};  // each n_slots * B * E floats
@@ -196,7 +197,6 @@ extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool*
     for (int st : {APM_P32, APM_M32, APM_V32}) if (!host->stores(st)) return fail(APM_ESTATE, "host pool lacks fp32 class %d", st);
     for (int st : {APM_G16, APM_P16}) if (!dev->stores(st)) return fail(APM_ESTATE, "GPU pool lacks 16-bit class %d", st);
     if (host->desc.page_elems != dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
-    if (host->desc.n_pages < dev->desc.n_pages) return fail(APM_EINVAL, "host pool has fewer pages than the GPU pool");
     if (batch_pages < 1 || batch_pages > dev->desc.n_pages) return fail(APM_EINVAL, "batch_pages out of range");
     if (n_slots < 2 || n_slots > 64) return fail(APM_EINVAL, "n_slots must be in [2, 64]");
     APM_HIP(hipSetDevice(dev->desc.hip_device));
@@ -273,6 +273,10 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     }
     const int states[3] = {APM_P32, APM_M32, APM_V32};
     const int64_t R = s->cache ? (s->R < N ? s->R : N) : 0;
+    // host pool page j holds model page host_first + j; the pages before it must be resident
+    const int64_t H0 = s->host_first;
+    if (R < H0 && N > 0) return fail(APM_ESTATE, "model pages [%lld, %lld) are neither resident in the cache nor held by the host pool", (long long)R, (long long)H0);
+    if (N - H0 > host->desc.n_pages) return fail(APM_ESTATE, "the host pool holds %lld pages, %lld are needed from model page %lld on", (long long)host->desc.n_pages, (long long)(N - H0), (long long)H0);
     if (direct) {
         for (int part = 0; part < 2; ++part) {  // resident pages first (HBM speed), then the host pages
             AdamwLaunch C = L;
@@ -290,7 +294,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
                 C.stride_wavefronts = s->direct_waves;
                 C.stride_waves_per_wg = s->direct_per_wg;
             }
-            C.state_first = C.grad_first = first;
+            C.state_first = part == 0 ? first : first - H0;
+            C.grad_first = first;
             C.n_listed = n;
             C.grad_norm = grad_norm ? grad_norm + first : nullptr;
             C.skip_mask = skip_mask ? skip_mask + first : nullptr;
@@ -341,7 +346,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
         if (b >= s->n_slots) APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_d2h[slot], 0));
         for (int k = 0; k < 3 && (what & kDoH2D); ++k) {
-            const char* src = static_cast<const char*>(host->base[states[k]]) + (size_t)first * pb;
+            const char* src = static_cast<const char*>(host->base[states[k]]) + (size_t)(first - H0) * pb;
             APM_HIP(hipMemcpyAsync(s->stage[k] + slot_off, src, pb * (size_t)nb, hipMemcpyHostToDevice, s->s_in));
         }
         APM_HIP(hipEventRecord(s->ev_h2d[slot], s->s_in));
@@ -379,7 +384,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
 
         APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_cmp[slot], 0));
         for (int k = 0; k < 3 && (what & kDoD2H); ++k) {
-            char* dst = static_cast<char*>(host->base[states[k]]) + (size_t)first * pb;
+            char* dst = static_cast<char*>(host->base[states[k]]) + (size_t)(first - H0) * pb;
             APM_HIP(hipMemcpyAsync(dst, s->stage[k] + slot_off, pb * (size_t)nb, hipMemcpyDeviceToHost, s->s_out));
         }
         APM_HIP(hipEventRecord(s->ev_d2h[slot], s->s_out));
@@ -463,6 +468,13 @@ extern "C" int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t 
     return APM_OK;
 }
 
+extern "C" int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    if (first_model_page < 0 || first_model_page > s->dev->desc.n_pages) return fail(APM_ERANGE, "first_model_page out of range");
+    s->host_first = first_model_page;
+    return APM_OK;
+}
+
 // One step driven by a schedule (Alg. 1's task list) instead of the fixed slot ring.  The staging
 // memory is the GPU memory the schedule was planned for, one page slot per page; a movement task
 // takes the lowest free slot, a compute task updates its layer's pages where they sit, writes them
@@ -482,7 +494,8 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
     if (layer_first_page[0] != 0 || layer_first_page[n_layers] != N) return fail(APM_EINVAL, "the layers must cover pages [0, %lld) in order", (long long)N);
     for (int64_t i = 0; i < n_layers; ++i)
         if (layer_first_page[i + 1] < layer_first_page[i]) return fail(APM_EINVAL, "layer_first_page must not decrease");
-    if (s->cache) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache");
+    if (s->cache || s->host_first != 0) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache");
+    if (s->host->desc.n_pages < N) return fail(APM_ESTATE, "the host pool holds fewer pages than are in use");
     AdamwLaunch L{};
     int rc = prepare_hyper(hyper, step, &L);
     if (rc != APM_OK) return rc;

@@ -105,9 +105,13 @@ def test_streamed_equals_resident_bit_exact(batch, slots, clip, mode):
     res.destroy()
 
 
-@pytest.mark.parametrize("frac,mode", [(0.0, "staged"), (0.35, "staged"), (1.0, "staged"), (0.35, "direct"), (1.0, "direct")])
-def test_mixed_residency_equals_resident_bit_exact(frac, mode):
-    # the first R pages keep their fp32 state in an HBM cache pool, the rest is streamed
+@pytest.mark.parametrize("frac,mode,short_host", [(0.0, "staged", False), (0.35, "staged", False), (1.0, "staged", False),
+                                                  (0.35, "direct", False), (1.0, "direct", False),
+                                                  (0.35, "direct", True), (0.35, "staged", True)])
+def test_mixed_residency_equals_resident_bit_exact(frac, mode, short_host):
+    # the first R pages keep their fp32 state in an HBM cache pool, the rest is streamed;
+    # short_host: the host pool holds only the pages from H0 = R - 3 on (a model whose fp32 state
+    # exceeds what can be pinned), its page j being model page H0 + j
     f, E = synth.WORKLOADS["gpt2_small_124m"]
     model = Model(f(), E, seed=2)
     n_pages, n_t = model.plan.n_pages, len(model.specs)
@@ -117,17 +121,24 @@ def test_mixed_residency_equals_resident_bit_exact(frac, mode):
     apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
     dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
     apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
-    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    H0 = R - 3 if short_host else 0
+    n_host = n_pages - H0
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_host, state_mask=apm.FP32_STATES)
     cache = DevicePool(max(R, 1), E, states=(apm.APM_P32, apm.APM_M32, apm.APM_V32))
-    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    apm.apm_page_copy_async(host, 0, res.pool, H0, n_host, apm.APM_P32)
     if R:
         apm.apm_page_copy_async(cache.pool, 0, res.pool, 0, R, apm.APM_P32)
         # the host copy of the cached pages is stale from now on: poison it to prove it is unused
-        hv = host_view(host, apm.APM_P32, n_pages, E)
+        hv = host_view(host, apm.APM_P32, n_host, E)
         torch.cuda.synchronize()
-        hv[:R] = np.nan
+        hv[:R - H0] = np.nan
     st = apm.apm_streamer_create(host, dev.pool, 16, 3)
     apm.apm_streamer_set_cache(st, cache.pool if R else None, R)
+    if short_host:
+        with pytest.raises(apm.ApmError) as e:      # without the offset the host pool is too small
+            apm.apm_streamer_step(st, 1, hy)
+        assert e.value.code == apm.APM_ESTATE
+        apm.apm_streamer_set_host_first_page(st, H0)
     set_mode(st, mode)
     norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
@@ -143,8 +154,8 @@ def test_mixed_residency_equals_resident_bit_exact(frac, mode):
         want = res.reg[s_].cpu().numpy().view(np.uint32)
         if R:
             assert np.array_equal(cache.reg[s_][:R].cpu().numpy().view(np.uint32), want[:R]), f"cached state {s_}"
-        hv = host_view(host, s_, n_pages, E)
-        assert np.array_equal(hv[R:].view(np.uint32), want[R:]), f"streamed state {s_}"
+        hv = host_view(host, s_, n_host, E)
+        assert np.array_equal(hv[R - H0:].view(np.uint32), want[R:]), f"streamed state {s_}"
     assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
     st.destroy()
     host.destroy()
@@ -212,6 +223,84 @@ def test_cfg4_gpt13b_shape_streamed_sampled_oracle():
     host.destroy()
     dev.destroy()
     tmp.destroy()
+
+
+def test_cfg4_gpt13b_full_shape_with_what_cannot_be_pinned_cached_in_hbm():
+    # The full 40-layer 13 B shape (12 578 pages, 154 GB of fp32 state).  The box pins about 64 GiB,
+    # so the host pool holds the tail of the model (as many pages as can be pinned) and the head's
+    # fp32 state is cached in HBM (the paper's GPU cache of optimizer states, Sec. 4.2); the host
+    # pool's page j is model page R + j.  Sampled pages of both parts are checked against the oracle.
+    from gpu_helpers import HOST_THREADS
+    E = 1 << 20
+    specs = synth.gpt_tensor_list(40, 5120, 20480, 50257, 2048)
+    plan = oracle.plan_pack([t.numel for t in specs], E)
+    n_pages, n_t = plan.n_pages, len(specs)
+    assert n_pages == 12578
+    host = None
+    for frac in (1.0, 0.45, 0.4, 0.3, 0.2, 0.1):
+        n_host = int(n_pages * frac)
+        try:
+            host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_host, state_mask=apm.FP32_STATES)
+            break
+        except apm.ApmError as e:
+            assert e.code == apm.APM_ENOMEM
+            print(f"cfg4 full: {n_host} pages ({n_host * E * 12 / 2**30:.0f} GiB) cannot be pinned", flush=True)
+    assert host is not None
+    R = n_pages - n_host
+    print(f"cfg4 full: {n_pages} pages, {n_host} in pinned host memory ({n_host * E * 12 / 2**30:.1f} GiB), "
+          f"{R} cached in HBM", flush=True)
+    model = Model(specs, E, seed=0)
+    sample = sorted(set(range(0, n_pages, 257)) | {0, R - 1, R, n_pages - 1} - {-1}
+                    | {k for k, p in enumerate(plan.pages) if p.used < E})
+    sample = [p for p in sample if 0 <= p < n_pages]
+    used = [plan.pages[p].used for p in sample]
+    h = oracle.Hyper(max_grad_norm=1.0)
+    hy = to_hyper(h)
+
+    init = DevicePool(n_pages, E, states=(apm.APM_P32,))       # the cache's P32 class is its head
+    apm.apm_pack_tensors(init.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    apm.apm_page_copy_async(host, 0, init.pool, R, n_host, apm.APM_P32)
+    torch.cuda.synchronize()
+    st = oracle.PagedAdamWState(model.host_pages(model.p_flat, sample).view(np.float32), used)
+    model.p_flat = None                                         # 51 GB back to the allocator
+    torch.cuda.empty_cache()
+    cache_mv = {s_: torch.zeros((max(R, 1), E), dtype=torch.float32, device=DEV) for s_ in (apm.APM_M32, apm.APM_V32)}
+    cache = apm.apm_pool_create(apm.APM_DEV_GPU, E, max(R, 1), state_mask=apm.FP32_STATES,
+                                flags=apm.APM_POOL_NO_ZERO,      # P32 holds the packed parameters already
+                                base={apm.APM_P32: init.reg[apm.APM_P32], **cache_mv})
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, apm.make_tensors(model.numels, apm.APM_BF16), n_t)
+    streamer = apm.apm_streamer_create(host, dev.pool, 32, 3)
+    apm.apm_streamer_set_cache(streamer, cache if R else None, R)
+    apm.apm_streamer_set_host_first_page(streamer, R)
+    norm_d = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 3):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT if t == 1 else apm.APM_STREAM_STAGED)
+        apm.apm_streamer_step(streamer, t, hy, norm_d, None)
+        norms, _ = st.step(model.host_pages(g, sample), t, h, threads=HOST_THREADS)
+        torch.cuda.synchronize()
+        got = norm_d.cpu().numpy()[sample]
+        assert np.all(np.abs(got - norms) <= 1e-6 * np.abs(norms))
+        del g
+    rows = {}
+    cached = [p for p in sample if p < R]
+    streamed = [p - R for p in sample if p >= R]
+    idx = torch.as_tensor(cached, device=DEV, dtype=torch.long)
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        head = (init.reg[s_] if s_ == apm.APM_P32 else cache_mv[s_])[idx].cpu().numpy() if cached else np.zeros((0, E), np.float32)
+        tail = host_view(host, s_, n_host, E)[streamed]
+        rows[s_] = np.concatenate([head, tail], axis=0)
+    worst = {k: check_state_close(k, rows[s_], ref, used)
+             for k, s_, ref in (("p", apm.APM_P32, st.p), ("m", apm.APM_M32, st.m), ("v", apm.APM_V32, st.v))}
+    print(f"cfg4 full worst rel err {worst}", flush=True)
+    check_p16(dev.rows_b16(apm.APM_P16, sample), rows[apm.APM_P32], st.p16, used)
+    streamer.destroy()
+    cache.destroy()
+    host.destroy()
+    dev.destroy()
+    init.destroy()
 
 
 def layer_ranges(model):
