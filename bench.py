@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--no-streamed", action="store_true", help="skip the host-streamed leg")
     ap.add_argument("--streamed-only", action="store_true", help="run only the host-streamed leg (gpt_13b: always)")
     ap.add_argument("--stream-steps", type=int, default=3)
+    ap.add_argument("--full-shape", action="store_true",
+                    help="run only the 13 B shape at its full 40 layers: what cannot be pinned is cached in HBM")
     ap.add_argument("--file-tier", default=None, metavar="DIR",
                     help="run only the file-tier leg, with the fp32 state in files under DIR")
     ap.add_argument("--io-threads", type=int, default=8)
@@ -693,6 +695,17 @@ def main():
            "config": {"workload": args.workload, "params": wl.total, "pages": n_pages, "page_elems": E,
                       "fragmentation": plan.fragmentation, "clip": clip, "skip_mode": skip}}
 
+    if args.full_shape:
+        fs = full_shape_leg(args, hyper)
+        out["full_shape"] = fs
+        out["value"], out["ms_per_step"] = fs["params_per_s"], fs["ms_per_step"]
+        out["steps"], out["warmup"] = args.stream_steps, 1
+        out["config"].update({"workload": "gpt_13b", "params": fs["params"], "pages": fs["pages"],
+                              "fragmentation": fs["fragmentation"],
+                              "step": "reduce + AdamW: cached pages in HBM, host pages across PCIe (direct mode)",
+                              "state": "fp32 p/m/v: head cached in HBM, tail in pinned host pages; bf16 g/p16 in HBM"})
+        print(json.dumps(out))
+        return
     if args.file_tier:
         out["file_tier"] = file_tier_leg(args, wl, hyper, n_pages)
         out["value"] = out["file_tier"]["unbuffered"]["params_per_s"]
@@ -806,6 +819,68 @@ def streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages):
     host.destroy()
     tmp.destroy()
     return out
+
+
+def full_shape_leg(args, hyper):
+    """The 13 B shape at its full 40 layers: the host pool holds as much of the model's tail as the
+    box can pin, the head's fp32 state is cached in HBM (Sec. 4.2's cache of optimizer states)."""
+    import torch
+    import paper_2303_02868_amd as apm
+    wl = Workload("gpt_13b", 40)
+    E = wl.E
+    plan = apm.apm_pack_plan(E, wl.numels)
+    N = plan.n_pages
+    host = None
+    for frac in (1.0, 0.45, 0.4, 0.3, 0.2, 0.1):
+        n_host = int(N * frac)
+        try:
+            host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_host, state_mask=apm.FP32_STATES)
+            break
+        except apm.ApmError as e:
+            if e.code != apm.APM_ENOMEM:
+                raise
+    R = N - n_host
+    dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, N, state_mask=apm.B16_STATES)
+    apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+    p32 = torch.zeros((N, E), dtype=torch.float32, device=DEV)
+    init = apm.apm_pool_create(apm.APM_DEV_GPU, E, N, state_mask=1 << apm.APM_P32, flags=apm.APM_POOL_NO_ZERO,
+                               base={apm.APM_P32: p32})
+    apm.apm_pack_tensors(init, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    apm.apm_page_copy_async(host, 0, init, R, n_host, apm.APM_P32)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    mv = {s_: torch.zeros((max(R, 1), E), dtype=torch.float32, device=DEV) for s_ in (apm.APM_M32, apm.APM_V32)}
+    cache = apm.apm_pool_create(apm.APM_DEV_GPU, E, max(R, 1), state_mask=apm.FP32_STATES,
+                                flags=apm.APM_POOL_NO_ZERO, base={apm.APM_P32: p32, **mv})
+    streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, N), args.slots)
+    apm.apm_streamer_set_cache(streamer, cache if R else None, R)
+    apm.apm_streamer_set_host_first_page(streamer, R)
+    stream = torch.cuda.current_stream()
+    apm.apm_streamer_step(streamer, 1, hyper, None, None, stream)
+    ts = []
+    for k in range(args.stream_steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        apm.apm_streamer_step(streamer, 2 + k, hyper, None, None, stream)
+        torch.cuda.synchronize()
+        ts.append(time.perf_counter() - t0)
+    used_host = sum(plan_used(plan, N)[R:])
+    out = {"params": wl.total, "pages": N, "layers": 40, "fragmentation": plan.fragmentation, "resident_pages": R, "host_pages": n_host,
+           "host_pinned_GB": n_host * E * 12 / 1e9, "hbm_cache_GB": R * E * 12 / 1e9, "mode": "direct",
+           "ms_per_step": min(ts) * 1e3, "ms_per_step_all": [t * 1e3 for t in ts],
+           "params_per_s": wl.total / min(ts), "pcie_GBps_each_way": used_host * 12 / min(ts) / 1e9}
+    streamer.destroy()
+    for p in (cache, init, host, dev_pool):
+        p.destroy()
+    return out
+
+
+def plan_used(plan, n_pages):
+    """Used elements per page of a packing plan."""
+    used = [0] * n_pages
+    for _, _, page, page_off, n in plan.segments:
+        used[page] = max(used[page], page_off + n)
+    return used
 
 
 if __name__ == "__main__":
