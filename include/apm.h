@@ -220,6 +220,8 @@ int apm_unpack(apm_pool* pool, int state, const apm_tensor* dst, int64_t n, void
  *   p' = p (1 - lr wd) - lr (m'/(1-b1^t)) / (sqrt(v'/(1-b2^t)) + eps);   p16' = bf16_rne(p').
  * Arithmetic is fp32 with correctly rounded divide and square root; p' is evaluated as
  * p - (lr wd p + (lr/(1-b1^t)) m'/denom) so that it is rounded once at the magnitude of p.
+ * Non-finite gradients get no special treatment (IEEE propagation: an infinite norm gives s = 0,
+ * a NaN norm s = NaN).
  *
  * pages: host pointer to n_pages distinct page indices, or NULL = pages [0, n_pages).
  * grad_norm (float[n_pages]) and skip_mask (uint8_t[n_pages]): device pointers, nullable,
