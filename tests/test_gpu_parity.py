@@ -434,6 +434,61 @@ def test_non_finite_gradients_propagate_as_in_the_oracle(clip):
     dp.destroy()
 
 
+@pytest.mark.parametrize("stepper", ["sync", "fused", "delayed"])
+def test_minimum_page_size_of_eight_elements(stepper):
+    # the smallest page the library accepts: every page is a fraction of one vector tile
+    E = 8
+    numels = [8, 3, 16, 5, 1, 0, 24, 7, 9, 8]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=17, sigma_g=1e-2, align_elems=8)
+    dp, st, worst = run_resident(model, 3, oracle.Hyper(max_grad_norm=0.01, skip_mode=1), stepper=stepper)
+    dp.destroy()
+
+
+def test_maximum_page_size_of_two_to_the_thirty_elements():
+    # the largest page the library accepts (4 GiB fp32 pages): one tensor that fills page 0 and
+    # spills into page 1, a small tensor alone in page 2.  The update is elementwise, so windows
+    # of elements (start, middle, page end, the spill, the small page) go through the oracle; the
+    # norms come from a float64 sum of squares over the whole pages.
+    E = 1 << 30
+    numels = [E + 12345, 777]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=33, sigma_g=1e-3)
+    assert model.plan.n_pages == 3
+    n_t = len(specs)
+    dp = DevicePool(3, E)
+    apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    h = oracle.Hyper()                      # no clip: elements are independent of each other
+    hy = to_hyper(h)
+    norm_d = torch.zeros(3, dtype=torch.float32, device=DEV)
+    windows = [(0, 0, 70000), (0, E // 2 - 3, 5000), (0, E - 4100, 4100), (1, 0, 12345), (2, 0, 777)]
+    state = []
+    for page, a, n in windows:
+        p0 = dp.reg[apm.APM_P32][page, a:a + n].cpu().numpy()
+        state.append([p0.astype(np.float64), np.zeros(n), np.zeros(n), np.zeros(n, dtype=np.uint16)])
+    for t in (1, 2):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(dp.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(dp.pool, None, 3, t, hy, norm_d, None)
+        torch.cuda.synchronize()
+        gp = dp.reg[apm.APM_G16]
+        want_norm = [float(torch.sqrt((gp[k].double() ** 2).sum())) for k in range(3)]
+        got = norm_d.cpu().numpy()
+        assert np.all(np.abs(got - want_norm) <= 1e-6 * np.abs(want_norm)), (got, want_norm)
+        for (page, a, n), (p, m, v, p16) in zip(windows, state):
+            oracle.page_adamw(p, m, v, p16, bf16_bits(gp[page, a:a + n]), t, h)
+        del g
+    for (page, a, n), (p, m, v, p16) in zip(windows, state):
+        for name, st_, want in (("p", apm.APM_P32, p), ("m", apm.APM_M32, m), ("v", apm.APM_V32, v)):
+            got = dp.reg[st_][page, a:a + n].cpu().numpy()[None, :]
+            check_state_close(f"{name} page {page} @ {a}", got, want[None, :], [n])
+        got16 = bf16_bits(dp.reg[apm.APM_P16][page, a:a + n])[None, :]
+        check_p16(got16, dp.reg[apm.APM_P32][page, a:a + n].cpu().numpy()[None, :], p16[None, :], [n])
+    # nothing beyond the used extents was written
+    assert not dp.reg[apm.APM_M32][1, 12345:12345 + (1 << 20)].any() and not dp.reg[apm.APM_M32][2, 777:].any()
+    dp.destroy()
+
+
 def test_no_outputs_no_clip_path_matches_path_with_reduce():
     # without clip/skip/outputs the reduce pass is not launched; results must be identical
     E = 16384
