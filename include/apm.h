@@ -324,6 +324,15 @@ int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, do
 int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident);
 
 /*
+ * Sizing the cache from the memory that is free now (Sec. 4.2: the cache size is decided per
+ * model so that training does not run out of GPU memory): *out = how many of n_pages pages'
+ * fp32 classes (12 * page_elems bytes each) fit into the device's free memory minus
+ * reserve_bytes, at most n_pages.  Call it after the model's other GPU allocations.
+ */
+int apm_cache_pages_that_fit(int hip_device, int64_t page_elems, int64_t n_pages,
+                             size_t reserve_bytes, int64_t* out);
+
+/*
  * With a cache, the host pool need not hold the resident pages: after this call page j of the host
  * pool is model page first_model_page + j (default 0), so a host pool of N - first_model_page
  * pages serves a model of N pages whose first n_resident >= first_model_page pages are cached --

@@ -31,7 +31,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_streamer_set_host_first_page", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_cache_pages_that_fit", "apm_streamer_set_host_first_page", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -126,6 +126,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_copy_only.argtypes = [vp, i32, vp]
     L.apm_streamer_set_cache.argtypes = [vp, vp, i64]
     L.apm_streamer_set_host_first_page.argtypes = [vp, i64]
+    L.apm_cache_pages_that_fit.argtypes = [i32, i64, i64, C.c_size_t, P(i64)]
     L.apm_streamer_set_mode.argtypes = [vp, i32, i32, i32]
     L.apm_streamer_get_mode.argtypes = [vp]
     L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
@@ -428,6 +429,12 @@ def apm_streamer_step_delayed(s: Streamer, new_g16, hyper: apm_hyper, stream=Non
 def apm_streamer_set_cache(s: Streamer, cache: Optional[Pool], n_resident: int) -> None:
     _check(lib().apm_streamer_set_cache(s.handle, cache.handle if cache else None, n_resident))
     s.cache = cache
+
+
+def apm_cache_pages_that_fit(page_elems: int, n_pages: int, reserve_bytes: int = 0, hip_device: int = 0) -> int:
+    out = C.c_int64(0)
+    _check(lib().apm_cache_pages_that_fit(hip_device, page_elems, n_pages, reserve_bytes, C.byref(out)))
+    return out.value
 
 
 def apm_streamer_set_host_first_page(s: Streamer, first_model_page: int) -> None:

@@ -468,6 +468,19 @@ extern "C" int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t 
     return APM_OK;
 }
 
+extern "C" int apm_cache_pages_that_fit(int hip_device, int64_t page_elems, int64_t n_pages,
+                                        size_t reserve_bytes, int64_t* out) {
+    if (!out || page_elems <= 0 || n_pages < 0) return fail(APM_EINVAL, "bad argument");
+    APM_HIP(hipSetDevice(hip_device));
+    size_t free_b = 0, total_b = 0;
+    APM_HIP(hipMemGetInfo(&free_b, &total_b));
+    const size_t page_bytes = (size_t)page_elems * 3u * sizeof(float);
+    const size_t usable = free_b > reserve_bytes ? free_b - reserve_bytes : 0;
+    const int64_t fit = (int64_t)(usable / page_bytes);
+    *out = fit < n_pages ? fit : n_pages;
+    return APM_OK;
+}
+
 extern "C" int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     if (first_model_page < 0 || first_model_page > s->dev->desc.n_pages) return fail(APM_ERANGE, "first_model_page out of range");

@@ -303,6 +303,17 @@ def test_cfg4_gpt13b_full_shape_with_what_cannot_be_pinned_cached_in_hbm():
     init.destroy()
 
 
+def test_cache_size_from_free_memory():
+    E = 1 << 20
+    free_b, total_b = torch.cuda.mem_get_info()
+    n_all = apm.apm_cache_pages_that_fit(E, 10 ** 9)
+    assert 0.9 * free_b / (12 * E) - 1 <= n_all <= total_b / (12 * E)
+    assert apm.apm_cache_pages_that_fit(E, 100) == 100
+    assert apm.apm_cache_pages_that_fit(E, 10 ** 9, reserve_bytes=total_b) == 0
+    half = apm.apm_cache_pages_that_fit(E, 10 ** 9, reserve_bytes=free_b // 2)
+    assert abs(half - n_all / 2) <= 0.1 * n_all + 2
+
+
 def layer_ranges(model):
     """First page of every transformer block (plus the embedding / final blocks): a page belongs
     to the block of its first tenant.  Returns the n_layers + 1 boundaries."""
