@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--no-streamed", action="store_true", help="skip the host-streamed leg")
     ap.add_argument("--streamed-only", action="store_true", help="run only the host-streamed leg (gpt_13b: always)")
     ap.add_argument("--stream-steps", type=int, default=3)
+    ap.add_argument("--page-sweep", action="store_true",
+                    help="run only the page-size sweep (update kernel, direct and page-granular staged streaming)")
     ap.add_argument("--full-shape", action="store_true",
                     help="run only the 13 B shape at its full 40 layers: what cannot be pinned is cached in HBM")
     ap.add_argument("--file-tier", default=None, metavar="DIR",
@@ -695,6 +697,15 @@ def main():
            "config": {"workload": args.workload, "params": wl.total, "pages": n_pages, "page_elems": E,
                       "fragmentation": plan.fragmentation, "clip": clip, "skip_mode": skip}}
 
+    if args.page_sweep:
+        out["page_sweep"] = page_sweep_leg(args)
+        out["config"] = {"workload": "one tensor of 2^30 elements, page size swept"}
+        out["steps"], out["warmup"] = 10, 2
+        best = max(out["page_sweep"], key=lambda r: r["resident_update_GBps"])
+        out["value"] = best["resident_update_GBps"] * 1e9 / BYTES_UPDATE
+        out["ms_per_step"] = (1 << 30) / out["value"] * 1e3
+        print(json.dumps(out))
+        return
     if args.full_shape:
         fs = full_shape_leg(args, hyper)
         out["full_shape"] = fs
@@ -819,6 +830,58 @@ def streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages):
     host.destroy()
     tmp.destroy()
     return out
+
+
+def page_sweep_leg(args):
+    """Page size against throughput (Sec. 4.1 "Optimal Page Size" asks which page size keeps the
+    transfer path busy): one tensor of 2^30 elements in pages of 2^14 .. 2^24 elements; the
+    resident update kernel, the direct streamed step, and the staged step moving one page per copy."""
+    import torch
+    import paper_2303_02868_amd as apm
+    total = 1 << 30
+    hyper = apm.make_hyper()
+    g = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+    g.normal_(0, 1e-3)
+    stream = torch.cuda.current_stream()
+    rows = []
+    for log_e in (14, 16, 18, 20, 22, 24):
+        E = 1 << log_e
+        n = total // E
+        t16 = apm.make_tensors([total], apm.APM_BF16, [g])
+        pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n)
+        apm.apm_pack_tensors(pool, apm.APM_G16, t16, 1)
+        for t in range(1, 3):
+            apm.apm_page_adamw_step(pool, None, n, t, hyper, None, None, stream)
+        torch.cuda.synchronize()
+        apm.apm_pool_set_timing(pool, True)
+        for t in range(3, 13):
+            apm.apm_page_adamw_step(pool, None, n, t, hyper, None, None, stream)
+        torch.cuda.synchronize()
+        ms, launches = apm.apm_pool_read_timing(pool)
+        upd = ms[apm.APM_K_UPDATE] / launches[apm.APM_K_UPDATE]
+        row = {"page_elems": E, "fp32_page_bytes": 4 * E, "pages": n,
+               "resident_update_GBps": total * BYTES_UPDATE / (upd * 1e-3) / 1e9}
+        host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n, state_mask=apm.FP32_STATES)
+        for st in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+            apm.apm_page_copy_async(host, 0, pool, 0, n, st)
+        torch.cuda.synchronize()
+        streamer = apm.apm_streamer_create(host, pool, 1, 4)
+        for name, mode in (("direct", apm.APM_STREAM_DIRECT), ("staged_one_page_per_copy", apm.APM_STREAM_STAGED)):
+            if mode == apm.APM_STREAM_STAGED and n > 16384:
+                row[name + "_GBps_each_way"] = None      # hundreds of thousands of tiny copies: not timed
+                continue
+            apm.apm_streamer_set_mode(streamer, mode)
+            apm.apm_streamer_step(streamer, 20, hyper, None, None, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            apm.apm_streamer_step(streamer, 21, hyper, None, None, stream)
+            torch.cuda.synchronize()
+            row[name + "_GBps_each_way"] = total * 12 / (time.perf_counter() - t0) / 1e9
+        streamer.destroy()
+        host.destroy()
+        pool.destroy()
+        rows.append(row)
+    return rows
 
 
 def full_shape_leg(args, hyper):

@@ -53,8 +53,11 @@ __device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w &
 // Round-to-nearest-even of an fp32 value to bf16 bits, on the integer representation.
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
     const uint32_t u = __float_as_uint(x);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    // both forms are computed and one is selected: a branch here would split the update kernel's
+    // body into basic blocks (see slice_body)
+    const uint32_t nan = (u >> 16) | 0x0040u;
+    const uint32_t rne = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? nan : rne;
 }
 
 // ---- tunables (defaults measured on MI355X; see the sweep notes next to each) ----------------
@@ -80,12 +83,18 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 // cut their number (MoE workload: update 3.03 ms -> 2.61 ms).
 #define APM_UPDATE_SLICES_SKIP 4
 #endif
+#ifndef APM_HOIST_LOADS
+#define APM_HOIST_LOADS 1
+#endif
 #ifndef APM_UPDATE_LDS
 // Dynamic LDS requested per workgroup for no purpose other than capping residency at
-// 160 KiB / 20 KiB = 8 wavefronts per CU: with four read and four write streams per wavefront,
-// more resident wavefronts lower the achieved HBM bandwidth (measured on the 1.3 B-parameter
-// workload: 5.6 TB/s uncapped, 6.0 at 13, 6.18 at 10, 6.25 at 8, 6.1 at 6 wavefronts per CU).
-#define APM_UPDATE_LDS 20480
+// 160 KiB / 32 KiB = 5 wavefronts per CU: with four read and four write streams per wavefront,
+// more resident wavefronts lower the achieved HBM bandwidth.  Measured on the 1.3 B-parameter
+// workload with the single-block slice body (16 loads, then 16 stores in flight per wavefront):
+// 5.5 TB/s at 16 wavefronts per CU, 5.6 at 13, 5.9 at 10, 5.7-6.1 at 8, 6.1 at 6, 6.3 at 5,
+// 6.0-6.3 at 4, 6.1 at 3, 5.1 at 2.  (The earlier body, whose wavefronts waited for each vector's
+// stores, peaked at 8.)
+#define APM_UPDATE_LDS 32768
 #endif
 
 // Gradient elements [e, e+8) of a page, read from its tenant tensors; elements that belong to no
@@ -346,53 +355,50 @@ constexpr int kUpdThreads = APM_UPDATE_THREADS;
 constexpr int kUpdU = APM_UPDATE_U;
 constexpr int kUpdTile = kUpdThreads * 4 * kUpdU;  // elements per workgroup
 
-// Fused update of one slice (kUpdTile elements from `start`) of one page by one wavefront:
-// 12 B + 2 B read and 12 B + 2 B written per element.  Each lane keeps kUpdU 128-bit vectors per
-// fp32 class in flight; every wavefront-wide access is one contiguous 1 KiB (fp32) or 512 B (bf16)
-// span.  GATHER / SCATTER: read g from / write p16 to the tenant tensors instead of the page
-// classes.
-template <bool GATHER, bool SCATTER>
-__device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs& segs, float scale,
-                                             int used8, int64_t gpage, int64_t spage, int start, int lane) {
-    f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
-    f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
-    f32x4* __restrict__ V = reinterpret_cast<f32x4*>(a.v32 + spage * a.E);
-    const u32x2* __restrict__ G = GATHER ? nullptr : reinterpret_cast<const u32x2*>(a.g16 + gpage * a.E);
-    u32x2* __restrict__ P16 = SCATTER ? nullptr : reinterpret_cast<u32x2*>(a.p16 + gpage * a.E);
-    bool edge = false;  // gather / scatter only: this slice is not wholly inside one tenant
-    if (GATHER || SCATTER) {
-        const int k = (segs.n[1] > 0 && start >= segs.off[1]) ? 1 : 0;
-        const int rel = start - segs.off[k];
-        const int span = min(kUpdTile, used8 - start);
-        // Wholly inside tenant k (the common case): address the tensor like a page whose element 0
-        // sits at ptr - off[k]; the slice then runs the same code as the page-class path.
-        if (rel >= 0 && rel + span <= segs.n[k]) {
-            if (GATHER) G = reinterpret_cast<const u32x2*>(segs.g[k] - segs.off[k]);
-            if (SCATTER) P16 = reinterpret_cast<u32x2*>(segs.q[k] - segs.off[k]);
-        } else {
-            edge = true;
-        }
-    }
-
-    const int nvec = used8 >> 2;
-    const int v0 = (start >> 2) + lane;
+// The body of a slice.  EDGE_G / EDGE_Q: the slice is not wholly inside one tenant tensor, so g is
+// gathered / p16 scattered lane by lane through the tenant descriptors; otherwise G and P16 are
+// plain page-like pointers and the body is straight-line code (all loads issued back to back, one
+// wait, all stores issued back to back).  The two forms are separate instantiations on purpose:
+// with the per-lane paths as branches inside one body the compiler put a wait for all outstanding
+// memory operations -- the stores of the previous vector included -- in front of every vector.
+//
+// FULL: every lane's kUpdU vectors lie inside the used extent (all slices of a page but its last),
+// so no access is predicated and the whole body is one basic block.  That matters beyond the
+// saved compares: on this target loads and stores share one counter, and at the entry of a basic
+// block the compiler must assume the worst about what is outstanding -- with a predicate per
+// vector, each vector's arithmetic began with a wait for every earlier memory operation, the
+// previous vector's stores included, i.e. three extra store round trips per wavefront.
+template <bool EDGE_G, bool EDGE_Q, bool FULL>
+__device__ __forceinline__ void slice_body(const UpdateArgs& a, const PageSegs& segs, float scale, int nvec, int v0,
+                                           f32x4* __restrict__ P, f32x4* __restrict__ M, f32x4* __restrict__ V,
+                                           const u32x2* __restrict__ G_, u32x2* __restrict__ P16_) {
+    // The tenant pointers come out of memory, so the compiler knows no address space for them and
+    // would use flat accesses, which count against both memory counters and force full waits.
+    // They are device (or pinned host) memory: say so.
+    typedef const u32x2 __attribute__((address_space(1))) * GlobalIn;
+    typedef u32x2 __attribute__((address_space(1))) * GlobalOut;
+    const GlobalIn G = (GlobalIn)G_;
+    const GlobalOut P16 = (GlobalOut)P16_;
     f32x4 p[kUpdU], m[kUpdU], v[kUpdU];
     u32x2 g[kUpdU];
 #pragma unroll
     for (int u = 0; u < kUpdU; ++u) {
         const int vi = v0 + u * kUpdThreads;
-        if (vi < nvec) {
-            if (GATHER && edge) g[u] = gather_g4(segs, vi << 2);
+        if (FULL || vi < nvec) {
+            if (EDGE_G) g[u] = gather_g4(segs, vi << 2);
             else g[u] = __builtin_nontemporal_load(G + vi);
             p[u] = __builtin_nontemporal_load(P + vi);
             m[u] = __builtin_nontemporal_load(M + vi);
             v[u] = __builtin_nontemporal_load(V + vi);
         }
     }
+    // all loads are issued before any arithmetic: without the barrier the scheduler, now that the
+    // body is one block, sinks half of them between the vectors' arithmetic to save registers
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < kUpdU; ++u) {
         const int vi = v0 + u * kUpdThreads;
-        if (vi < nvec) {
+        if (FULL || vi < nvec) {
             const float gf[4] = {bf16lo(g[u][0]), bf16hi(g[u][0]), bf16lo(g[u][1]), bf16hi(g[u][1])};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -408,10 +414,43 @@ __device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs
             __builtin_nontemporal_store(p[u], P + vi);
             __builtin_nontemporal_store(m[u], M + vi);
             __builtin_nontemporal_store(v[u], V + vi);
-            if (SCATTER && edge) scatter_q4(segs, vi << 2, o);
+            if (EDGE_Q) scatter_q4(segs, vi << 2, o);
             else __builtin_nontemporal_store(o, P16 + vi);
         }
     }
+}
+
+// Fused update of one slice (kUpdTile elements from `start`) of one page by one wavefront:
+// 12 B + 2 B read and 12 B + 2 B written per element.  Each lane keeps kUpdU 128-bit vectors per
+// fp32 class in flight; every wavefront-wide access is one contiguous 1 KiB (fp32) or 512 B (bf16)
+// span.  GATHER / SCATTER: read g from / write p16 to the tenant tensors instead of the page
+// classes.
+template <bool GATHER, bool SCATTER>
+__device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs& segs, float scale,
+                                             int used8, int64_t gpage, int64_t spage, int start, int lane) {
+    f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
+    f32x4* __restrict__ M = reinterpret_cast<f32x4*>(a.m32 + spage * a.E);
+    f32x4* __restrict__ V = reinterpret_cast<f32x4*>(a.v32 + spage * a.E);
+    const u32x2* __restrict__ G = GATHER ? nullptr : reinterpret_cast<const u32x2*>(a.g16 + gpage * a.E);
+    u32x2* __restrict__ P16 = SCATTER ? nullptr : reinterpret_cast<u32x2*>(a.p16 + gpage * a.E);
+    const int nvec = used8 >> 2;
+    const int v0 = (start >> 2) + lane;
+    if (GATHER || SCATTER) {
+        const int k = (segs.n[1] > 0 && start >= segs.off[1]) ? 1 : 0;
+        const int rel = start - segs.off[k];
+        const int span = min(kUpdTile, used8 - start);
+        // Wholly inside tenant k (the common case): address the tensor like a page whose element 0
+        // sits at ptr - off[k]; the slice then runs the same code as the page-class path.
+        if (rel >= 0 && rel + span <= segs.n[k]) {
+            if (GATHER) G = reinterpret_cast<const u32x2*>(segs.g[k] - segs.off[k]);
+            if (SCATTER) P16 = reinterpret_cast<u32x2*>(segs.q[k] - segs.off[k]);
+        } else {
+            slice_body<GATHER, SCATTER, false>(a, segs, scale, nvec, v0, P, M, V, G, P16);
+            return;
+        }
+    }
+    if (start + kUpdTile <= used8) slice_body<false, false, true>(a, segs, scale, nvec, v0, P, M, V, G, P16);
+    else slice_body<false, false, false>(a, segs, scale, nvec, v0, P, M, V, G, P16);
 }
 
 typedef long long i64x4 __attribute__((ext_vector_type(4)));
@@ -429,6 +468,16 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
     const i64x4 raw = *reinterpret_cast<const i64x4*>(a.meta + i);  // one load for the whole record
     PageSegs segs{};
     if (GATHER || SCATTER) segs = a.segs[i];
+#if APM_HOIST_LOADS
+    // The exits below would let the compiler sink every scalar load that only the working path
+    // needs (the tenant descriptors, the class base pointers) below them, which adds a third
+    // dependent memory round trip to the prologue.  Naming the values as inputs of an empty asm
+    // statement keeps those loads up here, in flight together with the page record.
+    asm volatile("" ::"s"(a.p32), "s"(a.m32), "s"(a.v32), "s"(a.g16), "s"(a.p16), "s"(a.E));
+    if (GATHER || SCATTER)
+        asm volatile("" ::"s"(segs.off[0]), "s"(segs.off[1]), "s"(segs.n[0]), "s"(segs.n[1]), "s"(segs.g[0]),
+                     "s"(segs.g[1]), "s"(segs.q[0]), "s"(segs.q[1]));
+#endif
     const float scale = __uint_as_float((uint32_t)((uint64_t)raw[0] >> 32));
     const int used8 = ((int32_t)(uint32_t)raw[0] + 7) & ~7;
     // (Folding the two exits below into the lane predicate, so that all scalar loads of the
