@@ -370,7 +370,7 @@ def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_para
     each_way_direct = total_params * 12
     direct = {"ms_per_step": dwall * 1e3, "ms_per_step_all": [w * 1e3 for w in dwalls],
               "pcie_GBps_each_way": each_way_direct / dwall / 1e9, "bytes_each_way": each_way_direct,
-              "wavefronts": args.direct_wavefronts or "library default (64)",
+              "wavefronts": args.direct_wavefronts or "library default (48)",
               "hbm_staging_bytes": 0}
 
     # The measured PCIe rate: the best each-way rate plain hipMemcpyAsync pairs reached with both

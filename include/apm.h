@@ -279,7 +279,7 @@ int apm_streamer_destroy(apm_streamer* s);
 /*
  * How the fp32 pages cross PCIe (Sec. 4.2 leaves the mechanism open):
  *   APM_STREAM_DIRECT: no copies and no staging; the update kernel itself reads p, m, v from the
- *     pinned host pages and writes them back, with `direct_wavefronts` wavefronts (0 = 64, which
+ *     pinned host pages and writes them back, with `direct_wavefronts` wavefronts (0 = 48, which
  *     saturates the link) of which `wavefronts_per_workgroup` (0 = 1, at most 16) share a
  *     workgroup and so a CU.  One per workgroup moves data fastest; more per workgroup occupy
  *     fewer CUs for the duration of the step, which disturbs concurrent kernels of the caller
