@@ -157,6 +157,7 @@ int prepare_hyper(const apm_hyper* h, int64_t step, AdamwLaunch* a);
 struct apm_pool {
     apm_pool_desc desc{};
     void* base[APM_N_STATES] = {};
+    void* alloc[APM_N_STATES] = {};  // what the library allocated for the class (base = alloc + skew)
     bool owned[APM_N_STATES] = {};
 
     bool has_layout = false;
