@@ -34,6 +34,8 @@ struct apm_streamer {
     int n_slots = 0;
     float* stage[3] = {nullptr, nullptr, nullptr};  // each n_slots * B * E floats
     hipStream_t s_in = nullptr, s_cmp = nullptr, s_out = nullptr;
+    hipStream_t s_res = nullptr;  // direct mode: the resident pages' update, beside the host pages'
+    hipEvent_t ev_res = nullptr;
     std::vector<hipEvent_t> ev_h2d, ev_cmp, ev_d2h;
     hipEvent_t ev_start = nullptr, ev_done = nullptr;
     bool in_is_null = false, out_is_null = false;  // a chosen copy stream may be the default stream
@@ -60,6 +62,8 @@ void free_streamer(apm_streamer* s) {
     if (s->s_in && !s->in_is_null) (void)hipStreamDestroy(s->s_in);
     if (s->s_out && !s->out_is_null) (void)hipStreamDestroy(s->s_out);
     if (s->s_cmp) (void)hipStreamDestroy(s->s_cmp);
+    if (s->s_res) (void)hipStreamDestroy(s->s_res);
+    if (s->ev_res) (void)hipEventDestroy(s->ev_res);
     for (auto* v : {&s->ev_h2d, &s->ev_cmp, &s->ev_d2h, &s->sched_ev})
         for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     if (s->ev_start) (void)hipEventDestroy(s->ev_start);
@@ -278,11 +282,20 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     if (R < H0 && N > 0) return fail(APM_ESTATE, "model pages [%lld, %lld) are neither resident in the cache nor held by the host pool", (long long)R, (long long)H0);
     if (N - H0 > host->desc.n_pages) return fail(APM_ESTATE, "the host pool holds %lld pages, %lld are needed from model page %lld on", (long long)host->desc.n_pages, (long long)(N - H0), (long long)H0);
     if (direct) {
-        for (int part = 0; part < 2; ++part) {  // resident pages first (HBM speed), then the host pages
+        // The resident pages (HBM speed) and the host pages (PCIe speed) are updated side by side
+        // on two streams; each part has its own range of the per-page scratch.
+        const bool two = R > 0 && R < N;
+        if (two && !s->s_res) {
+            APM_HIP(hipStreamCreateWithFlags(&s->s_res, hipStreamNonBlocking));
+            APM_HIP(hipEventCreateWithFlags(&s->ev_res, hipEventDisableTiming));
+        }
+        if (two) APM_HIP(hipStreamWaitEvent(s->s_res, s->ev_start, 0));
+        for (int part = 0; part < 2; ++part) {
             AdamwLaunch C = L;
             const int64_t first = part == 0 ? 0 : R;
             const int64_t n = part == 0 ? R : N - R;
             if (n == 0) continue;
+            hipStream_t st = part == 0 && two ? s->s_res : s->s_cmp;
             if (part == 0) {
                 C.p32 = static_cast<float*>(s->cache->base[APM_P32]);
                 C.m32 = static_cast<float*>(s->cache->base[APM_M32]);
@@ -294,14 +307,23 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
                 C.stride_wavefronts = s->direct_waves;
                 C.stride_waves_per_wg = s->direct_per_wg;
             }
+            C.meta = L.meta + first;
+            if (need_reduce) {
+                C.partials = L.partials + first * L.S;
+                C.nzflags = L.nzflags + first * L.S;
+            }
             C.state_first = part == 0 ? first : first - H0;
             C.grad_first = first;
             C.n_listed = n;
             C.grad_norm = grad_norm ? grad_norm + first : nullptr;
             C.skip_mask = skip_mask ? skip_mask + first : nullptr;
-            if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
-            else APM_HIP(launch_prepare(C, s->s_cmp));
-            APM_HIP(launch_adamw(C, s->s_cmp));
+            if (need_reduce) APM_HIP(launch_grad_reduce(C, st));
+            else APM_HIP(launch_prepare(C, st));
+            APM_HIP(launch_adamw(C, st));
+        }
+        if (two) {
+            APM_HIP(hipEventRecord(s->ev_res, s->s_res));
+            APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_res, 0));
         }
         APM_HIP(hipEventRecord(s->ev_done, s->s_cmp));
         APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
