@@ -92,6 +92,10 @@ struct PageMeta {
 // list positions and are launched together, with a grid sized for the class's largest extent, so
 // that a nearly empty page (a small tensor alone in its page) does not cost a full page's worth
 // of workgroups that only find out they have nothing to do.
+// Wavefronts of the update kernel when it reads and writes fp32 classes in host memory across
+// PCIe (the streamer's direct mode, the file tier's window); see apm_stream.hip for the sweep.
+constexpr int kDirectWavefronts = 48;
+
 constexpr int kMaxExtentClasses = 4;
 struct ExtentClass {
     int64_t begin;     // first list position

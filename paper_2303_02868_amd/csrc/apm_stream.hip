@@ -50,12 +50,12 @@ struct apm_streamer {
 using namespace apm;
 
 namespace {
-// Wavefronts of the direct-mode kernel when the caller names no number.  Measured on MI355X
-// (PCIe Gen5 x16, GB/s each way, 4 MiB pages, one wavefront per workgroup): 24 -> 44.5, 32 -> 46.6,
+// Wavefronts of the direct-mode kernel when the caller names no number: kDirectWavefronts.
+// Measured on MI355X (PCIe Gen5 x16, GB/s each way, 4 MiB pages, one wavefront per workgroup):
+// 24 -> 44.5, 32 -> 46.6,
 // 40 -> 48.4, 48 -> 49.5, 56 -> 49.4, 64 -> 49.0, 80 -> 48.3, 96 -> 48.0, 256 and more -> 45.4.
 // Packed onto fewer CUs a CU's own memory pipeline becomes the limit: 64 wavefronts reach
 // 47 GB/s at 8 per workgroup and 35 GB/s at 16; 128 at 16 reach 48.
-constexpr int kDirectWavefronts = 48;
 
 void free_streamer(apm_streamer* s) {
     (void)hipDeviceSynchronize();

@@ -225,7 +225,7 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
     L.m32 = t->win_dev[1];
     L.v32 = t->win_dev[2];
     L.meta = dev->d_meta;
-    L.stride_wavefronts = 64;
+    L.stride_wavefronts = kDirectWavefronts;
     L.stride_waves_per_wg = 1;
     const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
     if (need_reduce) {
