@@ -572,3 +572,53 @@ def test_file_tier_reports_a_failed_read_and_drains(tmp_path):
     tier.destroy()
     filep.destroy()
     dev.destroy()
+
+
+def test_streamer_and_tier_argument_errors(tmp_path):
+    E, n = 4096, 6
+    dev = DevicePool(n, E, states=(apm.APM_G16, apm.APM_P16))
+    x = torch.zeros(n * E, dtype=torch.bfloat16, device=DEV)
+    apm.apm_pool_set_layout(dev.pool, apm.make_tensors([n * E], apm.APM_BF16, [x]), 1)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n, state_mask=apm.FP32_STATES)
+    hy = to_hyper(oracle.Hyper())
+
+    def code(fn):
+        with pytest.raises(apm.ApmError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: apm.apm_streamer_create(host, dev.pool, 0, 2)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_create(host, dev.pool, 2, 1)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_create(dev.pool, dev.pool, 2, 2)) == apm.APM_EDEVICE
+    st = apm.apm_streamer_create(host, dev.pool, 2, 2)
+    assert apm.apm_streamer_get_mode(st) == apm.APM_STREAM_DIRECT
+    assert apm.apm_streamer_probe_rates(st) == (0.0, 0.0, 0.0)            # staged set-up has not run
+    assert code(lambda: apm.apm_streamer_copy_only(st, 3)) == apm.APM_ESTATE   # a staged-mode measurement
+    assert code(lambda: apm.apm_streamer_set_mode(st, 7)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_set_mode(st, apm.APM_STREAM_DIRECT, -1)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_set_mode(st, apm.APM_STREAM_DIRECT, 8, 17)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_set_host_first_page(st, n + 1)) == apm.APM_ERANGE
+    apm.apm_streamer_set_host_first_page(st, 2)
+    assert code(lambda: apm.apm_streamer_step(st, 1, hy)) == apm.APM_ESTATE     # pages 0, 1 are nowhere
+    apm.apm_streamer_set_host_first_page(st, 0)
+    assert code(lambda: apm.apm_streamer_step(st, 0, hy)) == apm.APM_EINVAL     # step numbers start at 1
+    apm.apm_streamer_step(st, 1, hy)
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, [(apm.APM_TASK_COMPUTE, 0, 0)], [0, n], 2, hy)) == apm.APM_ESTATE
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, [(9, 0, 0)], [0, n], 2, hy)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, [], [0, n - 1], 2, hy)) == apm.APM_EINVAL
+    torch.cuda.synchronize()
+    st.destroy()
+
+    filep = apm.apm_file_pool_create(str(tmp_path / "s"), E, n)
+    assert code(lambda: apm.apm_tiered_create(host, dev.pool, 2, 2, 2)) == apm.APM_EDEVICE   # not a FILE pool
+    assert code(lambda: apm.apm_tiered_create(filep, dev.pool, 2, 1, 2)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_tiered_create(filep, dev.pool, 2, 2, 0)) == apm.APM_EINVAL
+    assert code(lambda: apm.apm_streamer_create(filep, dev.pool, 2, 2)) == apm.APM_EDEVICE
+    assert code(lambda: apm.apm_page_copy_async(filep, 0, dev.pool, 0, 1, apm.APM_P16)) in (apm.APM_ERANGE, apm.APM_EDEVICE)
+    tier = apm.apm_tiered_create(filep, dev.pool, 4, 2, 2)
+    assert code(lambda: apm.apm_tiered_step(tier, 0, hy)) == apm.APM_EINVAL
+    apm.apm_tiered_step(tier, 1, hy)
+    tier.destroy()
+    filep.destroy()
+    host.destroy()
+    dev.destroy()
