@@ -664,8 +664,17 @@ def cpu_baseline(args, E, n_pages, clip, skip):
     c1 = time.perf_counter()
     one.step(g_rows[:n_one], 2, h)
     c1 = time.perf_counter() - c1
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     return {"value": n_cpu * E * args.cpu_steps / cw, "unit": "params/s", "cores": threads,
-            "kind": "oracle", "single_thread_value": n_one * E / c1,
+            "kind": "oracle", "single_thread_value": n_one * E / c1, "cpu_model": model,
+            "host_cpus": os.cpu_count(),
             "sample": f"{n_cpu} full pages x {args.cpu_steps} steps of the same update (reduce + AdamW "
                       f"in double), pages split over {threads} threads, {cw:.2f} s wall"}
 
