@@ -119,9 +119,10 @@ extern "C" int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* la
     if (n_layers > 0 && layer_offsets[0] != 0) return fail(APM_EINVAL, "layer_offsets[0] must be 0");
     if (P != n_pages) return fail(APM_EINVAL, "the layers list %lld pages, n_pages is %lld: every page belongs to exactly one layer", (long long)P, (long long)n_pages);
     if (P > 0 && !layer_pages) return fail(APM_EINVAL, "layer_pages is NULL");
+    for (int64_t i = 0; i < n_layers; ++i)  // before anything is read through them
+        if (layer_offsets[i + 1] < layer_offsets[i] || layer_offsets[i + 1] > P) return fail(APM_EINVAL, "layer_offsets must not decrease");
     std::vector<int32_t> owner((size_t)n_pages, -1);  // by page id
     for (int64_t i = 0; i < n_layers; ++i) {
-        if (layer_offsets[i + 1] < layer_offsets[i]) return fail(APM_EINVAL, "layer_offsets must not decrease");
         if (layer_bytes[i] < 0) return fail(APM_EINVAL, "layer_bytes[%lld] is negative", (long long)i);
         for (int64_t k = layer_offsets[i]; k < layer_offsets[i + 1]; ++k) {
             const int64_t p = layer_pages[k];
