@@ -76,7 +76,7 @@ typedef struct {
     int32_t device;     /* apm_device */
     int32_t hip_device; /* HIP device ordinal that owns / addresses the pool */
     int64_t page_elems; /* E > 0, a multiple of 8 */
-    int64_t n_pages;    /* capacity in page groups, > 0 */
+    int64_t n_pages;    /* capacity in page groups, > 0, at most 2^31 - 1 */
     uint32_t state_mask; /* bit s set = the pool stores state class s */
     uint32_t flags;      /* apm_pool_flags */
     /* base[s] != NULL: caller-owned region for class s (n_pages*E elements, 16-byte aligned,
@@ -226,8 +226,8 @@ int apm_unpack(apm_pool* pool, int state, const apm_tensor* dst, int64_t n, void
  * pages: host pointer to n_pages distinct page indices, or NULL = pages [0, n_pages).
  * grad_norm (float[n_pages]) and skip_mask (uint8_t[n_pages]): device pointers, nullable,
  * indexed like `pages`, written by the kernel.
- * Errors: APM_EINVAL (step < 1, bad hyper-parameters, NULL hyper), APM_ERANGE (page index),
- * APM_ESTATE (pool lacks a class), APM_EDEVICE.
+ * Errors: APM_EINVAL (step < 1, bad hyper-parameters, NULL hyper, a page listed twice),
+ * APM_ERANGE (page index), APM_ESTATE (pool lacks a class), APM_EDEVICE.
  */
 int apm_page_adamw_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t step,
                         const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,

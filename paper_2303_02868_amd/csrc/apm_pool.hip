@@ -222,6 +222,7 @@ extern "C" int apm_pool_create(apm_pool** out, const apm_pool_desc* desc) {
     if (desc->page_elems <= 0 || desc->page_elems % kAlign != 0) return fail(APM_EINVAL, "page_elems must be a positive multiple of %lld", (long long)kAlign);
     if (desc->page_elems > (int64_t)1 << 30) return fail(APM_EINVAL, "page_elems above 2^30 is not supported");
     if (desc->n_pages <= 0) return fail(APM_EINVAL, "n_pages must be positive");
+    if (desc->n_pages > INT32_MAX || desc->n_pages > ((int64_t)1 << 60) / desc->page_elems) return fail(APM_EINVAL, "n_pages = %lld is beyond what a pool can index", (long long)desc->n_pages);
     if (desc->state_mask == 0 || desc->state_mask >> APM_N_STATES) return fail(APM_EINVAL, "bad state_mask 0x%x", desc->state_mask);
     for (int st = 0; st < APM_N_STATES; ++st)
         if (desc->base[st] && (reinterpret_cast<uintptr_t>(desc->base[st]) & 15u)) return fail(APM_EINVAL, "base[%d] is not 16-byte aligned", st);
@@ -379,7 +380,8 @@ extern "C" int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* sr
     if (!dst->stores(state) || !src->stores(state)) return fail(APM_ERANGE, "state class %d is not stored by both pools", state);
     if (dst->desc.page_elems != src->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
     if (n_pages < 0) return fail(APM_EINVAL, "negative page count");
-    if (dst_page < 0 || dst_page + n_pages > dst->desc.n_pages || src_page < 0 || src_page + n_pages > src->desc.n_pages)
+    if (dst_page < 0 || dst_page > dst->desc.n_pages || n_pages > dst->desc.n_pages - dst_page ||
+        src_page < 0 || src_page > src->desc.n_pages || n_pages > src->desc.n_pages - src_page)
         return fail(APM_ERANGE, "page range out of bounds");
     if (n_pages == 0) return APM_OK;
     if (dst->desc.device == APM_DEV_FILE || src->desc.device == APM_DEV_FILE) {

@@ -75,9 +75,21 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     const int64_t in_use = pool->has_layout ? (int64_t)pool->plan.pages.size() : 0;
     auto page_at = [&](int64_t k) { return pages ? pages[k] : k; };
     auto used_of = [&](int64_t page) { return page < in_use ? pool->plan.pages[(size_t)page].used : (int64_t)0; };
-    if (pages)
-        for (int64_t k = 0; k < n_pages; ++k)
+    if (pages) {
+        // Two workgroups updating one page at once would race: a listed page is listed once.
+        std::vector<uint8_t> seen((size_t)pool->desc.n_pages, 0);
+        for (int64_t k = 0; k < n_pages; ++k) {
             if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] = %lld out of range [0, %lld)", (long long)k, (long long)pages[k], (long long)pool->desc.n_pages);
+            if (seen[(size_t)pages[k]]) return fail(APM_EINVAL, "pages[%lld] = %lld is listed twice", (long long)k, (long long)pages[k]);
+            seen[(size_t)pages[k]] = 1;
+        }
+    }
+    if (grad_tensors || p16_tensors) {  // the tensors cover the pages of the layout and no others
+        if (!pages && n_pages > in_use) return fail(APM_ERANGE, "page count %lld exceeds the %lld pages in use", (long long)n_pages, (long long)in_use);
+        if (pages)
+            for (int64_t k = 0; k < n_pages; ++k)
+                if (pages[k] >= in_use) return fail(APM_ERANGE, "pages[%lld] = %lld is not in use by the layout", (long long)k, (long long)pages[k]);
+    }
     auto class_of = [&](int64_t used) { return used * 4 > E ? 0 : used * 32 > E ? 1 : used * 512 > E ? 2 : 3; };
     int64_t cnt[kMaxExtentClasses] = {}, mx[kMaxExtentClasses] = {};
     for (int64_t k = 0; k < n_pages; ++k) {
@@ -149,10 +161,6 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     }
 
     if (grad_tensors || p16_tensors) {
-        if (!pages && n_pages > in_use) return fail(APM_ERANGE, "page count %lld exceeds the %lld pages in use", (long long)n_pages, (long long)in_use);
-        if (pages)
-            for (int64_t k = 0; k < n_pages; ++k)
-                if (pages[k] >= in_use) return fail(APM_ERANGE, "pages[%lld] = %lld is not in use by the layout", (long long)k, (long long)pages[k]);
         // One PageSegs entry per list position, rebuilt per call: the tensors are caller-owned and
         // their addresses may change from step to step.
         const size_t n_in_use = pool->plan.pages.size();
@@ -218,6 +226,7 @@ int ensure_delayed(apm_pool* pool) {
     if (pool->upd_stream) return APM_OK;
     const size_t bytes = (size_t)pool->desc.n_pages * (size_t)pool->desc.page_elems * 2u;
     for (int k = 0; k < 2; ++k) {
+        if (pool->gbuf[k]) continue;  // kept from an attempt that failed further down
         hipError_t e = hipMalloc((void**)&pool->gbuf[k], bytes);
         if (e != hipSuccess) {
             (void)hipGetLastError();
@@ -232,10 +241,10 @@ int ensure_delayed(apm_pool* pool) {
     // alignment gaps inside a page's used extent are read as gradient.
     for (int k = 0; k < 2; ++k) APM_HIP(hipMemset(pool->gbuf[k], 0, bytes));
     for (int k = 0; k < 2; ++k) {
-        APM_HIP(hipEventCreateWithFlags(&pool->ev_staged[k], hipEventDisableTiming));
-        APM_HIP(hipEventCreateWithFlags(&pool->ev_applied[k], hipEventDisableTiming));
+        if (!pool->ev_staged[k]) APM_HIP(hipEventCreateWithFlags(&pool->ev_staged[k], hipEventDisableTiming));
+        if (!pool->ev_applied[k]) APM_HIP(hipEventCreateWithFlags(&pool->ev_applied[k], hipEventDisableTiming));
     }
-    APM_HIP(hipEventCreateWithFlags(&pool->ev_flush, hipEventDisableTiming));
+    if (!pool->ev_flush) APM_HIP(hipEventCreateWithFlags(&pool->ev_flush, hipEventDisableTiming));
     APM_HIP(hipStreamCreateWithFlags(&pool->upd_stream, hipStreamNonBlocking));
     return APM_OK;
 }

@@ -424,7 +424,7 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
 }
 
 // Alg. 2 with the optimizer states off the GPU: the updating side is the streamed step (in direct
-// mode a 64-wavefront kernel working through the host pages), the buffering side the caller's
+// mode a few dozen wavefronts working through the host pages), the buffering side the caller's
 // stream handing over the next gradient.
 extern "C" int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, const apm_hyper* hyper,
                                          void* stream) {

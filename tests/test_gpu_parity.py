@@ -515,6 +515,9 @@ def test_error_paths_and_page_table():
     with pytest.raises(apm.ApmError) as e:
         apm.apm_page_adamw_step(dp.pool, None, 2, 1, apm.make_hyper(beta1=1.0))
     assert e.value.code == apm.APM_EINVAL
+    with pytest.raises(apm.ApmError) as e:                    # one page, two updates at once
+        apm.apm_page_adamw_step(dp.pool, [3, 1, 3], 3, 1, hy)
+    assert e.value.code == apm.APM_EINVAL and "twice" in str(e.value)
     apm.apm_page_adamw_step(dp.pool, None, 0, 1, hy)          # empty list: a no-op
     # layout too large for the pool
     big = apm.make_tensors([7 * E], apm.APM_F32)
