@@ -8,113 +8,18 @@
 // the one-step-stale form, the library's updater thread -- Alg. 2's two actors as two host
 // threads) waits for a slot's reads, enqueues the kernels, waits for their event and hands the
 // slot to the writers; the last write of a slot starts the reads of the batch that reuses it.
-#include <fcntl.h>
-#include <unistd.h>
-
 #include <cerrno>
-#include <condition_variable>
-#include <cstdlib>
 #include <cstring>
-#include <deque>
-#include <mutex>
 #include <string>
 #include <thread>
 
 #include "apm_internal.h"
+#include "apm_io.h"
 
 using namespace apm;
-
-namespace {
-
-constexpr size_t kIoPiece = (size_t)8 << 20;  // bytes per pread / pwrite task
-
-class IoPool {
- public:
-    explicit IoPool(int n) {
-        for (int k = 0; k < n; ++k) thr_.emplace_back([this] { run(); });
-    }
-    ~IoPool() {
-        {
-            std::lock_guard<std::mutex> g(m_);
-            stop_ = true;
-        }
-        cv_.notify_all();
-        for (auto& t : thr_) t.join();
-    }
-    void submit(std::function<void()> f) {
-        {
-            std::lock_guard<std::mutex> g(m_);
-            q_.push_back(std::move(f));
-        }
-        cv_.notify_one();
-    }
-
- private:
-    void run() {
-        for (;;) {
-            std::function<void()> f;
-            {
-                std::unique_lock<std::mutex> g(m_);
-                cv_.wait(g, [this] { return stop_ || !q_.empty(); });
-                if (q_.empty()) return;  // stop requested and nothing left
-                f = std::move(q_.front());
-                q_.pop_front();
-            }
-            f();
-        }
-    }
-    std::vector<std::thread> thr_;
-    std::deque<std::function<void()>> q_;
-    std::mutex m_;
-    std::condition_variable cv_;
-    bool stop_ = false;
-};
-
-// Reads or writes exactly `len` bytes at `off`; 0 or an errno value.
-int io_full(int fd, char* buf, size_t len, off_t off, bool write) {
-    while (len > 0) {
-        const ssize_t r = write ? pwrite(fd, buf, len, off) : pread(fd, buf, len, off);
-        if (r < 0) {
-            if (errno == EINTR) continue;
-            return errno;
-        }
-        if (r == 0) return EIO;  // a short file: the pool's files are created at full size
-        buf += r;
-        off += r;
-        len -= (size_t)r;
-    }
-    return 0;
-}
-
-// Unbuffered I/O cannot address GPU-pinned host memory directly (the kernel refuses to pin the
-// driver's mapping: EFAULT), so with APM_POOL_FILE_DIRECT every piece passes through an ordinary
-// page-aligned buffer of the calling thread.
-int io_piece(int fd, char* buf, size_t len, off_t off, bool write, bool direct) {
-    if (!direct) return io_full(fd, buf, len, off, write);
-    struct Bounce {
-        void* p = nullptr;
-        ~Bounce() { free(p); }
-    };
-    static thread_local Bounce bounce;
-    if (!bounce.p && posix_memalign(&bounce.p, 4096, kIoPiece) != 0) {
-        bounce.p = nullptr;
-        return ENOMEM;
-    }
-    char* b = static_cast<char*>(bounce.p);
-    while (len > 0) {
-        const size_t n = len < kIoPiece ? len : kIoPiece;
-        if (write) std::memcpy(b, buf, n);
-        const int err = io_full(fd, b, n, off, write);
-        if (err) return err;
-        if (!write) std::memcpy(buf, b, n);
-        buf += n;
-        off += (off_t)n;
-        len -= n;
-    }
-    return 0;
-}
-
-}  // namespace
+using apm::io::IoPool;
+using apm::io::WindowChain;
+using apm::io::io_piece;
 
 struct apm_tiered {
     apm_pool* file = nullptr;
@@ -127,15 +32,7 @@ struct apm_tiered {
     hipEvent_t ev_start = nullptr;
     std::vector<hipEvent_t> ev_done;  // per slot
     IoPool* io = nullptr;
-
-    // progress of the running step (guarded by m)
-    std::mutex m;
-    std::condition_variable cv;
-    std::vector<int64_t> loaded;    // per slot: batch whose pages are in the window, -1 = none
-    std::vector<int> pending;       // per slot: outstanding pieces of the current read or write
-    int64_t batches_written = 0;
-    int io_errno = 0;
-    int64_t n_batches = 0, n_pages = 0;
+    WindowChain* chain = nullptr;  // the batches' way through the window (apm_io.h)
 
     // one-step-stale form
     std::thread updater;
@@ -150,55 +47,13 @@ namespace {
 void free_tiered(apm_tiered* t) {
     if (t->updater.joinable()) t->updater.join();
     delete t->io;  // drains and joins the I/O threads
+    delete t->chain;
     (void)hipDeviceSynchronize();
     for (char* p : t->win) if (p) (void)hipHostFree(p);
     for (hipEvent_t e : t->ev_done) if (e) (void)hipEventDestroy(e);
     if (t->ev_start) (void)hipEventDestroy(t->ev_start);
     if (t->s_cmp) (void)hipStreamDestroy(t->s_cmp);
     delete t;
-}
-
-// Queues the reads (write == false) or writes of batch b through the I/O threads.  When the last
-// piece of a write completes, the reads of the batch that reuses the slot are queued.
-void queue_io(apm_tiered* t, int64_t b, bool write) {
-    const int64_t E = t->dev->desc.page_elems;
-    const size_t pb = (size_t)E * sizeof(float);
-    const int slot = (int)(b % t->n_slots);
-    const int64_t first = b * t->B;
-    const int64_t nb = t->n_pages - first < t->B ? t->n_pages - first : t->B;
-    const size_t bytes = pb * (size_t)nb;
-    const int pieces_per_class = (int)((bytes + kIoPiece - 1) / kIoPiece);
-    {
-        std::lock_guard<std::mutex> g(t->m);
-        t->pending[(size_t)slot] = 3 * pieces_per_class;
-    }
-    const int states[3] = {APM_P32, APM_M32, APM_V32};
-    for (int c = 0; c < 3; ++c) {
-        for (int k = 0; k < pieces_per_class; ++k) {
-            const size_t o = (size_t)k * kIoPiece;
-            const size_t len = bytes - o < kIoPiece ? bytes - o : kIoPiece;
-            char* buf = t->win[c] + (size_t)slot * (size_t)t->B * pb + o;
-            const off_t off = (off_t)((size_t)first * pb + o);
-            const int fd = t->file->fd[states[c]];
-            const bool direct = (t->file->desc.flags & APM_POOL_FILE_DIRECT) != 0;
-            t->io->submit([t, b, slot, write, fd, buf, len, off, direct] {
-                const int err = io_piece(fd, buf, len, off, write, direct);
-                bool last = false;
-                {
-                    std::lock_guard<std::mutex> g(t->m);
-                    if (err && !t->io_errno) t->io_errno = err;
-                    last = --t->pending[(size_t)slot] == 0;
-                    if (last) {
-                        if (write) ++t->batches_written;
-                        else t->loaded[(size_t)slot] = b;
-                    }
-                }
-                if (!last) return;
-                if (write && b + t->n_slots < t->n_batches) queue_io(t, b + t->n_slots, false);
-                t->cv.notify_all();
-            });
-        }
-    }
 }
 
 // One step; blocks until the last write has completed.  caller != nullptr: the kernels start after
@@ -232,61 +87,23 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
         L.partials = dev->d_partials;
         L.nzflags = dev->d_nzflags;
     }
-    {
-        std::lock_guard<std::mutex> g(t->m);
-        t->n_pages = N;
-        t->n_batches = (N + t->B - 1) / t->B;
-        t->batches_written = 0;
-        t->io_errno = 0;
-        for (auto& x : t->loaded) x = -1;
-        for (auto& x : t->pending) x = 0;
-    }
-    const int64_t nbatches = t->n_batches;
-    for (int64_t b = 0; b < nbatches && b < t->n_slots; ++b) queue_io(t, b, false);
+    // Kernels are skipped after a failure, but every batch still passes through the chain so that
+    // the step drains.
     hipError_t gpu_err = hipSuccess;
-    for (int64_t b = 0; b < nbatches; ++b) {
-        const int slot = (int)(b % t->n_slots);
-        {
-            std::unique_lock<std::mutex> g(t->m);
-            t->cv.wait(g, [&] { return t->loaded[(size_t)slot] == b; });
-        }
-        const int64_t first = b * t->B;
-        const int64_t nb = N - first < t->B ? N - first : t->B;
-        // Kernels are skipped after a failure, but every batch still passes through the writers so
-        // that the slot chain keeps moving and the step drains.
-        bool failed;
-        {
-            std::lock_guard<std::mutex> g(t->m);
-            failed = t->io_errno != 0;
-        }
-        if (!failed && gpu_err == hipSuccess) {
-            AdamwLaunch C = L;
-            C.state_first = (int64_t)slot * t->B;
-            C.grad_first = first;
-            C.n_listed = nb;
-            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
-            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
-            gpu_err = need_reduce ? launch_grad_reduce(C, t->s_cmp) : launch_prepare(C, t->s_cmp);
-            if (gpu_err == hipSuccess) gpu_err = launch_adamw(C, t->s_cmp);
-            if (gpu_err == hipSuccess) gpu_err = hipEventRecord(t->ev_done[(size_t)slot], t->s_cmp);
-            if (gpu_err == hipSuccess) gpu_err = hipEventSynchronize(t->ev_done[(size_t)slot]);
-        }
-        if (!failed && gpu_err == hipSuccess) {
-            queue_io(t, b, true);
-        } else {
-            // nothing valid to write: account for the batch and keep the chain going
-            {
-                std::lock_guard<std::mutex> g(t->m);
-                ++t->batches_written;
-            }
-            if (b + t->n_slots < nbatches) queue_io(t, b + t->n_slots, false);
-        }
-    }
-    {
-        std::unique_lock<std::mutex> g(t->m);
-        t->cv.wait(g, [&] { return t->batches_written == nbatches; });
-        if (t->io_errno) return fail(APM_EDEVICE, "file I/O failed during the step: %s (the files may hold a partly updated state)", strerror(t->io_errno));
-    }
+    const int io_err = t->chain->run(N, [&](int64_t, int slot, int64_t first, int64_t nb) {
+        AdamwLaunch C = L;
+        C.state_first = (int64_t)slot * t->B;
+        C.grad_first = first;
+        C.n_listed = nb;
+        C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+        C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+        gpu_err = need_reduce ? launch_grad_reduce(C, t->s_cmp) : launch_prepare(C, t->s_cmp);
+        if (gpu_err == hipSuccess) gpu_err = launch_adamw(C, t->s_cmp);
+        if (gpu_err == hipSuccess) gpu_err = hipEventRecord(t->ev_done[(size_t)slot], t->s_cmp);
+        if (gpu_err == hipSuccess) gpu_err = hipEventSynchronize(t->ev_done[(size_t)slot]);
+        return gpu_err == hipSuccess;
+    });
+    if (io_err > 0) return fail(APM_EDEVICE, "file I/O failed during the step: %s (the files may hold a partly updated state)", strerror(io_err));
     if (gpu_err != hipSuccess) return fail(APM_EDEVICE, "a kernel launch of the step failed: %s", hipGetErrorString(gpu_err));
     return APM_OK;
 }
@@ -397,9 +214,10 @@ extern "C" int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev
     }
     int rc = ensure_scratch(dev);
     if (rc != APM_OK) { free_tiered(t); return rc; }
-    t->loaded.assign((size_t)n_slots, -1);
-    t->pending.assign((size_t)n_slots, 0);
     t->io = new IoPool(io_threads);
+    const int fds[3] = {file->fd[APM_P32], file->fd[APM_M32], file->fd[APM_V32]};
+    t->chain = new WindowChain(t->io, fds, t->win, (size_t)dev->desc.page_elems * sizeof(float), batch_pages,
+                               n_slots, (file->desc.flags & APM_POOL_FILE_DIRECT) != 0);
     *out = t;
     return APM_OK;
 }
