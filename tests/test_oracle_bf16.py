@@ -53,3 +53,20 @@ def test_is_nearest_even_by_brute_force():
     want = np.where(d_lo < d_hi, lo_bits, np.where(d_hi < d_lo, hi_bits,
                     np.where((lo_bits & 1) == 0, lo_bits, hi_bits)))
     assert np.array_equal(oracle.bf16_rne(u), want.astype(np.uint16))
+
+
+def test_matches_library_cast_on_every_fp32_pattern():
+    """All 2^32 fp32 bit patterns, in 64 chunks: the oracle's cast equals the library's on every
+    non-NaN pattern, and every NaN stays a NaN of the same sign."""
+    chunk = 1 << 26
+    for c in range(64):
+        u = np.arange(c * chunk, (c + 1) * chunk, dtype=np.uint64).astype(np.uint32)
+        got = oracle.bf16_rne(u)
+        nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+        want = torch_cast(u)
+        if nan.any():
+            assert np.all((got[nan] & 0x7F80) == 0x7F80) and np.all((got[nan] & 0x007F) != 0)
+            assert np.array_equal(got[nan] >> 15, (u[nan] >> 31).astype(np.uint16))
+            got[nan] = 0
+            want[nan] = 0
+        assert np.array_equal(got, want), f"chunk {c}"
