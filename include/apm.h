@@ -224,8 +224,8 @@ int apm_unpack(apm_pool* pool, int state, const apm_tensor* dst, int64_t n, void
  * a NaN norm s = NaN).
  *
  * pages: host pointer to n_pages distinct page indices, or NULL = pages [0, n_pages).
- * grad_norm (float[n_pages]) and skip_mask (uint8_t[n_pages]): device pointers, nullable,
- * indexed like `pages`, written by the kernel.
+ * grad_norm (float[n_pages]) and skip_mask (uint8_t[n_pages]): device pointers (or pinned host
+ * memory, which the GPU addresses as well), nullable, indexed like `pages`, written by the kernel.
  * Errors: APM_EINVAL (step < 1, bad hyper-parameters, NULL hyper, a page listed twice),
  * APM_ERANGE (page index), APM_ESTATE (pool lacks a class), APM_EDEVICE.
  */

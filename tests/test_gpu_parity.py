@@ -502,6 +502,32 @@ def test_no_outputs_no_clip_path_matches_path_with_reduce():
     b.destroy()
 
 
+def test_outputs_in_pinned_host_memory_equal_outputs_in_device_memory():
+    # grad_norm / skip_mask are written by the kernel: any memory the GPU can address will do
+    E = 4096
+    specs = [synth.TensorSpec(0, "a", 3 * E + 40), synth.TensorSpec(1, "b", 9), synth.TensorSpec(2, "c", 2 * E)]
+    model = Model(specs, E, seed=11)
+    n = model.plan.n_pages
+    dp = DevicePool(n, E)
+    apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), len(specs))
+    g = model.grad_flat(1)
+    g[int(model.off[1]):int(model.off[2])] = 0                    # tensor b: an all-zero page
+    apm.apm_pack_tensors(dp.pool, apm.APM_G16, model.tensors(g), len(specs))
+    hy = apm.make_hyper(max_grad_norm=0.01, skip_mode=apm.APM_SKIP_UNTOUCHED)
+    listed = list(reversed(range(n)))
+    norm_d = torch.full((n,), -1.0, dtype=torch.float32, device=DEV)
+    skip_d = torch.full((n,), 7, dtype=torch.uint8, device=DEV)
+    norm_h = torch.full((n,), -1.0, dtype=torch.float32).pin_memory()
+    skip_h = torch.full((n,), 7, dtype=torch.uint8).pin_memory()
+    apm.apm_page_adamw_step(dp.pool, listed, n, 1, hy, norm_d, skip_d)
+    apm.apm_page_adamw_step(dp.pool, listed, n, 2, hy, norm_h, skip_h)
+    torch.cuda.synchronize()
+    assert torch.equal(norm_d.cpu().view(torch.int32), norm_h.view(torch.int32))
+    assert torch.equal(skip_d.cpu(), skip_h)
+    assert int(skip_h.sum()) == 1 and float(norm_h.max()) > 0.01
+    dp.destroy()
+
+
 def test_error_paths_and_page_table():
     E = 1024
     dp = DevicePool(6, E)
