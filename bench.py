@@ -889,8 +889,39 @@ def page_sweep_leg(args):
         streamer.destroy()
         host.destroy()
         pool.destroy()
+        if args.file_tier:
+            row.update(file_tier_page_row(args, g, E, hyper, stream))
         rows.append(row)
     return rows
+
+
+def file_tier_page_row(args, g, E, hyper, stream):
+    """The file tier moving one page per batch (2^28 elements, 1 GiB per class): the page is then the
+    unit of I/O, as it is the unit of the paper's SSD transfers."""
+    import torch
+    import paper_2303_02868_amd as apm
+    total = 1 << 28
+    n = total // E
+    pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n, state_mask=apm.B16_STATES)
+    apm.apm_pack_tensors(pool, apm.APM_G16, apm.make_tensors([total], apm.APM_BF16, [g]), 1)
+    torch.cuda.synchronize()
+    out = {}
+    for name, flags in (("buffered", 0), ("unbuffered", apm.APM_POOL_FILE_DIRECT)):
+        if flags and 4 * E % 4096:
+            continue
+        prefix = os.path.join(args.file_tier, f"apm_sweep_{os.getpid()}_{E}_{name}")
+        filep = apm.apm_file_pool_create(prefix, E, n, flags=flags)     # zero-filled (sparse) files
+        tier = apm.apm_tiered_create(filep, pool, 1, 8, args.io_threads)
+        apm.apm_tiered_step(tier, 1, hyper, None, None, stream)          # writes every page once
+        t0 = time.perf_counter()
+        apm.apm_tiered_step(tier, 2, hyper, None, None, stream)
+        out[f"file_{name}_one_page_per_batch_GBps_each_way"] = total * 12 / (time.perf_counter() - t0) / 1e9
+        tier.destroy()
+        filep.destroy()
+        for suffix in (".p32", ".m32", ".v32"):
+            os.remove(prefix + suffix)
+    pool.destroy()
+    return out
 
 
 def full_shape_leg(args, hyper):
