@@ -622,3 +622,80 @@ def test_streamer_and_tier_argument_errors(tmp_path):
     filep.destroy()
     host.destroy()
     dev.destroy()
+
+
+@pytest.mark.parametrize("form", ["resident", "fused", "delayed", "direct", "staged"])
+def test_calls_on_a_side_stream_are_ordered_by_that_stream(form):
+    # Everything (input generation, pack, steps, unpack) is enqueued on one non-default stream with
+    # no synchronisation in between: a call that put part of its work on another stream, or joined
+    # the caller's stream too early, would read gradients that are still being generated.
+    E = 65536
+    specs = [synth.TensorSpec(0, "a", 40 * E + 12), synth.TensorSpec(1, "b", 300), synth.TensorSpec(2, "c", 23 * E),
+             synth.TensorSpec(3, "d", 7), synth.TensorSpec(4, "e", 9 * E + 1000)]
+    model = Model(specs, E, seed=31, align_elems=8)
+    n_pages, n_t = model.plan.n_pages, len(specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=0.05))
+    steps = 3
+
+    def run(side):
+        s = torch.cuda.Stream() if side else torch.cuda.current_stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            streamed = form in ("direct", "staged")
+            dp = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16) if streamed else (0, 1, 2, 3, 4))
+            torch.cuda.synchronize()
+            host = st = None
+            if streamed:
+                tmp = DevicePool(n_pages, E, states=(apm.APM_P32,))
+                torch.cuda.synchronize()
+                apm.apm_pack_tensors(tmp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t, stream=s)
+                apm.apm_pool_set_layout(dp.pool, model.tensors(model.p_flat), n_t, stream=s)
+                host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+                apm.apm_page_copy_async(host, 0, tmp.pool, 0, n_pages, apm.APM_P32, stream=s)
+                st = apm.apm_streamer_create(host, dp.pool, 8, 3)
+                set_mode(st, form)
+            else:
+                apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t, stream=s)
+            norm = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+            q_flat = torch.zeros(model.total, dtype=torch.bfloat16, device=DEV)
+            keep = []
+            for t in range(1, steps + 1):
+                if side and hasattr(torch.cuda, "_sleep"):
+                    torch.cuda._sleep(50_000_000)            # a bounded spin (tens of ms) ahead of the inputs
+                g = model.grad_flat(t)                       # many kernels on s
+                keep.append(g)
+                if form == "fused":
+                    apm.apm_page_adamw_step_fused(dp.pool, None, n_pages, t, hy, model.tensors(g),
+                                                  model.tensors(q_flat), n_t, norm, None, stream=s)
+                    continue
+                apm.apm_pack_tensors(dp.pool, apm.APM_G16, model.tensors(g), n_t, stream=s)
+                if form == "resident":
+                    apm.apm_page_adamw_step(dp.pool, list(reversed(range(n_pages))), n_pages, t, hy, norm, None, stream=s)
+                elif form == "delayed":
+                    apm.apm_step_delayed(dp.pool, None, n_pages, dp.reg[apm.APM_G16], hy, stream=s)
+                else:
+                    apm.apm_streamer_step(st, t, hy, norm, None, stream=s)
+            if form == "delayed":
+                apm.apm_step_delayed(dp.pool, None, n_pages, None, hy, stream=s)
+            if form != "fused":
+                apm.apm_unpack(dp.pool, apm.APM_P16, model.tensors(q_flat), n_t, stream=s)
+            s.synchronize()
+            torch.cuda.synchronize()
+            if streamed:
+                out = [host_view(host, c, n_pages, E).view(np.uint32).copy() for c in (apm.APM_P32, apm.APM_M32, apm.APM_V32)]
+                st.destroy()
+                host.destroy()
+                tmp.destroy()
+            else:
+                out = [dp.reg[c].cpu().numpy().view(np.uint32) for c in (apm.APM_P32, apm.APM_M32, apm.APM_V32)]
+            out.append(bf16_bits(q_flat))
+            if form != "delayed":
+                out.append(norm.cpu().numpy().view(np.uint32))
+            dp.destroy()
+        return out
+
+    want = run(False)
+    got = run(True)
+    for k, (a, b) in enumerate(zip(want, got)):
+        assert np.array_equal(a, b), f"output {k} differs between the default stream and a side stream"
+    assert want[0].any() and want[3].any()
