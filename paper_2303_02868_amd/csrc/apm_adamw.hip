@@ -3,7 +3,9 @@
 //   apm_grad_finalize_kernel  per page: norm, clip scale, skip decision -> the page's record
 //   apm_page_meta_kernel      the page records when no reduce pass is needed
 //   apm_adamw_kernel          the fused update (optionally gathering g16 from / scattering p16 to
-//                             the caller's tensors)
+//                             the caller's tensors), one workgroup per page slice
+//   apm_adamw_stride_kernel   the same slice body run by a fixed, small number of wavefronts that
+//                             stride over all slices (fp32 classes in host memory across PCIe)
 //   apm_grad_accum_kernel     g' += g for the buffered gradient of the delayed path
 //
 // All are HBM-bandwidth bound (no reuse, ~50 VALU operations per element at most), so the design
@@ -13,7 +15,8 @@
 //
 // Work decomposition: grid.y walks the listed pages, grid.x the fixed-size slices of a page;
 // slices that start beyond the page's used extent exit at once.  The page table (`used`) is read
-// on the device, so a call needs no host-side knowledge of extents.
+// on the device; the host, which knows the extents from the layout, only sizes the grids (pages
+// grouped into extent classes) so that few workgroups are launched for nothing.
 #include "apm_internal.h"
 
 namespace apm {
