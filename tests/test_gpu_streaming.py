@@ -440,6 +440,16 @@ def test_streamer_delayed_calls_plus_flush_equal_synchronous_steps(mode):
     init.destroy()
 
 
+def needs_unbuffered_io(tmp_path):
+    """Skips when the directory's file system refuses O_DIRECT (a memory file system does)."""
+    probe = str(tmp_path / "o_direct_probe")
+    try:
+        os.close(os.open(probe, os.O_RDWR | os.O_CREAT | os.O_DIRECT, 0o600))
+    except OSError as e:
+        pytest.skip(f"no unbuffered I/O in {tmp_path}: {e}")
+    os.remove(probe)
+
+
 def file_rows(prefix, suffix, n_pages, E):
     return np.fromfile(prefix + suffix, dtype=np.uint32).reshape(n_pages, E)
 
@@ -457,6 +467,8 @@ def test_file_tier_step_equals_resident_bit_exact(tmp_path, batch, slots, thread
     apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
     prefix = str(tmp_path / "state")
     fl = apm.APM_POOL_FILE_DIRECT if flags == "direct" else 0
+    if fl:
+        needs_unbuffered_io(tmp_path)
     filep = apm.apm_file_pool_create(prefix, E, n_pages, flags=fl)
     # initial master parameters reach the files through a host pool
     host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
