@@ -31,7 +31,9 @@ static double bf16_to_double(uint16_t b) {
     return (double)f; /* exact */
 }
 
-/* Round-to-nearest-even of an fp32 bit pattern to bf16, written on the integer representation. */
+/* Round-to-nearest-even of an fp32 bit pattern to bf16, written on the integer representation.
+ * Pinned on every fp32 pattern against a library cast; for NaN inputs the pins fix that the result
+ * is a NaN of the same sign -- which payload bits it carries is parity unpinned. */
 uint16_t oracle_bf16_rne(uint32_t u) {
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) /* NaN: keep sign/payload top bits, force quiet bit */
         return (uint16_t)((u >> 16) | 0x0040u);
