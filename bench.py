@@ -770,6 +770,9 @@ def main():
                            "avg_launch_ms": r["upd_ms"]}
         out["kernels"] = r["kernels"]
         out["d2d_copy_GBps"] = d2d_copy_ceiling()
+        seg = out.get("unfused_step", {}).get("kernels", {}).get("seg_copy_bf16")
+        if seg:   # this library's plain copy kernel in the same run: the practical ceiling beside the 8 TB/s
+            out["roofline"]["plain_copy_kernel_GBps"] = seg["GBps"]
         if args.workload == "moe_8x64" and not args.update_only:
             out["delayed"] = delayed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
             out["active_page_list"] = moe_active_list_leg(args, wl, pool, hyper, plan, r["next_step"] + 100)
