@@ -521,8 +521,11 @@ def file_tier_leg(args, wl, hyper, n_pages):
     import torch
     import paper_2303_02868_amd as apm
     E = wl.E
+    import synth
     dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=apm.B16_STATES)
-    apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+    # MoE: the experts of one step's draw have a gradient; skipped pages then need no file I/O
+    act = synth.moe_active_tensors(wl.specs, 1, 0, 64, 8) if wl.name == "moe_8x64" else None
+    apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3, act)), wl.n_t)
     host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
     tmp = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=1 << apm.APM_P32)
     apm.apm_pack_tensors(tmp, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
@@ -545,9 +548,11 @@ def file_tier_leg(args, wl, hyper, n_pages):
             t0 = time.perf_counter()
             apm.apm_tiered_step(tier, 2 + k, hyper, None, None, stream)
             ts.append(time.perf_counter() - t0)
+        rd, wr = apm.apm_tiered_io_bytes(tier)
+        per_step = rd / (1 + args.stream_steps)          # bytes read (= written) per step
         res = {"write_p32_GBps": n_pages * E * 4 / t_init / 1e9, "ms_per_step": min(ts) * 1e3,
-               "ms_per_step_all": [t * 1e3 for t in ts], "io_GBps_each_way": each_way / min(ts) / 1e9,
-               "params_per_s": wl.total / min(ts)}
+               "ms_per_step_all": [t * 1e3 for t in ts], "io_bytes_each_way_per_step": per_step,
+               "io_GBps_each_way": per_step / min(ts) / 1e9, "params_per_s": wl.total / min(ts)}
         if name == "unbuffered":
             # Alg. 2: products (stand-in for forward/backward) sized to one update, then the update;
             # against the update running on the library's updater thread beside the products

@@ -440,11 +440,18 @@ int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev, int64_t b
                       int n_slots, int io_threads);
 int apm_tiered_destroy(apm_tiered* t); /* before the pools it uses */
 
+/* Measurement aid: bytes queued for reading from / writing to the files since creation (host
+ * pointers, nullable). */
+int apm_tiered_io_bytes(apm_tiered* t, int64_t* bytes_read, int64_t* bytes_written);
+
 /*
  * One AdamW step over all pages in use.  The kernels start after everything enqueued on `stream`
  * so far; the call blocks the calling thread until the last page has been written back (so,
  * unlike the other step calls, it is synchronous).  grad_norm / skip_mask as in
  * apm_page_adamw_step.  Results are bit-identical to the resident update.
+ * With APM_SKIP_UNTOUCHED, the pages that are skipped (decided by one reduce pass over all
+ * gradients, which live in HBM) are neither read from nor written to the files: I/O is
+ * proportional to the pages that receive a gradient (the experts a step routed tokens to).
  * Errors: as apm_page_adamw_step, and APM_EDEVICE if a read or write fails (the step still drains;
  * the files may then hold a partly updated state).
  */

@@ -134,9 +134,19 @@ class WindowChain {
     // through the chain so that it drains.  Returns 0, an errno value of the first failed I/O, or
     // -1 if process returned false.  Everything queued has completed when this returns.
     int run(int64_t n_pages, const std::function<bool(int64_t, int, int64_t, int64_t)>& process) {
+        return run_list(nullptr, n_pages, process);
+    }
+
+    // The same for the pages pages[0 .. n_pages) only (ascending page indices; nullptr = pages
+    // [0, n_pages)): batch b holds list positions [b*B, b*B + nb), position b*B + j sitting in page
+    // j of the slot; process gets the first list position of the batch.  Pages that are not listed
+    // are neither read nor written.  `pages` must stay valid until the call returns.
+    int run_list(const int64_t* pages, int64_t n_pages,
+                 const std::function<bool(int64_t, int, int64_t, int64_t)>& process) {
         int64_t nbatches;
         {
             std::lock_guard<std::mutex> g(m_);
+            list_ = pages;
             n_pages_ = n_pages;
             nbatches = n_batches_ = (n_pages + B_ - 1) / B_;
             batches_written_ = 0;
@@ -183,23 +193,35 @@ class WindowChain {
         const int slot = (int)(b % n_slots_);
         const int64_t first = b * B_;
         int64_t n_pages;
+        const int64_t* list;
         {
             std::lock_guard<std::mutex> g(m_);
             n_pages = n_pages_;
+            list = list_;
         }
         const int64_t nb = n_pages - first < B_ ? n_pages - first : B_;
-        const size_t bytes = pb_ * (size_t)nb;
-        const int pieces_per_class = (int)((bytes + kIoPiece - 1) / kIoPiece);
+        // pieces: runs of consecutive file pages, cut at kIoPiece bytes
+        struct Piece { size_t win_off; off_t file_off; size_t len; };
+        std::vector<Piece> pieces;
+        for (int64_t j = 0; j < nb;) {
+            const int64_t p0 = list ? list[first + j] : first + j;
+            int64_t n = 1;
+            while (j + n < nb && (list ? list[first + j + n] : first + j + n) == p0 + n) ++n;
+            const size_t bytes = pb_ * (size_t)n;
+            for (size_t o = 0; o < bytes; o += kIoPiece)
+                pieces.push_back({(size_t)j * pb_ + o, (off_t)((size_t)p0 * pb_ + o), bytes - o < kIoPiece ? bytes - o : kIoPiece});
+            j += n;
+        }
         {
             std::lock_guard<std::mutex> g(m_);
-            pending_[(size_t)slot] = 3 * pieces_per_class;
+            pending_[(size_t)slot] = 3 * (int)pieces.size();
+            (write ? bytes_written_ : bytes_read_) += 3 * (int64_t)(pb_ * (size_t)nb);
         }
         for (int c = 0; c < 3; ++c) {
-            for (int k = 0; k < pieces_per_class; ++k) {
-                const size_t o = (size_t)k * kIoPiece;
-                const size_t len = bytes - o < kIoPiece ? bytes - o : kIoPiece;
-                char* buf = slot_base(c, slot) + o;
-                const off_t off = (off_t)((size_t)first * pb_ + o);
+            for (const Piece& pc : pieces) {
+                char* buf = slot_base(c, slot) + pc.win_off;
+                const off_t off = pc.file_off;
+                const size_t len = pc.len;
                 const int fd = fd_[c];
                 pool_->submit([this, b, slot, write, fd, buf, len, off] {
                     const int err = io_piece(fd, buf, len, off, write, direct_);
@@ -225,6 +247,15 @@ class WindowChain {
         }
     }
 
+ public:
+    // Bytes queued for reading / writing since construction (all three classes).
+    void io_bytes(int64_t* read, int64_t* written) {
+        std::lock_guard<std::mutex> g(m_);
+        if (read) *read = bytes_read_;
+        if (written) *written = bytes_written_;
+    }
+
+ private:
     IoPool* pool_;
     int fd_[3];
     char* win_[3];
@@ -239,6 +270,8 @@ class WindowChain {
     int64_t batches_written_ = 0;
     int io_errno_ = 0;
     int64_t n_batches_ = 0, n_pages_ = 0;
+    const int64_t* list_ = nullptr;  // the listed pages of the running pass, nullptr = all
+    int64_t bytes_read_ = 0, bytes_written_ = 0;
 };
 
 }  // namespace io

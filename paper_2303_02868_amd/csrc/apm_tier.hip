@@ -33,6 +33,8 @@ struct apm_tiered {
     std::vector<hipEvent_t> ev_done;  // per slot
     IoPool* io = nullptr;
     WindowChain* chain = nullptr;  // the batches' way through the window (apm_io.h)
+    uint8_t* d_skip = nullptr;     // per page: skipped? (device; used when the caller passes no mask)
+    uint8_t* h_skip = nullptr;     // the same on the host (pinned)
 
     // one-step-stale form
     std::thread updater;
@@ -50,6 +52,8 @@ void free_tiered(apm_tiered* t) {
     delete t->chain;
     (void)hipDeviceSynchronize();
     for (char* p : t->win) if (p) (void)hipHostFree(p);
+    if (t->d_skip) (void)hipFree(t->d_skip);
+    if (t->h_skip) (void)hipHostFree(t->h_skip);
     for (hipEvent_t e : t->ev_done) if (e) (void)hipEventDestroy(e);
     if (t->ev_start) (void)hipEventDestroy(t->ev_start);
     if (t->s_cmp) (void)hipStreamDestroy(t->s_cmp);
@@ -87,25 +91,57 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
         L.partials = dev->d_partials;
         L.nzflags = dev->d_nzflags;
     }
+    // With skipping on, a page without gradient needs no I/O at all: one reduce pass over every page
+    // (the gradients are in HBM: 2 B per element) decides which pages are skipped -- and writes the
+    // caller's per-page outputs -- and only the other pages pass through the window.
+    std::vector<int64_t> active;
+    const bool sparse = L.skip_mode == APM_SKIP_UNTOUCHED && N > 0;
+    if (sparse) {
+        AdamwLaunch A = L;
+        A.state_first = A.grad_first = 0;
+        A.n_listed = N;
+        A.grad_norm = grad_norm;
+        A.skip_mask = skip_mask ? skip_mask : t->d_skip;
+        APM_HIP(launch_grad_reduce(A, t->s_cmp));
+        APM_HIP(hipMemcpyAsync(t->h_skip, A.skip_mask, (size_t)N, hipMemcpyDefault, t->s_cmp));
+        APM_HIP(hipStreamSynchronize(t->s_cmp));
+        for (int64_t p = 0; p < N; ++p)
+            if (!t->h_skip[p]) active.push_back(p);
+    }
     // Kernels are skipped after a failure, but every batch still passes through the chain so that
     // the step drains.
     hipError_t gpu_err = hipSuccess;
-    const int io_err = t->chain->run(N, [&](int64_t, int slot, int64_t first, int64_t nb) {
+    int ring_rc = APM_OK;
+    const auto process = [&](int64_t, int slot, int64_t first, int64_t nb) {
         AdamwLaunch C = L;
         C.state_first = (int64_t)slot * t->B;
-        C.grad_first = first;
         C.n_listed = nb;
-        C.grad_norm = grad_norm ? grad_norm + first : nullptr;
-        C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+        int ring_slot = -1;
+        if (sparse) {  // list positions [first, first + nb) of the active pages; outputs are written already
+            ring_rc = dev->ring.acquire((size_t)nb * sizeof(int64_t), &ring_slot);
+            if (ring_rc != APM_OK) return false;
+            int64_t* h = static_cast<int64_t*>(dev->ring.h[ring_slot]);
+            for (int64_t k = 0; k < nb; ++k) h[k] = active[(size_t)(first + k)];
+            ring_rc = dev->ring.commit(ring_slot, (size_t)nb * sizeof(int64_t), t->s_cmp);
+            if (ring_rc != APM_OK) return false;
+            C.grad_pages = static_cast<const int64_t*>(dev->ring.d[ring_slot]);
+        } else {
+            C.grad_first = first;
+            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+        }
         gpu_err = need_reduce ? launch_grad_reduce(C, t->s_cmp) : launch_prepare(C, t->s_cmp);
         if (gpu_err == hipSuccess) gpu_err = launch_adamw(C, t->s_cmp);
         if (gpu_err == hipSuccess) gpu_err = hipEventRecord(t->ev_done[(size_t)slot], t->s_cmp);
         if (gpu_err == hipSuccess) gpu_err = hipEventSynchronize(t->ev_done[(size_t)slot]);
-        return gpu_err == hipSuccess;
-    });
+        if (ring_slot >= 0 && gpu_err == hipSuccess) ring_rc = dev->ring.seal(ring_slot, t->s_cmp);
+        return gpu_err == hipSuccess && ring_rc == APM_OK;
+    };
+    const int io_err = sparse ? t->chain->run_list(active.data(), (int64_t)active.size(), process)
+                              : t->chain->run(N, process);
     if (io_err > 0) return fail(APM_EDEVICE, "file I/O failed during the step: %s (the files may hold a partly updated state)", strerror(io_err));
     if (gpu_err != hipSuccess) return fail(APM_EDEVICE, "a kernel launch of the step failed: %s", hipGetErrorString(gpu_err));
-    return APM_OK;
+    return ring_rc;
 }
 
 int join_updater(apm_tiered* t) {
@@ -212,6 +248,13 @@ extern "C" int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev
         free_tiered(t);
         return fail(APM_EDEVICE, "creating the stream / events failed: %s", hipGetErrorString(e));
     }
+    e = hipMalloc((void**)&t->d_skip, (size_t)dev->desc.n_pages);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&t->h_skip, (size_t)dev->desc.n_pages, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        free_tiered(t);
+        return fail(APM_ENOMEM, "allocating the per-page skip flags failed: %s", hipGetErrorString(e));
+    }
     int rc = ensure_scratch(dev);
     if (rc != APM_OK) { free_tiered(t); return rc; }
     t->io = new IoPool(io_threads);
@@ -226,6 +269,12 @@ extern "C" int apm_tiered_destroy(apm_tiered* t) {
     if (!t) return APM_OK;
     (void)hipSetDevice(t->dev->desc.hip_device);
     free_tiered(t);
+    return APM_OK;
+}
+
+extern "C" int apm_tiered_io_bytes(apm_tiered* t, int64_t* bytes_read, int64_t* bytes_written) {
+    if (!t) return fail(APM_EINVAL, "NULL handle");
+    t->chain->io_bytes(bytes_read, bytes_written);
     return APM_OK;
 }
 

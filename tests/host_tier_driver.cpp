@@ -92,6 +92,51 @@ void case_roundtrip(const std::string& dir, const char* tag, int64_t n_pages, in
         }
 }
 
+// Only some pages pass through the window (the pages of a step that received a gradient): the
+// listed pages change, the others keep their bits, and only the listed ones are read and written.
+void case_list(const std::string& dir) {
+    const int64_t n_pages = 50, page_floats = 2048, B = 4;
+    const int n_slots = 3;
+    Files f;
+    make_files(f, dir, "list", n_pages, page_floats, 0);
+    const size_t pb = (size_t)page_floats * sizeof(float);
+    std::vector<std::vector<char>> win(3, std::vector<char>((size_t)n_slots * (size_t)B * pb));
+    char* w[3] = {win[0].data(), win[1].data(), win[2].data()};
+    const std::vector<int64_t> pages = {0, 1, 2, 7, 9, 10, 11, 12, 13, 20, 33, 34, 48, 49};  // runs and singles
+    IoPool pool(4);
+    WindowChain chain(&pool, f.fd, w, pb, B, n_slots, false);
+    int64_t seen = 0;
+    const int rc = chain.run_list(pages.data(), (int64_t)pages.size(), [&](int64_t b, int slot, int64_t first, int64_t nb) {
+        if (first != b * B) die("list batch geometry", b, first);
+        for (int c = 0; c < 3; ++c) {
+            float* x = reinterpret_cast<float*>(chain.slot_base(c, slot));
+            for (int64_t j = 0; j < nb; ++j) {
+                const int64_t p = pages[(size_t)(first + j)];
+                for (int64_t e = 0; e < page_floats; ++e) {
+                    if (x[j * page_floats + e] != initial(c, p, e)) die("window holds the wrong page", p, e);
+                    x[j * page_floats + e] = -(float)(p + 1);
+                }
+            }
+        }
+        seen += nb;
+        return true;
+    });
+    if (rc != 0 || seen != (int64_t)pages.size()) die("list run", rc, seen);
+    int64_t rd = 0, wr = 0;
+    chain.io_bytes(&rd, &wr);
+    if (rd != 3 * (int64_t)pages.size() * (int64_t)pb || wr != rd) die("bytes moved for a list", rd, wr);
+    std::vector<float> page((size_t)page_floats);
+    for (int c = 0; c < 3; ++c)
+        for (int64_t p = 0; p < n_pages; ++p) {
+            if (apm::io::io_full(f.fd[c], reinterpret_cast<char*>(page.data()), pb, (off_t)((size_t)p * pb), false) != 0) die("read back");
+            bool listed = false;
+            for (int64_t q : pages) listed = listed || q == p;
+            for (int64_t e = 0; e < page_floats; ++e)
+                if (page[(size_t)e] != (listed ? -(float)(p + 1) : initial(c, p, e))) die("page after a list run", p, e);
+        }
+    if (chain.run_list(pages.data(), 0, [&](int64_t, int, int64_t, int64_t) { return true; }) != 0) die("empty list");
+}
+
 // A file that is shorter than the pool: reads beyond its end fail; the run must report the error,
 // process nothing after it, and return with nothing in flight.
 void case_short_file(const std::string& dir) {
@@ -152,6 +197,7 @@ int main(int argc, char** argv) {
     case_roundtrip(dir, "c", 64, 256, 1, 4, 2, false, 2);        // one page per batch
     case_roundtrip(dir, "d", 5, 3 << 20, 2, 2, 4, false, 1);     // batches of several I/O pieces
     case_roundtrip(dir, "e", 24, 2048, 4, 2, 4, true, 2);        // unbuffered, through the bounce buffers
+    case_list(dir);
     case_short_file(dir);
     case_refusal(dir);
     std::printf("ok\n");

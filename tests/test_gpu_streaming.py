@@ -502,6 +502,79 @@ def test_file_tier_step_equals_resident_bit_exact(tmp_path, batch, slots, thread
     res.destroy()
 
 
+@pytest.mark.parametrize("with_mask,stale", [(True, False), (False, False), (False, True)])
+def test_file_tier_moves_only_the_pages_that_received_a_gradient(tmp_path, with_mask, stale):
+    # MoE-like: per step a few "experts" have a gradient; with APM_SKIP_UNTOUCHED the other pages are
+    # neither read nor written, and the files still end bit-identical to the resident update
+    E = 16384
+    specs = [synth.TensorSpec(0, "dense", 2 * E + 100)]
+    for x in range(10):
+        specs += [synth.TensorSpec(1 + 2 * x, f"w1_{x}", 3 * E), synth.TensorSpec(2 + 2 * x, f"b_{x}", 64)]
+    rng = np.random.default_rng(5)
+    draws = {t: rng.permutation(10)[:3] for t in range(1, 6)}
+
+    def active(step):
+        a = np.zeros(len(specs), dtype=bool)
+        a[0] = True
+        for x in draws[step]:
+            a[1 + 2 * x] = a[2 + 2 * x] = True
+        return a
+
+    model = Model(specs, E, seed=12, active_fn=active)
+    n_pages, n_t = model.plan.n_pages, len(specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=0.05, skip_mode=1))
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    prefix = str(tmp_path / "state")
+    filep = apm.apm_file_pool_create(prefix, E, n_pages)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    apm.apm_page_copy_async(filep, 0, host, 0, n_pages, apm.APM_P32)
+    tier = apm.apm_tiered_create(filep, dev.pool, 4, 3, 4)
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    skip_r = torch.zeros(n_pages, dtype=torch.uint8, device=DEV)
+    norm_s = torch.full((n_pages,), -1.0, dtype=torch.float32, device=DEV)
+    skip_s = torch.full((n_pages,), 9, dtype=torch.uint8, device=DEV) if with_mask else None
+    produce = DevicePool(n_pages, E, states=(apm.APM_G16,))
+    apm.apm_pool_set_layout(produce.pool, model.tensors(model.p_flat), n_t)
+    if stale:
+        apm.apm_delayed_set_outputs(dev.pool, norm_s, skip_s)
+    moved_pages = 0
+    for t in range(1, 6):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, skip_r)
+        if stale:
+            apm.apm_pack_tensors(produce.pool, apm.APM_G16, model.tensors(g), n_t)
+            apm.apm_tiered_step_delayed(tier, produce.reg[apm.APM_G16], hy)
+        else:
+            apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+            apm.apm_tiered_step(tier, t, hy, norm_s, skip_s)
+        torch.cuda.synchronize()
+        n_active = int((skip_r == 0).sum())
+        assert 0 < n_active < n_pages
+        moved_pages += n_active
+        if not stale:
+            assert torch.equal(norm_r, norm_s)
+            if with_mask:
+                assert torch.equal(skip_r, skip_s)
+    if stale:
+        apm.apm_tiered_step_delayed(tier, None, hy)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s)
+    rd, wr = apm.apm_tiered_io_bytes(tier)
+    assert rd == wr == moved_pages * 12 * E, (rd, wr, moved_pages)
+    tier.destroy()
+    filep.destroy()
+    for s_, suffix in ((apm.APM_P32, ".p32"), (apm.APM_M32, ".m32"), (apm.APM_V32, ".v32")):
+        assert np.array_equal(file_rows(prefix, suffix, n_pages, E), res.reg[s_].cpu().numpy().view(np.uint32)), suffix
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    for x in (produce, host, dev, res):
+        x.destroy()
+
+
 def test_file_tier_delayed_calls_plus_flush_equal_synchronous_steps(tmp_path):
     # Alg. 2 with its two actors as host threads: the updater thread works through the files while
     # the caller hands over the next gradient
