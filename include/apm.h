@@ -467,7 +467,8 @@ int apm_tiered_step(apm_tiered* t, int64_t step, const apm_hyper* hyper, float* 
  * gradient while the updater fetches, updates and offloads the states.  new_g16 == NULL flushes:
  * the buffered gradient is applied and the call returns when that update is complete.
  * N calls + flush leave exactly the state of N apm_tiered_step calls.  While an update runs, the
- * GPU pool's per-page scratch is in use: no other step call on that pool.  The applied counter
+ * GPU pool's per-page scratch is in use: no other step call on that pool (apm_delayed_accumulate
+ * into the gradient being collected is fine: Alg. 2's buffering actor).  The applied counter
  * and apm_delayed_set_outputs are those of the GPU pool; apm_delayed_grad_buffer is not available
  * here (APM_EINVAL).  An error of the background update is reported by the next call.
  */

@@ -35,6 +35,8 @@ struct apm_tiered {
     WindowChain* chain = nullptr;  // the batches' way through the window (apm_io.h)
     uint8_t* d_skip = nullptr;     // per page: skipped? (device; used when the caller passes no mask)
     uint8_t* h_skip = nullptr;     // the same on the host (pinned)
+    StageRing ring;                // page lists of the batches; the handle's own, because the step may
+                                   // run on the updater thread while the caller uses the GPU pool's
 
     // one-step-stale form
     std::thread updater;
@@ -52,6 +54,7 @@ void free_tiered(apm_tiered* t) {
     delete t->chain;
     (void)hipDeviceSynchronize();
     for (char* p : t->win) if (p) (void)hipHostFree(p);
+    t->ring.destroy();
     if (t->d_skip) (void)hipFree(t->d_skip);
     if (t->h_skip) (void)hipHostFree(t->h_skip);
     for (hipEvent_t e : t->ev_done) if (e) (void)hipEventDestroy(e);
@@ -118,13 +121,13 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
         C.n_listed = nb;
         int ring_slot = -1;
         if (sparse) {  // list positions [first, first + nb) of the active pages; outputs are written already
-            ring_rc = dev->ring.acquire((size_t)nb * sizeof(int64_t), &ring_slot);
+            ring_rc = t->ring.acquire((size_t)nb * sizeof(int64_t), &ring_slot);
             if (ring_rc != APM_OK) return false;
-            int64_t* h = static_cast<int64_t*>(dev->ring.h[ring_slot]);
+            int64_t* h = static_cast<int64_t*>(t->ring.h[ring_slot]);
             for (int64_t k = 0; k < nb; ++k) h[k] = active[(size_t)(first + k)];
-            ring_rc = dev->ring.commit(ring_slot, (size_t)nb * sizeof(int64_t), t->s_cmp);
+            ring_rc = t->ring.commit(ring_slot, (size_t)nb * sizeof(int64_t), t->s_cmp);
             if (ring_rc != APM_OK) return false;
-            C.grad_pages = static_cast<const int64_t*>(dev->ring.d[ring_slot]);
+            C.grad_pages = static_cast<const int64_t*>(t->ring.d[ring_slot]);
         } else {
             C.grad_first = first;
             C.grad_norm = grad_norm ? grad_norm + first : nullptr;
@@ -134,7 +137,7 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
         if (gpu_err == hipSuccess) gpu_err = launch_adamw(C, t->s_cmp);
         if (gpu_err == hipSuccess) gpu_err = hipEventRecord(t->ev_done[(size_t)slot], t->s_cmp);
         if (gpu_err == hipSuccess) gpu_err = hipEventSynchronize(t->ev_done[(size_t)slot]);
-        if (ring_slot >= 0 && gpu_err == hipSuccess) ring_rc = dev->ring.seal(ring_slot, t->s_cmp);
+        if (ring_slot >= 0 && gpu_err == hipSuccess) ring_rc = t->ring.seal(ring_slot, t->s_cmp);
         return gpu_err == hipSuccess && ring_rc == APM_OK;
     };
     const int io_err = sparse ? t->chain->run_list(active.data(), (int64_t)active.size(), process)

@@ -784,3 +784,61 @@ def test_calls_on_a_side_stream_are_ordered_by_that_stream(form):
     for k, (a, b) in enumerate(zip(want, got)):
         assert np.array_equal(a, b), f"output {k} differs between the default stream and a side stream"
     assert want[0].any() and want[3].any()
+
+
+@pytest.mark.parametrize("where", ["host", "file"])
+def test_accumulated_gradients_with_the_state_off_the_gpu(tmp_path, where):
+    # Alg. 2 in full: the buffering side sums several micro-gradients while the updating side works
+    # on states that live in pinned host memory or in files; equal to synchronous resident steps
+    # on the pre-summed gradients (bf16 sums: fp32 add, nearest even)
+    E = 16384
+    numels = [3 * E + 5, 100, 2 * E, 9000, E, 5 * E + 77]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=13, sigma_g=5e-3)
+    n, n_t = model.plan.n_pages, len(specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=0.5))
+    res = DevicePool(n, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n, state_mask=apm.FP32_STATES)
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n, apm.APM_P32)
+    torch.cuda.synchronize()
+    filep = tier = st = None
+    if where == "file":
+        prefix = str(tmp_path / "state")
+        filep = apm.apm_file_pool_create(prefix, E, n)
+        apm.apm_page_copy_async(filep, 0, host, 0, n, apm.APM_P32)
+        tier = apm.apm_tiered_create(filep, dev.pool, 3, 2, 3)
+        hand_over = lambda g: apm.apm_tiered_step_delayed(tier, g, hy)
+    else:
+        st = apm.apm_streamer_create(host, dev.pool, 4, 2)
+        hand_over = lambda g: apm.apm_streamer_step_delayed(st, g, hy)
+    stage = DevicePool(n, E, states=(apm.APM_G16,))
+    apm.apm_pool_set_layout(stage.pool, model.tensors(model.p_flat), n_t)
+    for t in range(1, 4):
+        gs = [model.grad_flat(10 * t + k) for k in range(3)]
+        total = (gs[0] + gs[1]) + gs[2]
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(total), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n, t, hy)
+        apm.apm_pack_tensors(stage.pool, apm.APM_G16, model.tensors(gs[0]), n_t)
+        hand_over(stage.reg[apm.APM_G16])
+        for k in (1, 2):
+            apm.apm_pack_tensors(stage.pool, apm.APM_G16, model.tensors(gs[k]), n_t)
+            apm.apm_delayed_accumulate(dev.pool, None, n, stage.reg[apm.APM_G16])
+        torch.cuda.synchronize()
+    hand_over(None)
+    torch.cuda.synchronize()
+    assert apm.apm_delayed_applied(dev.pool) == 3
+    if where == "file":
+        tier.destroy()
+        filep.destroy()
+        got = [file_rows(prefix, suffix, n, E) for suffix in (".p32", ".m32", ".v32")]
+    else:
+        st.destroy()
+        got = [host_view(host, c, n, E).view(np.uint32) for c in (apm.APM_P32, apm.APM_M32, apm.APM_V32)]
+    for c, g in zip((apm.APM_P32, apm.APM_M32, apm.APM_V32), got):
+        assert np.array_equal(g, res.reg[c].cpu().numpy().view(np.uint32)), f"state {c}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    for x in (stage, host, dev, res):
+        x.destroy()
