@@ -341,6 +341,10 @@ int apm_cache_pages_that_fit(int hip_device, int64_t page_elems, int64_t n_pages
  */
 int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page);
 
+/* Restricts the step calls of `s` to model pages [0, n_pages) (n_pages < 0: all pages in use); the
+ * pages beyond are some other handle's (apm_tiered_set_range).  Not with the scheduled step. */
+int apm_streamer_set_page_count(apm_streamer* s, int64_t n_pages);
+
 /*
  * Measurement aid (staged mode only): the same pipeline (streams, events, copy sizes, slot reuse)
  * with the kernels left out.  directions: 1 = copy-in only, 2 = copy-out only, 3 = both.  The data make a round
@@ -439,6 +443,16 @@ int apm_file_pool_create(apm_pool** out, const char* path_prefix, int32_t hip_de
 int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev, int64_t batch_pages,
                       int n_slots, int io_threads);
 int apm_tiered_destroy(apm_tiered* t); /* before the pools it uses */
+
+/*
+ * Restricts the step calls of `t` to model pages [first_page, first_page + n_pages) (n_pages < 0:
+ * to the last page in use); file page k is model page k as before.  With
+ * apm_streamer_set_page_count this composes the paper's three levels on one GPU pool (Sec. 4.2,
+ * Sec. 4.3): the leading pages cached in HBM, the next in pinned host memory (both one
+ * apm_streamer_step), the rest in files (one apm_tiered_step).  Per-page outputs stay indexed by
+ * model page.  Only one of the handles on a GPU pool may drive the one-step-stale form.
+ */
+int apm_tiered_set_range(apm_tiered* t, int64_t first_page, int64_t n_pages);
 
 /* Measurement aid: bytes queued for reading from / writing to the files since creation (host
  * pointers, nullable). */

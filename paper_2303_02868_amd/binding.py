@@ -31,7 +31,7 @@ EXPORTS = [
     "apm_pool_pages_in_use", "apm_pool_page_info", "apm_pool_state_ptr", "apm_pool_set_layout",
     "apm_pack_tensors", "apm_unpack", "apm_page_adamw_step", "apm_page_adamw_step_fused",
     "apm_page_copy_async",
-    "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_io_bytes", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_cache_pages_that_fit", "apm_streamer_set_host_first_page", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
+    "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_io_bytes", "apm_tiered_set_range", "apm_streamer_set_page_count", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_cache_pages_that_fit", "apm_streamer_set_host_first_page", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
 ]
 
@@ -120,6 +120,8 @@ def lib() -> C.CDLL:
     L.apm_tiered_destroy.argtypes = [vp]
     L.apm_tiered_step.argtypes = [vp, i64, P(apm_hyper), vp, vp, vp]
     L.apm_tiered_io_bytes.argtypes = [vp, P(i64), P(i64)]
+    L.apm_tiered_set_range.argtypes = [vp, i64, i64]
+    L.apm_streamer_set_page_count.argtypes = [vp, i64]
     L.apm_tiered_step_delayed.argtypes = [vp, vp, P(apm_hyper), vp]
     L.apm_streamer_create.argtypes = [P(vp), vp, vp, i64, i32]
     L.apm_streamer_destroy.argtypes = [vp]
@@ -350,6 +352,14 @@ def apm_tiered_create(file: Pool, dev: Pool, batch_pages: int, n_slots: int, io_
 
 def apm_tiered_destroy(t: Tiered) -> None:
     t.destroy()
+
+
+def apm_tiered_set_range(t: Tiered, first_page: int, n_pages: int = -1) -> None:
+    _check(lib().apm_tiered_set_range(t.handle, first_page, n_pages))
+
+
+def apm_streamer_set_page_count(s: "Streamer", n_pages: int) -> None:
+    _check(lib().apm_streamer_set_page_count(s.handle, n_pages))
 
 
 def apm_tiered_io_bytes(t: Tiered):

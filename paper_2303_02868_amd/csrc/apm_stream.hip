@@ -30,6 +30,7 @@ struct apm_streamer {
     apm_pool* cache = nullptr;  // optional GPU pool holding the fp32 classes of pages [0, R)
     int64_t R = 0;              // number of leading pages whose fp32 state is HBM-resident
     int64_t host_first = 0;     // model page held by page 0 of the host pool
+    int64_t page_limit = -1;    // the step covers model pages [0, page_limit); -1 = all pages in use
     int64_t B = 0;
     int n_slots = 0;
     float* stage[3] = {nullptr, nullptr, nullptr};  // each n_slots * B * E floats
@@ -248,7 +249,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     if (rc != APM_OK) return rc;
     APM_HIP(hipSetDevice(dev->desc.hip_device));
     hipStream_t caller = static_cast<hipStream_t>(stream);
-    const int64_t N = (int64_t)dev->plan.pages.size();
+    const int64_t in_use = (int64_t)dev->plan.pages.size();
+    const int64_t N = s->page_limit >= 0 && s->page_limit < in_use ? s->page_limit : in_use;
     const int64_t E = dev->desc.page_elems;
     const size_t pb = (size_t)E * sizeof(float);
 
@@ -503,6 +505,12 @@ extern "C" int apm_cache_pages_that_fit(int hip_device, int64_t page_elems, int6
     return APM_OK;
 }
 
+extern "C" int apm_streamer_set_page_count(apm_streamer* s, int64_t n_pages) {
+    if (!s) return fail(APM_EINVAL, "NULL streamer");
+    s->page_limit = n_pages < 0 ? -1 : n_pages;
+    return APM_OK;
+}
+
 extern "C" int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page) {
     if (!s) return fail(APM_EINVAL, "NULL streamer");
     if (first_model_page < 0 || first_model_page > s->dev->desc.n_pages) return fail(APM_ERANGE, "first_model_page out of range");
@@ -529,7 +537,7 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
     if (layer_first_page[0] != 0 || layer_first_page[n_layers] != N) return fail(APM_EINVAL, "the layers must cover pages [0, %lld) in order", (long long)N);
     for (int64_t i = 0; i < n_layers; ++i)
         if (layer_first_page[i + 1] < layer_first_page[i]) return fail(APM_EINVAL, "layer_first_page must not decrease");
-    if (s->cache || s->host_first != 0) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache");
+    if (s->cache || s->host_first != 0 || s->page_limit >= 0) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache or a page range");
     if (s->host->desc.n_pages < N) return fail(APM_ESTATE, "the host pool holds fewer pages than are in use");
     AdamwLaunch L{};
     int rc = prepare_hyper(hyper, step, &L);

@@ -35,6 +35,8 @@ struct apm_tiered {
     WindowChain* chain = nullptr;  // the batches' way through the window (apm_io.h)
     uint8_t* d_skip = nullptr;     // per page: skipped? (device; used when the caller passes no mask)
     uint8_t* h_skip = nullptr;     // the same on the host (pinned)
+    int64_t first_page = 0;        // the step covers model pages [first_page, first_page + page_count)
+    int64_t page_count = -1;       // -1 = to the last page in use
     StageRing ring;                // page lists of the batches; the handle's own, because the step may
                                    // run on the updater thread while the caller uses the GPU pool's
 
@@ -72,7 +74,9 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
     int rc = prepare_hyper(hyper, step, &L);
     if (rc != APM_OK) return rc;
     APM_HIP(hipSetDevice(dev->desc.hip_device));
-    const int64_t N = (int64_t)dev->plan.pages.size();
+    const int64_t in_use = (int64_t)dev->plan.pages.size();
+    const int64_t P0 = t->first_page < in_use ? t->first_page : in_use;  // first model page of the step
+    const int64_t N = t->page_count < 0 || t->page_count > in_use - P0 ? in_use - P0 : t->page_count;
     const int64_t E = dev->desc.page_elems;
     if (have_caller) {
         APM_HIP(hipEventRecord(t->ev_start, caller));
@@ -101,16 +105,20 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
     const bool sparse = L.skip_mode == APM_SKIP_UNTOUCHED && N > 0;
     if (sparse) {
         AdamwLaunch A = L;
-        A.state_first = A.grad_first = 0;
+        A.state_first = A.grad_first = P0;
         A.n_listed = N;
-        A.grad_norm = grad_norm;
-        A.skip_mask = skip_mask ? skip_mask : t->d_skip;
+        A.grad_norm = grad_norm ? grad_norm + P0 : nullptr;
+        A.skip_mask = skip_mask ? skip_mask + P0 : t->d_skip;
         APM_HIP(launch_grad_reduce(A, t->s_cmp));
         APM_HIP(hipMemcpyAsync(t->h_skip, A.skip_mask, (size_t)N, hipMemcpyDefault, t->s_cmp));
         APM_HIP(hipStreamSynchronize(t->s_cmp));
         for (int64_t p = 0; p < N; ++p)
-            if (!t->h_skip[p]) active.push_back(p);
+            if (!t->h_skip[p]) active.push_back(P0 + p);
+    } else if (P0 > 0) {  // a range that does not start at page 0 goes through the list form as well
+        active.resize((size_t)N);
+        for (int64_t p = 0; p < N; ++p) active[(size_t)p] = P0 + p;
     }
+    const bool listed = sparse || P0 > 0;
     // Kernels are skipped after a failure, but every batch still passes through the chain so that
     // the step drains.
     hipError_t gpu_err = hipSuccess;
@@ -128,10 +136,10 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
             ring_rc = t->ring.commit(ring_slot, (size_t)nb * sizeof(int64_t), t->s_cmp);
             if (ring_rc != APM_OK) return false;
             C.grad_pages = static_cast<const int64_t*>(t->ring.d[ring_slot]);
-        } else {
-            C.grad_first = first;
-            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
-            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+        } else {  // consecutive model pages from P0 + first on
+            C.grad_first = P0 + first;
+            C.grad_norm = grad_norm ? grad_norm + P0 + first : nullptr;
+            C.skip_mask = skip_mask ? skip_mask + P0 + first : nullptr;
         }
         gpu_err = need_reduce ? launch_grad_reduce(C, t->s_cmp) : launch_prepare(C, t->s_cmp);
         if (gpu_err == hipSuccess) gpu_err = launch_adamw(C, t->s_cmp);
@@ -140,7 +148,7 @@ int tiered_run(apm_tiered* t, int64_t step, const apm_hyper* hyper, const uint16
         if (ring_slot >= 0 && gpu_err == hipSuccess) ring_rc = t->ring.seal(ring_slot, t->s_cmp);
         return gpu_err == hipSuccess && ring_rc == APM_OK;
     };
-    const int io_err = sparse ? t->chain->run_list(active.data(), (int64_t)active.size(), process)
+    const int io_err = listed ? t->chain->run_list(active.data(), (int64_t)active.size(), process)
                               : t->chain->run(N, process);
     if (io_err > 0) return fail(APM_EDEVICE, "file I/O failed during the step: %s (the files may hold a partly updated state)", strerror(io_err));
     if (gpu_err != hipSuccess) return fail(APM_EDEVICE, "a kernel launch of the step failed: %s", hipGetErrorString(gpu_err));
@@ -272,6 +280,16 @@ extern "C" int apm_tiered_destroy(apm_tiered* t) {
     if (!t) return APM_OK;
     (void)hipSetDevice(t->dev->desc.hip_device);
     free_tiered(t);
+    return APM_OK;
+}
+
+extern "C" int apm_tiered_set_range(apm_tiered* t, int64_t first_page, int64_t n_pages) {
+    if (!t) return fail(APM_EINVAL, "NULL handle");
+    if (first_page < 0 || first_page > t->dev->desc.n_pages) return fail(APM_ERANGE, "first_page out of range");
+    int rc = join_updater(t);
+    if (rc != APM_OK) return rc;
+    t->first_page = first_page;
+    t->page_count = n_pages < 0 ? -1 : n_pages;
     return APM_OK;
 }
 

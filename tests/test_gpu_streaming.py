@@ -842,3 +842,65 @@ def test_accumulated_gradients_with_the_state_off_the_gpu(tmp_path, where):
     assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
     for x in (stage, host, dev, res):
         x.destroy()
+
+
+@pytest.mark.parametrize("mode,skip", [("direct", 0), ("staged", 0), ("direct", 1)])
+def test_three_levels_hbm_cache_host_memory_and_files_in_one_step(tmp_path, mode, skip):
+    # the leading pages' fp32 state cached in HBM, the next in pinned host memory, the rest in
+    # files: a streamer step over [0, H) and a tier step over [H, N) on the same GPU pool
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    specs = f()
+    zero = {i for i, t in enumerate(specs) if skip and i % 3 == 1}
+    model = Model(specs, E, seed=14, active_fn=(lambda t: np.array([i not in zero for i in range(len(specs))])) if skip else None)
+    N, n_t = model.plan.n_pages, len(specs)
+    R, H = N // 4, (2 * N) // 3
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0, skip_mode=skip))
+    res = DevicePool(N, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(N, E, states=(apm.APM_G16, apm.APM_P16))
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    cache = DevicePool(R, E, states=(apm.APM_P32, apm.APM_M32, apm.APM_V32))
+    apm.apm_page_copy_async(cache.pool, 0, res.pool, 0, R, apm.APM_P32)
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, H - R, state_mask=apm.FP32_STATES)     # model pages [R, H)
+    apm.apm_page_copy_async(host, 0, res.pool, R, H - R, apm.APM_P32)
+    bounce = apm.apm_pool_create(apm.APM_DEV_HOST, E, N - H, state_mask=1 << apm.APM_P32)
+    apm.apm_page_copy_async(bounce, 0, res.pool, H, N - H, apm.APM_P32)
+    prefix = str(tmp_path / "state")
+    filep = apm.apm_file_pool_create(prefix, E, N)                                       # file page = model page
+    apm.apm_page_copy_async(filep, H, bounce, 0, N - H, apm.APM_P32)
+    st = apm.apm_streamer_create(host, dev.pool, 16, 3)
+    set_mode(st, mode)
+    apm.apm_streamer_set_cache(st, cache.pool, R)
+    apm.apm_streamer_set_host_first_page(st, R)
+    apm.apm_streamer_set_page_count(st, H)
+    tier = apm.apm_tiered_create(filep, dev.pool, 8, 3, 4)
+    apm.apm_tiered_set_range(tier, H)
+    norm_r = torch.zeros(N, dtype=torch.float32, device=DEV)
+    skip_r = torch.zeros(N, dtype=torch.uint8, device=DEV)
+    norm_s = torch.full((N,), -1.0, dtype=torch.float32, device=DEV)
+    skip_s = torch.full((N,), 9, dtype=torch.uint8, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, N, t, hy, norm_r, skip_r)
+        apm.apm_streamer_step(st, t, hy, norm_s, skip_s)
+        apm.apm_tiered_step(tier, t, hy, norm_s, skip_s)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s) and torch.equal(skip_r, skip_s)
+    if skip:
+        assert 0 < int(skip_r[H:].sum()) < N - H
+        rd, wr = apm.apm_tiered_io_bytes(tier)
+        assert rd == wr == 3 * int((skip_r[H:] == 0).sum()) * 12 * E
+    tier.destroy()
+    filep.destroy()
+    st.destroy()
+    for c, suffix in ((apm.APM_P32, ".p32"), (apm.APM_M32, ".m32"), (apm.APM_V32, ".v32")):
+        want = res.reg[c].cpu().numpy().view(np.uint32)
+        assert np.array_equal(cache.reg[c].cpu().numpy().view(np.uint32), want[:R]), f"cache {c}"
+        assert np.array_equal(host_view(host, c, H - R, E).view(np.uint32), want[R:H]), f"host {c}"
+        assert np.array_equal(file_rows(prefix, suffix, N, E)[H:], want[H:]), f"file {c}"
+        assert not file_rows(prefix, suffix, N, E)[:H].any(), "file pages below the range were written"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    for x in (bounce, host, cache, dev, res):
+        x.destroy()
