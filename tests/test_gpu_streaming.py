@@ -691,6 +691,11 @@ def test_streamer_and_tier_argument_errors(tmp_path):
     assert code(lambda: apm.apm_streamer_step_scheduled(st, [(apm.APM_TASK_COMPUTE, 0, 0)], [0, n], 2, hy)) == apm.APM_ESTATE
     assert code(lambda: apm.apm_streamer_step_scheduled(st, [(9, 0, 0)], [0, n], 2, hy)) == apm.APM_EINVAL
     assert code(lambda: apm.apm_streamer_step_scheduled(st, [], [0, n - 1], 2, hy)) == apm.APM_EINVAL
+    apm.apm_streamer_set_page_count(st, 3)                    # a page range: not with a schedule
+    tasks = [(apm.APM_TASK_MOVE_TO_GPU, 0, p) for p in range(n)] + [(apm.APM_TASK_COMPUTE, 0, 0)]
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, tasks, [0, n], 2, hy)) == apm.APM_ESTATE
+    apm.apm_streamer_step(st, 2, hy)                          # pages [0, 3) only
+    apm.apm_streamer_set_page_count(st, -1)
     torch.cuda.synchronize()
     st.destroy()
 
@@ -703,6 +708,15 @@ def test_streamer_and_tier_argument_errors(tmp_path):
     tier = apm.apm_tiered_create(filep, dev.pool, 4, 2, 2)
     assert code(lambda: apm.apm_tiered_step(tier, 0, hy)) == apm.APM_EINVAL
     apm.apm_tiered_step(tier, 1, hy)
+    assert code(lambda: apm.apm_tiered_set_range(tier, -1)) == apm.APM_ERANGE
+    assert code(lambda: apm.apm_tiered_set_range(tier, n + 1)) == apm.APM_ERANGE
+    rd0, wr0 = apm.apm_tiered_io_bytes(tier)
+    apm.apm_tiered_set_range(tier, n)                         # an empty range: a step that moves nothing
+    apm.apm_tiered_step(tier, 2, hy)
+    assert apm.apm_tiered_io_bytes(tier) == (rd0, wr0) == (n * 12 * E, n * 12 * E)
+    apm.apm_tiered_set_range(tier, 2, 3)
+    apm.apm_tiered_step(tier, 2, hy)
+    assert apm.apm_tiered_io_bytes(tier) == ((n + 3) * 12 * E, (n + 3) * 12 * E)
     tier.destroy()
     filep.destroy()
     host.destroy()
