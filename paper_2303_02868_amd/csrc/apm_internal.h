@@ -4,7 +4,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <exception>
 #include <functional>
+#include <new>
 #include <vector>
 
 #include "apm.h"
@@ -13,6 +15,20 @@ namespace apm {
 
 // ---- errors -------------------------------------------------------------------------------
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// Every int-returning entry point runs inside this: no C++ exception crosses the C boundary.
+template <class F>
+int guarded(F&& f) noexcept {
+    try {
+        return f();
+    } catch (const std::bad_alloc&) {
+        return fail(APM_ENOMEM, "out of host memory");
+    } catch (const std::exception& e) {
+        return fail(APM_EDEVICE, "unexpected failure: %s", e.what());
+    } catch (...) {
+        return fail(APM_EDEVICE, "unexpected failure");
+    }
+}
 
 #define APM_HIP(expr)                                                                   \
     do {                                                                                \

@@ -28,16 +28,14 @@ constexpr size_t kIoPiece = (size_t)8 << 20;  // bytes per pread / pwrite task
 class IoPool {
  public:
     explicit IoPool(int n) {
-        for (int k = 0; k < n; ++k) thr_.emplace_back([this] { run(); });
-    }
-    ~IoPool() {
-        {
-            std::lock_guard<std::mutex> g(m_);
-            stop_ = true;
+        try {
+            for (int k = 0; k < n; ++k) thr_.emplace_back([this] { run(); });
+        } catch (...) {  // a thread could not be started: end the ones that run, then report
+            stop_and_join();
+            throw;
         }
-        cv_.notify_all();
-        for (auto& t : thr_) t.join();
     }
+    ~IoPool() { stop_and_join(); }
     IoPool(const IoPool&) = delete;
     IoPool& operator=(const IoPool&) = delete;
     void submit(std::function<void()> f) {
@@ -49,6 +47,15 @@ class IoPool {
     }
 
  private:
+    void stop_and_join() {
+        {
+            std::lock_guard<std::mutex> g(m_);
+            stop_ = true;
+        }
+        cv_.notify_all();
+        for (auto& t : thr_) t.join();
+        thr_.clear();
+    }
     void run() {
         for (;;) {
             std::function<void()> f;

@@ -307,8 +307,10 @@ using namespace apm;
 extern "C" int apm_page_adamw_step(apm_pool* pool, const int64_t* pages, int64_t n_pages,
                                    int64_t step, const apm_hyper* hyper, float* grad_norm,
                                    uint8_t* skip_mask, void* stream) {
-    return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
-                        static_cast<hipStream_t>(stream));
+    return apm::guarded([&]() -> int {
+        return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
+                            static_cast<hipStream_t>(stream));
+    });
 }
 
 extern "C" int apm_page_adamw_step_fused(apm_pool* pool, const int64_t* pages, int64_t n_pages,
@@ -316,68 +318,74 @@ extern "C" int apm_page_adamw_step_fused(apm_pool* pool, const int64_t* pages, i
                                          const apm_tensor* grad_tensors,
                                          const apm_tensor* p16_tensors, int64_t n_tensors,
                                          float* grad_norm, uint8_t* skip_mask, void* stream) {
-    if (!grad_tensors && !p16_tensors) return fail(APM_EINVAL, "neither a gradient nor a parameter tensor list was given");
-    if (n_tensors < 0) return fail(APM_EINVAL, "negative tensor count");
-    return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
-                        static_cast<hipStream_t>(stream), grad_tensors, p16_tensors, n_tensors);
+    return apm::guarded([&]() -> int {
+        if (!grad_tensors && !p16_tensors) return fail(APM_EINVAL, "neither a gradient nor a parameter tensor list was given");
+        if (n_tensors < 0) return fail(APM_EINVAL, "negative tensor count");
+        return enqueue_step(pool, pages, n_pages, step, hyper, nullptr, grad_norm, skip_mask,
+                            static_cast<hipStream_t>(stream), grad_tensors, p16_tensors, n_tensors);
+    });
 }
 
 extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages,
                                 const void* new_g16, const apm_hyper* hyper, void* stream) {
-    if (!pool) return fail(APM_EINVAL, "NULL pool");
-    if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the update runs on GPU pools only");
-    if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
-    AdamwLaunch probe{};
-    int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
-    if (rc != APM_OK) return rc;
-    if (pages)
-        for (int64_t k = 0; k < n_pages; ++k)
-            if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
-    return delayed_call(pool, pages, n_pages, new_g16, static_cast<hipStream_t>(stream),
-                        [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
-                            return enqueue_step(pool, pages, n_pages, step, hyper, g16, pool->delayed_norm,
-                                                pool->delayed_skip, upd);
-                        });
+    return apm::guarded([&]() -> int {
+        if (!pool) return fail(APM_EINVAL, "NULL pool");
+        if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the update runs on GPU pools only");
+        if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
+        AdamwLaunch probe{};
+        int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
+        if (rc != APM_OK) return rc;
+        if (pages)
+            for (int64_t k = 0; k < n_pages; ++k)
+                if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
+        return delayed_call(pool, pages, n_pages, new_g16, static_cast<hipStream_t>(stream),
+                            [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
+                                return enqueue_step(pool, pages, n_pages, step, hyper, g16, pool->delayed_norm,
+                                                    pool->delayed_skip, upd);
+                            });
+    });
 }
 
 extern "C" int apm_delayed_accumulate(apm_pool* pool, const int64_t* pages, int64_t n_pages,
                                       const void* g16, void* stream) {
-    if (!pool || !g16) return fail(APM_EINVAL, "NULL argument");
-    if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "GPU pools only");
-    if (!pool->buffered) return fail(APM_ESTATE, "no gradient is being collected: call apm_step_delayed with a gradient first");
-    if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
-    if (n_pages == 0) return APM_OK;
-    APM_HIP(hipSetDevice(pool->desc.hip_device));
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int64_t first = 0;
-    bool run = true;
-    if (pages) {
-        first = pages[0];
-        for (int64_t k = 0; k < n_pages; ++k) {
-            if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
-            if (pages[k] != first + k) run = false;
+    return apm::guarded([&]() -> int {
+        if (!pool || !g16) return fail(APM_EINVAL, "NULL argument");
+        if (pool->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "GPU pools only");
+        if (!pool->buffered) return fail(APM_ESTATE, "no gradient is being collected: call apm_step_delayed with a gradient first");
+        if (n_pages < 0 || n_pages > pool->desc.n_pages) return fail(APM_ERANGE, "page count %lld out of range", (long long)n_pages);
+        if (n_pages == 0) return APM_OK;
+        APM_HIP(hipSetDevice(pool->desc.hip_device));
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int64_t first = 0;
+        bool run = true;
+        if (pages) {
+            first = pages[0];
+            for (int64_t k = 0; k < n_pages; ++k) {
+                if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
+                if (pages[k] != first + k) run = false;
+            }
         }
-    }
-    const int64_t* d_list = nullptr;
-    int slot = -1;
-    if (!run) {
-        int rc = pool->ring.acquire((size_t)n_pages * sizeof(int64_t), &slot);
-        if (rc != APM_OK) return rc;
-        int64_t* h = static_cast<int64_t*>(pool->ring.h[slot]);
-        for (int64_t k = 0; k < n_pages; ++k) h[k] = pages[k];
-        rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(int64_t), s);
-        if (rc != APM_OK) return rc;
-        d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
-    }
-    // The collecting half was staged on the producer's stream; the sum is ordered after it there,
-    // and the "staged" event moves behind the sum so that the update sees the accumulated values.
-    const int k = pool->cur;
-    APM_HIP(hipStreamWaitEvent(s, pool->ev_staged[k], 0));
-    APM_HIP(launch_grad_accum(pool->gbuf[k], static_cast<const uint16_t*>(g16), pool->d_used, d_list, first,
-                              n_pages, pool->desc.page_elems, s));
-    APM_HIP(hipEventRecord(pool->ev_staged[k], s));
-    if (slot >= 0) return pool->ring.seal(slot, s);
-    return APM_OK;
+        const int64_t* d_list = nullptr;
+        int slot = -1;
+        if (!run) {
+            int rc = pool->ring.acquire((size_t)n_pages * sizeof(int64_t), &slot);
+            if (rc != APM_OK) return rc;
+            int64_t* h = static_cast<int64_t*>(pool->ring.h[slot]);
+            for (int64_t k = 0; k < n_pages; ++k) h[k] = pages[k];
+            rc = pool->ring.commit(slot, (size_t)n_pages * sizeof(int64_t), s);
+            if (rc != APM_OK) return rc;
+            d_list = static_cast<const int64_t*>(pool->ring.d[slot]);
+        }
+        // The collecting half was staged on the producer's stream; the sum is ordered after it there,
+        // and the "staged" event moves behind the sum so that the update sees the accumulated values.
+        const int k = pool->cur;
+        APM_HIP(hipStreamWaitEvent(s, pool->ev_staged[k], 0));
+        APM_HIP(launch_grad_accum(pool->gbuf[k], static_cast<const uint16_t*>(g16), pool->d_used, d_list, first,
+                                  n_pages, pool->desc.page_elems, s));
+        APM_HIP(hipEventRecord(pool->ev_staged[k], s));
+        if (slot >= 0) return pool->ring.seal(slot, s);
+        return APM_OK;
+    });
 }
 
 extern "C" void* apm_delayed_grad_buffer(apm_pool* pool, void* stream) {
@@ -398,8 +406,10 @@ extern "C" void* apm_delayed_grad_buffer(apm_pool* pool, void* stream) {
 extern "C" int64_t apm_delayed_applied(const apm_pool* pool) { return pool ? pool->applied : 0; }
 
 extern "C" int apm_delayed_set_outputs(apm_pool* pool, float* grad_norm, uint8_t* skip_mask) {
-    if (!pool) return fail(APM_EINVAL, "NULL pool");
-    pool->delayed_norm = grad_norm;
-    pool->delayed_skip = skip_mask;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!pool) return fail(APM_EINVAL, "NULL pool");
+        pool->delayed_norm = grad_norm;
+        pool->delayed_skip = skip_mask;
+        return APM_OK;
+    });
 }

@@ -197,39 +197,43 @@ bool map_host_classes(apm_streamer* s) {
 
 extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool* dev,
                                    int64_t batch_pages, int n_slots) {
-    if (!out || !host || !dev) return fail(APM_EINVAL, "NULL argument");
-    if (host->desc.device != APM_DEV_HOST || dev->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "expected a HOST pool and a GPU pool");
-    for (int st : {APM_P32, APM_M32, APM_V32}) if (!host->stores(st)) return fail(APM_ESTATE, "host pool lacks fp32 class %d", st);
-    for (int st : {APM_G16, APM_P16}) if (!dev->stores(st)) return fail(APM_ESTATE, "GPU pool lacks 16-bit class %d", st);
-    if (host->desc.page_elems != dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
-    if (batch_pages < 1 || batch_pages > dev->desc.n_pages) return fail(APM_EINVAL, "batch_pages out of range");
-    if (n_slots < 2 || n_slots > 64) return fail(APM_EINVAL, "n_slots must be in [2, 64]");
-    APM_HIP(hipSetDevice(dev->desc.hip_device));
-    apm_streamer* s = new apm_streamer();
-    s->host = host; s->dev = dev; s->B = batch_pages; s->n_slots = n_slots;
-    s->direct_waves = kDirectWavefronts;
-    hipError_t e = hipStreamCreateWithFlags(&s->s_cmp, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_start, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_done, hipEventDisableTiming);
-    if (e != hipSuccess) {
-        free_streamer(s);
-        return fail(APM_EDEVICE, "creating streams/events failed: %s", hipGetErrorString(e));
-    }
-    int rc = ensure_scratch(dev);
-    if (rc == APM_OK) {
-        if (map_host_classes(s)) s->mode = APM_STREAM_DIRECT;
-        else { s->mode = APM_STREAM_STAGED; rc = ensure_staged(s); }
-    }
-    if (rc != APM_OK) { free_streamer(s); return rc; }
-    *out = s;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!out || !host || !dev) return fail(APM_EINVAL, "NULL argument");
+        if (host->desc.device != APM_DEV_HOST || dev->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "expected a HOST pool and a GPU pool");
+        for (int st : {APM_P32, APM_M32, APM_V32}) if (!host->stores(st)) return fail(APM_ESTATE, "host pool lacks fp32 class %d", st);
+        for (int st : {APM_G16, APM_P16}) if (!dev->stores(st)) return fail(APM_ESTATE, "GPU pool lacks 16-bit class %d", st);
+        if (host->desc.page_elems != dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
+        if (batch_pages < 1 || batch_pages > dev->desc.n_pages) return fail(APM_EINVAL, "batch_pages out of range");
+        if (n_slots < 2 || n_slots > 64) return fail(APM_EINVAL, "n_slots must be in [2, 64]");
+        APM_HIP(hipSetDevice(dev->desc.hip_device));
+        apm_streamer* s = new apm_streamer();
+        s->host = host; s->dev = dev; s->B = batch_pages; s->n_slots = n_slots;
+        s->direct_waves = kDirectWavefronts;
+        hipError_t e = hipStreamCreateWithFlags(&s->s_cmp, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_start, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_done, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            free_streamer(s);
+            return fail(APM_EDEVICE, "creating streams/events failed: %s", hipGetErrorString(e));
+        }
+        int rc = ensure_scratch(dev);
+        if (rc == APM_OK) {
+            if (map_host_classes(s)) s->mode = APM_STREAM_DIRECT;
+            else { s->mode = APM_STREAM_STAGED; rc = ensure_staged(s); }
+        }
+        if (rc != APM_OK) { free_streamer(s); return rc; }
+        *out = s;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_streamer_destroy(apm_streamer* s) {
-    if (!s) return APM_OK;
-    (void)hipSetDevice(s->dev->desc.hip_device);
-    free_streamer(s);
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!s) return APM_OK;
+        (void)hipSetDevice(s->dev->desc.hip_device);
+        free_streamer(s);
+        return APM_OK;
+    });
 }
 
 namespace {
@@ -421,8 +425,10 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
 
 extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper,
                                  float* grad_norm, uint8_t* skip_mask, void* stream) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, grad_norm, skip_mask, stream);
+    });
 }
 
 // Alg. 2 with the optimizer states off the GPU: the updating side is the streamed step (in direct
@@ -430,92 +436,108 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
 // stream handing over the next gradient.
 extern "C" int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, const apm_hyper* hyper,
                                          void* stream) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    apm_pool* dev = s->dev;
-    if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
-    AdamwLaunch probe{};
-    int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
-    if (rc != APM_OK) return rc;
-    const int64_t N = (int64_t)dev->plan.pages.size();
-    return delayed_call(dev, nullptr, N, new_g16, static_cast<hipStream_t>(stream),
-                        [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
-                            return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, dev->delayed_norm,
-                                                dev->delayed_skip, upd, g16);
-                        });
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        apm_pool* dev = s->dev;
+        if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+        AdamwLaunch probe{};
+        int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
+        if (rc != APM_OK) return rc;
+        const int64_t N = (int64_t)dev->plan.pages.size();
+        return delayed_call(dev, nullptr, N, new_g16, static_cast<hipStream_t>(stream),
+                            [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
+                                return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, dev->delayed_norm,
+                                                    dev->delayed_skip, upd, g16);
+                            });
+    });
 }
 
 extern "C" int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_wavefronts,
                                      int wavefronts_per_workgroup) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    if (mode != APM_STREAM_STAGED && mode != APM_STREAM_DIRECT) return fail(APM_EINVAL, "unknown streamer mode %d", mode);
-    if (direct_wavefronts < 0 || direct_wavefronts > (1 << 20)) return fail(APM_EINVAL, "direct_wavefronts out of range");
-    if (wavefronts_per_workgroup < 0 || wavefronts_per_workgroup > 16) return fail(APM_EINVAL, "wavefronts_per_workgroup must be in [0, 16]");
-    APM_HIP(hipSetDevice(s->dev->desc.hip_device));
-    if (mode == APM_STREAM_DIRECT) {
-        if (!map_host_classes(s)) return fail(APM_EDEVICE, "the host pool's memory is not mapped into the GPU's address space (not pinned?)");
-        s->direct_waves = direct_wavefronts > 0 ? direct_wavefronts : kDirectWavefronts;
-        s->direct_per_wg = wavefronts_per_workgroup > 0 ? wavefronts_per_workgroup : 1;
-    } else {
-        int rc = ensure_staged(s);
-        if (rc != APM_OK) return rc;
-    }
-    s->mode = mode;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (mode != APM_STREAM_STAGED && mode != APM_STREAM_DIRECT) return fail(APM_EINVAL, "unknown streamer mode %d", mode);
+        if (direct_wavefronts < 0 || direct_wavefronts > (1 << 20)) return fail(APM_EINVAL, "direct_wavefronts out of range");
+        if (wavefronts_per_workgroup < 0 || wavefronts_per_workgroup > 16) return fail(APM_EINVAL, "wavefronts_per_workgroup must be in [0, 16]");
+        APM_HIP(hipSetDevice(s->dev->desc.hip_device));
+        if (mode == APM_STREAM_DIRECT) {
+            if (!map_host_classes(s)) return fail(APM_EDEVICE, "the host pool's memory is not mapped into the GPU's address space (not pinned?)");
+            s->direct_waves = direct_wavefronts > 0 ? direct_wavefronts : kDirectWavefronts;
+            s->direct_per_wg = wavefronts_per_workgroup > 0 ? wavefronts_per_workgroup : 1;
+        } else {
+            int rc = ensure_staged(s);
+            if (rc != APM_OK) return rc;
+        }
+        s->mode = mode;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_streamer_get_mode(const apm_streamer* s) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    return s->mode;
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        return s->mode;
+    });
 }
 
 extern "C" int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, double* duplex_each_way) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    if (h2d) *h2d = s->probe_h2d;
-    if (d2h) *d2h = s->probe_d2h;
-    if (duplex_each_way) *duplex_each_way = s->probe_duplex;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (h2d) *h2d = s->probe_h2d;
+        if (d2h) *d2h = s->probe_d2h;
+        if (duplex_each_way) *duplex_each_way = s->probe_duplex;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_streamer_set_cache(apm_streamer* s, apm_pool* cache, int64_t n_resident) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    if (!cache || n_resident == 0) {
-        s->cache = nullptr;
-        s->R = 0;
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (!cache || n_resident == 0) {
+            s->cache = nullptr;
+            s->R = 0;
+            return APM_OK;
+        }
+        if (cache->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the cache must be a GPU pool");
+        for (int st : {APM_P32, APM_M32, APM_V32}) if (!cache->stores(st)) return fail(APM_ESTATE, "cache pool lacks fp32 class %d", st);
+        if (cache->desc.page_elems != s->dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
+        if (n_resident < 0 || n_resident > cache->desc.n_pages) return fail(APM_ERANGE, "n_resident %lld exceeds the cache pool's %lld pages", (long long)n_resident, (long long)cache->desc.n_pages);
+        s->cache = cache;
+        s->R = n_resident;
         return APM_OK;
-    }
-    if (cache->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "the cache must be a GPU pool");
-    for (int st : {APM_P32, APM_M32, APM_V32}) if (!cache->stores(st)) return fail(APM_ESTATE, "cache pool lacks fp32 class %d", st);
-    if (cache->desc.page_elems != s->dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
-    if (n_resident < 0 || n_resident > cache->desc.n_pages) return fail(APM_ERANGE, "n_resident %lld exceeds the cache pool's %lld pages", (long long)n_resident, (long long)cache->desc.n_pages);
-    s->cache = cache;
-    s->R = n_resident;
-    return APM_OK;
+    });
 }
 
 extern "C" int apm_cache_pages_that_fit(int hip_device, int64_t page_elems, int64_t n_pages,
                                         size_t reserve_bytes, int64_t* out) {
-    if (!out || page_elems <= 0 || n_pages < 0) return fail(APM_EINVAL, "bad argument");
-    APM_HIP(hipSetDevice(hip_device));
-    size_t free_b = 0, total_b = 0;
-    APM_HIP(hipMemGetInfo(&free_b, &total_b));
-    const size_t page_bytes = (size_t)page_elems * 3u * sizeof(float);
-    const size_t usable = free_b > reserve_bytes ? free_b - reserve_bytes : 0;
-    const int64_t fit = (int64_t)(usable / page_bytes);
-    *out = fit < n_pages ? fit : n_pages;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!out || page_elems <= 0 || n_pages < 0) return fail(APM_EINVAL, "bad argument");
+        APM_HIP(hipSetDevice(hip_device));
+        size_t free_b = 0, total_b = 0;
+        APM_HIP(hipMemGetInfo(&free_b, &total_b));
+        const size_t page_bytes = (size_t)page_elems * 3u * sizeof(float);
+        const size_t usable = free_b > reserve_bytes ? free_b - reserve_bytes : 0;
+        const int64_t fit = (int64_t)(usable / page_bytes);
+        *out = fit < n_pages ? fit : n_pages;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_streamer_set_page_count(apm_streamer* s, int64_t n_pages) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    s->page_limit = n_pages < 0 ? -1 : n_pages;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        s->page_limit = n_pages < 0 ? -1 : n_pages;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    if (first_model_page < 0 || first_model_page > s->dev->desc.n_pages) return fail(APM_ERANGE, "first_model_page out of range");
-    s->host_first = first_model_page;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (first_model_page < 0 || first_model_page > s->dev->desc.n_pages) return fail(APM_ERANGE, "first_model_page out of range");
+        s->host_first = first_model_page;
+        return APM_OK;
+    });
 }
 
 // One step driven by a schedule (Alg. 1's task list) instead of the fixed slot ring.  The staging
@@ -528,190 +550,194 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                                            const int64_t* layer_first_page, int64_t n_layers,
                                            int64_t step, const apm_hyper* hyper, float* grad_norm,
                                            uint8_t* skip_mask, void* stream) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    if (n_tasks < 0 || n_layers < 0 || (n_tasks > 0 && !tasks) || !layer_first_page) return fail(APM_EINVAL, "bad task or layer arrays");
-    apm_pool* dev = s->dev;
-    apm_pool* host = s->host;
-    if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
-    const int64_t N = (int64_t)dev->plan.pages.size();
-    if (layer_first_page[0] != 0 || layer_first_page[n_layers] != N) return fail(APM_EINVAL, "the layers must cover pages [0, %lld) in order", (long long)N);
-    for (int64_t i = 0; i < n_layers; ++i)
-        if (layer_first_page[i + 1] < layer_first_page[i]) return fail(APM_EINVAL, "layer_first_page must not decrease");
-    if (s->cache || s->host_first != 0 || s->page_limit >= 0) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache or a page range");
-    if (s->host->desc.n_pages < N) return fail(APM_ESTATE, "the host pool holds fewer pages than are in use");
-    AdamwLaunch L{};
-    int rc = prepare_hyper(hyper, step, &L);
-    if (rc != APM_OK) return rc;
-    rc = ensure_staged(s);
-    if (rc != APM_OK) return rc;
-    APM_HIP(hipSetDevice(dev->desc.hip_device));
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (n_tasks < 0 || n_layers < 0 || (n_tasks > 0 && !tasks) || !layer_first_page) return fail(APM_EINVAL, "bad task or layer arrays");
+        apm_pool* dev = s->dev;
+        apm_pool* host = s->host;
+        if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+        const int64_t N = (int64_t)dev->plan.pages.size();
+        if (layer_first_page[0] != 0 || layer_first_page[n_layers] != N) return fail(APM_EINVAL, "the layers must cover pages [0, %lld) in order", (long long)N);
+        for (int64_t i = 0; i < n_layers; ++i)
+            if (layer_first_page[i + 1] < layer_first_page[i]) return fail(APM_EINVAL, "layer_first_page must not decrease");
+        if (s->cache || s->host_first != 0 || s->page_limit >= 0) return fail(APM_ESTATE, "the scheduled step does not combine with a resident cache or a page range");
+        if (s->host->desc.n_pages < N) return fail(APM_ESTATE, "the host pool holds fewer pages than are in use");
+        AdamwLaunch L{};
+        int rc = prepare_hyper(hyper, step, &L);
+        if (rc != APM_OK) return rc;
+        rc = ensure_staged(s);
+        if (rc != APM_OK) return rc;
+        APM_HIP(hipSetDevice(dev->desc.hip_device));
 
-    // ---- pass 1 (host only): replay the schedule against the slots -------------------------
-    const int64_t n_slots = (int64_t)s->n_slots * s->B;
-    std::vector<int64_t> slot_of((size_t)N, -1);
-    std::vector<uint8_t> moved((size_t)N, 0);
-    std::vector<int64_t> free_slots((size_t)n_slots);  // min-heap: the lowest free slot first keeps runs together
-    for (int64_t k = 0; k < n_slots; ++k) free_slots[(size_t)k] = k;
-    auto cmp = [](int64_t a, int64_t b) { return a > b; };
-    std::make_heap(free_slots.begin(), free_slots.end(), cmp);
-    std::vector<int64_t> slot_seq((size_t)N, -1);  // slot given to each movement task, by page
-    int64_t next_layer = 0, n_moves = 0;
-    for (int64_t k = 0; k < n_tasks; ++k) {
-        const apm_task& t = tasks[k];
-        if (t.op == APM_TASK_MOVE_TO_GPU) {
-            if (t.target < 0 || t.target >= N) return fail(APM_ERANGE, "task %lld moves page %lld, out of range", (long long)k, (long long)t.target);
-            if (moved[(size_t)t.target]) return fail(APM_EINVAL, "task %lld moves page %lld a second time", (long long)k, (long long)t.target);
-            if (free_slots.empty()) return fail(APM_ENOMEM, "task %lld: the schedule needs more than the %lld staging page slots", (long long)k, (long long)n_slots);
-            std::pop_heap(free_slots.begin(), free_slots.end(), cmp);
-            slot_seq[(size_t)t.target] = slot_of[(size_t)t.target] = free_slots.back();
-            free_slots.pop_back();
-            moved[(size_t)t.target] = 1;
-            ++n_moves;
-        } else if (t.op == APM_TASK_COMPUTE) {
-            if (t.target != next_layer) return fail(APM_EINVAL, "task %lld computes layer %lld, expected layer %lld", (long long)k, (long long)t.target, (long long)next_layer);
-            for (int64_t p = layer_first_page[next_layer]; p < layer_first_page[next_layer + 1]; ++p) {
-                if (slot_of[(size_t)p] < 0) return fail(APM_ESTATE, "task %lld computes layer %lld before its page %lld was moved", (long long)k, (long long)next_layer, (long long)p);
-                free_slots.push_back(slot_of[(size_t)p]);
-                std::push_heap(free_slots.begin(), free_slots.end(), cmp);
-                slot_of[(size_t)p] = -1;
+        // ---- pass 1 (host only): replay the schedule against the slots -------------------------
+        const int64_t n_slots = (int64_t)s->n_slots * s->B;
+        std::vector<int64_t> slot_of((size_t)N, -1);
+        std::vector<uint8_t> moved((size_t)N, 0);
+        std::vector<int64_t> free_slots((size_t)n_slots);  // min-heap: the lowest free slot first keeps runs together
+        for (int64_t k = 0; k < n_slots; ++k) free_slots[(size_t)k] = k;
+        auto cmp = [](int64_t a, int64_t b) { return a > b; };
+        std::make_heap(free_slots.begin(), free_slots.end(), cmp);
+        std::vector<int64_t> slot_seq((size_t)N, -1);  // slot given to each movement task, by page
+        int64_t next_layer = 0, n_moves = 0;
+        for (int64_t k = 0; k < n_tasks; ++k) {
+            const apm_task& t = tasks[k];
+            if (t.op == APM_TASK_MOVE_TO_GPU) {
+                if (t.target < 0 || t.target >= N) return fail(APM_ERANGE, "task %lld moves page %lld, out of range", (long long)k, (long long)t.target);
+                if (moved[(size_t)t.target]) return fail(APM_EINVAL, "task %lld moves page %lld a second time", (long long)k, (long long)t.target);
+                if (free_slots.empty()) return fail(APM_ENOMEM, "task %lld: the schedule needs more than the %lld staging page slots", (long long)k, (long long)n_slots);
+                std::pop_heap(free_slots.begin(), free_slots.end(), cmp);
+                slot_seq[(size_t)t.target] = slot_of[(size_t)t.target] = free_slots.back();
+                free_slots.pop_back();
+                moved[(size_t)t.target] = 1;
+                ++n_moves;
+            } else if (t.op == APM_TASK_COMPUTE) {
+                if (t.target != next_layer) return fail(APM_EINVAL, "task %lld computes layer %lld, expected layer %lld", (long long)k, (long long)t.target, (long long)next_layer);
+                for (int64_t p = layer_first_page[next_layer]; p < layer_first_page[next_layer + 1]; ++p) {
+                    if (slot_of[(size_t)p] < 0) return fail(APM_ESTATE, "task %lld computes layer %lld before its page %lld was moved", (long long)k, (long long)next_layer, (long long)p);
+                    free_slots.push_back(slot_of[(size_t)p]);
+                    std::push_heap(free_slots.begin(), free_slots.end(), cmp);
+                    slot_of[(size_t)p] = -1;
+                }
+                ++next_layer;
+            } else {
+                return fail(APM_EINVAL, "task %lld has unknown operation %d", (long long)k, t.op);
             }
-            ++next_layer;
-        } else {
-            return fail(APM_EINVAL, "task %lld has unknown operation %d", (long long)k, t.op);
         }
-    }
-    if (next_layer != n_layers || n_moves != N) return fail(APM_EINVAL, "the schedule computes %lld of %lld layers and moves %lld of %lld pages", (long long)next_layer, (long long)n_layers, (long long)n_moves, (long long)N);
+        if (next_layer != n_layers || n_moves != N) return fail(APM_EINVAL, "the schedule computes %lld of %lld layers and moves %lld of %lld pages", (long long)next_layer, (long long)n_layers, (long long)n_moves, (long long)N);
 
-    // ---- pass 2: enqueue --------------------------------------------------------------------
-    hipStream_t caller = static_cast<hipStream_t>(stream);
-    const int64_t E = dev->desc.page_elems;
-    const size_t pb = (size_t)E * sizeof(float);
-    const int states[3] = {APM_P32, APM_M32, APM_V32};
-    size_t ev_used = 0;
-    auto new_event = [&](hipEvent_t* out) -> int {
-        if (ev_used == s->sched_ev.size()) {
-            hipEvent_t e = nullptr;
-            APM_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-            s->sched_ev.push_back(e);
+        // ---- pass 2: enqueue --------------------------------------------------------------------
+        hipStream_t caller = static_cast<hipStream_t>(stream);
+        const int64_t E = dev->desc.page_elems;
+        const size_t pb = (size_t)E * sizeof(float);
+        const int states[3] = {APM_P32, APM_M32, APM_V32};
+        size_t ev_used = 0;
+        auto new_event = [&](hipEvent_t* out) -> int {
+            if (ev_used == s->sched_ev.size()) {
+                hipEvent_t e = nullptr;
+                APM_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+                s->sched_ev.push_back(e);
+            }
+            *out = s->sched_ev[ev_used++];
+            return APM_OK;
+        };
+        APM_HIP(hipEventRecord(s->ev_start, caller));
+        APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
+        APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_start, 0));
+        APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
+
+        // the slot of every page, for the kernels (fp32 classes are addressed by slot, 16-bit ones by page)
+        int slots_ring_slot = -1;
+        {
+            int slot;
+            rc = dev->ring.acquire((size_t)N * sizeof(int64_t), &slot);
+            if (rc != APM_OK) return rc;
+            int64_t* h = static_cast<int64_t*>(dev->ring.h[slot]);
+            for (int64_t p = 0; p < N; ++p) h[p] = slot_seq[(size_t)p];
+            rc = dev->ring.commit(slot, (size_t)N * sizeof(int64_t), s->s_cmp);
+            if (rc != APM_OK) return rc;
+            slots_ring_slot = slot;
+            L.state_pages = static_cast<const int64_t*>(dev->ring.d[slot]);
         }
-        *out = s->sched_ev[ev_used++];
-        return APM_OK;
-    };
-    APM_HIP(hipEventRecord(s->ev_start, caller));
-    APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
-    APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_start, 0));
-    APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
+        L.g16 = static_cast<const uint16_t*>(dev->base[APM_G16]);
+        L.p16 = static_cast<uint16_t*>(dev->base[APM_P16]);
+        L.used = dev->d_used;
+        L.E = E;
+        L.S = dev->S;
+        L.p32 = s->stage[0];
+        L.m32 = s->stage[1];
+        L.v32 = s->stage[2];
+        L.meta = dev->d_meta;
+        const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
+        if (need_reduce) {
+            L.partials = dev->d_partials;
+            L.nzflags = dev->d_nzflags;
+        }
+        const int64_t* d_slots = L.state_pages;
 
-    // the slot of every page, for the kernels (fp32 classes are addressed by slot, 16-bit ones by page)
-    int slots_ring_slot = -1;
-    {
-        int slot;
-        rc = dev->ring.acquire((size_t)N * sizeof(int64_t), &slot);
-        if (rc != APM_OK) return rc;
-        int64_t* h = static_cast<int64_t*>(dev->ring.h[slot]);
-        for (int64_t p = 0; p < N; ++p) h[p] = slot_seq[(size_t)p];
-        rc = dev->ring.commit(slot, (size_t)N * sizeof(int64_t), s->s_cmp);
-        if (rc != APM_OK) return rc;
-        slots_ring_slot = slot;
-        L.state_pages = static_cast<const int64_t*>(dev->ring.d[slot]);
-    }
-    L.g16 = static_cast<const uint16_t*>(dev->base[APM_G16]);
-    L.p16 = static_cast<uint16_t*>(dev->base[APM_P16]);
-    L.used = dev->d_used;
-    L.E = E;
-    L.S = dev->S;
-    L.p32 = s->stage[0];
-    L.m32 = s->stage[1];
-    L.v32 = s->stage[2];
-    L.meta = dev->d_meta;
-    const bool need_reduce = grad_norm || skip_mask || L.max_norm > 0.0 || L.skip_mode != APM_SKIP_NONE;
-    if (need_reduce) {
-        L.partials = dev->d_partials;
-        L.nzflags = dev->d_nzflags;
-    }
-    const int64_t* d_slots = L.state_pages;
-
-    std::vector<hipEvent_t> slot_free((size_t)n_slots, nullptr);  // write-back that last freed the slot
-    std::vector<hipEvent_t> page_in((size_t)N, nullptr);          // copy-in that brought the page
-    int64_t k = 0;
-    while (k < n_tasks) {
-        if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
-            // a run of movement tasks over consecutive pages and consecutive slots is one copy per class
-            const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
-            int64_t n = 1;
-            while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
-                   slot_seq[(size_t)(p0 + n)] == s0 + n)
-                ++n;
+        std::vector<hipEvent_t> slot_free((size_t)n_slots, nullptr);  // write-back that last freed the slot
+        std::vector<hipEvent_t> page_in((size_t)N, nullptr);          // copy-in that brought the page
+        int64_t k = 0;
+        while (k < n_tasks) {
+            if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
+                // a run of movement tasks over consecutive pages and consecutive slots is one copy per class
+                const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
+                int64_t n = 1;
+                while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
+                       slot_seq[(size_t)(p0 + n)] == s0 + n)
+                    ++n;
+                hipEvent_t last_wait = nullptr;
+                for (int64_t j = 0; j < n; ++j) {
+                    hipEvent_t w = slot_free[(size_t)(s0 + j)];
+                    if (w && w != last_wait) {
+                        APM_HIP(hipStreamWaitEvent(s->s_in, w, 0));
+                        last_wait = w;
+                    }
+                }
+                for (int c = 0; c < 3; ++c) {
+                    const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
+                    APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s->s_in));
+                }
+                hipEvent_t done;
+                rc = new_event(&done);
+                if (rc != APM_OK) return rc;
+                APM_HIP(hipEventRecord(done, s->s_in));
+                for (int64_t j = 0; j < n; ++j) page_in[(size_t)(p0 + j)] = done;
+                k += n;
+                continue;
+            }
+            const int64_t i = tasks[k].target;
+            const int64_t first = layer_first_page[i], n = layer_first_page[i + 1] - first;
+            ++k;
+            if (n == 0) continue;
             hipEvent_t last_wait = nullptr;
             for (int64_t j = 0; j < n; ++j) {
-                hipEvent_t w = slot_free[(size_t)(s0 + j)];
-                if (w && w != last_wait) {
-                    APM_HIP(hipStreamWaitEvent(s->s_in, w, 0));
+                hipEvent_t w = page_in[(size_t)(first + j)];
+                if (w != last_wait) {
+                    APM_HIP(hipStreamWaitEvent(s->s_cmp, w, 0));
                     last_wait = w;
                 }
             }
-            for (int c = 0; c < 3; ++c) {
-                const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
-                APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s->s_in));
-            }
-            hipEvent_t done;
-            rc = new_event(&done);
+            AdamwLaunch C = L;
+            C.state_pages = d_slots + first;
+            C.grad_first = first;
+            C.n_listed = n;
+            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+            if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
+            else APM_HIP(launch_prepare(C, s->s_cmp));
+            APM_HIP(launch_adamw(C, s->s_cmp));
+            hipEvent_t computed, written;
+            rc = new_event(&computed);
+            if (rc == APM_OK) rc = new_event(&written);
             if (rc != APM_OK) return rc;
-            APM_HIP(hipEventRecord(done, s->s_in));
-            for (int64_t j = 0; j < n; ++j) page_in[(size_t)(p0 + j)] = done;
-            k += n;
-            continue;
-        }
-        const int64_t i = tasks[k].target;
-        const int64_t first = layer_first_page[i], n = layer_first_page[i + 1] - first;
-        ++k;
-        if (n == 0) continue;
-        hipEvent_t last_wait = nullptr;
-        for (int64_t j = 0; j < n; ++j) {
-            hipEvent_t w = page_in[(size_t)(first + j)];
-            if (w != last_wait) {
-                APM_HIP(hipStreamWaitEvent(s->s_cmp, w, 0));
-                last_wait = w;
+            APM_HIP(hipEventRecord(computed, s->s_cmp));
+            APM_HIP(hipStreamWaitEvent(s->s_out, computed, 0));
+            for (int64_t j = 0; j < n;) {  // write back in runs of consecutive slots
+                const int64_t s0 = slot_seq[(size_t)(first + j)];
+                int64_t m = 1;
+                while (j + m < n && slot_seq[(size_t)(first + j + m)] == s0 + m) ++m;
+                for (int c = 0; c < 3; ++c) {
+                    char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)(first + j) * pb;
+                    APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * (size_t)m, hipMemcpyDeviceToHost, s->s_out));
+                }
+                j += m;
             }
+            APM_HIP(hipEventRecord(written, s->s_out));
+            for (int64_t j = 0; j < n; ++j) slot_free[(size_t)slot_seq[(size_t)(first + j)]] = written;
         }
-        AdamwLaunch C = L;
-        C.state_pages = d_slots + first;
-        C.grad_first = first;
-        C.n_listed = n;
-        C.grad_norm = grad_norm ? grad_norm + first : nullptr;
-        C.skip_mask = skip_mask ? skip_mask + first : nullptr;
-        if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
-        else APM_HIP(launch_prepare(C, s->s_cmp));
-        APM_HIP(launch_adamw(C, s->s_cmp));
-        hipEvent_t computed, written;
-        rc = new_event(&computed);
-        if (rc == APM_OK) rc = new_event(&written);
+        rc = dev->ring.seal(slots_ring_slot, s->s_cmp);
         if (rc != APM_OK) return rc;
-        APM_HIP(hipEventRecord(computed, s->s_cmp));
-        APM_HIP(hipStreamWaitEvent(s->s_out, computed, 0));
-        for (int64_t j = 0; j < n;) {  // write back in runs of consecutive slots
-            const int64_t s0 = slot_seq[(size_t)(first + j)];
-            int64_t m = 1;
-            while (j + m < n && slot_seq[(size_t)(first + j + m)] == s0 + m) ++m;
-            for (int c = 0; c < 3; ++c) {
-                char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)(first + j) * pb;
-                APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * (size_t)m, hipMemcpyDeviceToHost, s->s_out));
-            }
-            j += m;
-        }
-        APM_HIP(hipEventRecord(written, s->s_out));
-        for (int64_t j = 0; j < n; ++j) slot_free[(size_t)slot_seq[(size_t)(first + j)]] = written;
-    }
-    rc = dev->ring.seal(slots_ring_slot, s->s_cmp);
-    if (rc != APM_OK) return rc;
-    // every copy-in feeds a compute and every compute a write-back: the copy-out stream ends last
-    APM_HIP(hipEventRecord(s->ev_done, s->s_out));
-    APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
-    return APM_OK;
+        // every copy-in feeds a compute and every compute a write-back: the copy-out stream ends last
+        APM_HIP(hipEventRecord(s->ev_done, s->s_out));
+        APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_streamer_copy_only(apm_streamer* s, int directions, void* stream) {
-    if (!s) return fail(APM_EINVAL, "NULL streamer");
-    if (directions < 1 || directions > 3) return fail(APM_EINVAL, "directions must be 1 (H2D), 2 (D2H) or 3 (both)");
-    return run_pipeline(s, directions, 1, nullptr, nullptr, nullptr, stream);
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (directions < 1 || directions > 3) return fail(APM_EINVAL, "directions must be 1 (H2D), 2 (D2H) or 3 (both)");
+        return run_pipeline(s, directions, 1, nullptr, nullptr, nullptr, stream);
+    });
 }

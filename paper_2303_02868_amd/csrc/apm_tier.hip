@@ -11,6 +11,7 @@
 #include <cerrno>
 #include <cstring>
 #include <string>
+#include <system_error>
 #include <thread>
 
 #include "apm_internal.h"
@@ -168,41 +169,43 @@ int join_updater(apm_tiered* t) {
 extern "C" int apm_file_pool_create(apm_pool** out, const char* path_prefix, int32_t hip_device,
                                     int64_t page_elems, int64_t n_pages, uint32_t state_mask,
                                     uint32_t flags) {
-    if (!out || !path_prefix || !*path_prefix) return fail(APM_EINVAL, "NULL argument or empty path prefix");
-    if (page_elems <= 0 || page_elems % kAlign != 0 || page_elems > (int64_t)1 << 30) return fail(APM_EINVAL, "page_elems must be a positive multiple of %lld, at most 2^30", (long long)kAlign);
-    if (n_pages <= 0) return fail(APM_EINVAL, "n_pages must be positive");
-    if (state_mask == 0 || state_mask >> APM_N_STATES) return fail(APM_EINVAL, "bad state_mask 0x%x", state_mask);
-    if (flags & ~(uint32_t)(APM_POOL_NO_ZERO | APM_POOL_FILE_DIRECT)) return fail(APM_EINVAL, "unknown flags 0x%x", flags);
-    apm_pool* pool = new apm_pool();
-    pool->desc.device = APM_DEV_FILE;
-    pool->desc.hip_device = hip_device;
-    pool->desc.page_elems = page_elems;
-    pool->desc.n_pages = n_pages;
-    pool->desc.state_mask = state_mask;
-    pool->desc.flags = flags;
-    static const char* const suffix[APM_N_STATES] = {".p32", ".m32", ".v32", ".g16", ".p16"};
-    for (int st = 0; st < APM_N_STATES; ++st) {
-        if (!pool->stores(st)) continue;
-        const size_t page_bytes = (size_t)page_elems * (size_t)elem_bytes(st);
-        if ((flags & APM_POOL_FILE_DIRECT) && page_bytes % 4096 != 0) {
-            apm_pool_destroy(pool);
-            return fail(APM_EINVAL, "unbuffered file I/O needs pages of a multiple of 4096 bytes (class %d has %zu)", st, page_bytes);
+    return apm::guarded([&]() -> int {
+        if (!out || !path_prefix || !*path_prefix) return fail(APM_EINVAL, "NULL argument or empty path prefix");
+        if (page_elems <= 0 || page_elems % kAlign != 0 || page_elems > (int64_t)1 << 30) return fail(APM_EINVAL, "page_elems must be a positive multiple of %lld, at most 2^30", (long long)kAlign);
+        if (n_pages <= 0) return fail(APM_EINVAL, "n_pages must be positive");
+        if (state_mask == 0 || state_mask >> APM_N_STATES) return fail(APM_EINVAL, "bad state_mask 0x%x", state_mask);
+        if (flags & ~(uint32_t)(APM_POOL_NO_ZERO | APM_POOL_FILE_DIRECT)) return fail(APM_EINVAL, "unknown flags 0x%x", flags);
+        apm_pool* pool = new apm_pool();
+        pool->desc.device = APM_DEV_FILE;
+        pool->desc.hip_device = hip_device;
+        pool->desc.page_elems = page_elems;
+        pool->desc.n_pages = n_pages;
+        pool->desc.state_mask = state_mask;
+        pool->desc.flags = flags;
+        static const char* const suffix[APM_N_STATES] = {".p32", ".m32", ".v32", ".g16", ".p16"};
+        for (int st = 0; st < APM_N_STATES; ++st) {
+            if (!pool->stores(st)) continue;
+            const size_t page_bytes = (size_t)page_elems * (size_t)elem_bytes(st);
+            if ((flags & APM_POOL_FILE_DIRECT) && page_bytes % 4096 != 0) {
+                apm_pool_destroy(pool);
+                return fail(APM_EINVAL, "unbuffered file I/O needs pages of a multiple of 4096 bytes (class %d has %zu)", st, page_bytes);
+            }
+            const std::string path = std::string(path_prefix) + suffix[st];
+            int oflags = O_RDWR | O_CREAT | O_CLOEXEC;
+            if (!(flags & APM_POOL_NO_ZERO)) oflags |= O_TRUNC;  // recreated at full size below: reads as zeros
+            if (flags & APM_POOL_FILE_DIRECT) oflags |= O_DIRECT;
+            const int fd = open(path.c_str(), oflags, 0600);
+            if (fd < 0 || ftruncate(fd, (off_t)(page_bytes * (size_t)n_pages)) != 0) {
+                const int err = errno;
+                if (fd >= 0) close(fd);
+                apm_pool_destroy(pool);
+                return fail(APM_EDEVICE, "cannot create %s: %s", path.c_str(), strerror(err));
+            }
+            pool->fd[st] = fd;
         }
-        const std::string path = std::string(path_prefix) + suffix[st];
-        int oflags = O_RDWR | O_CREAT | O_CLOEXEC;
-        if (!(flags & APM_POOL_NO_ZERO)) oflags |= O_TRUNC;  // recreated at full size below: reads as zeros
-        if (flags & APM_POOL_FILE_DIRECT) oflags |= O_DIRECT;
-        const int fd = open(path.c_str(), oflags, 0600);
-        if (fd < 0 || ftruncate(fd, (off_t)(page_bytes * (size_t)n_pages)) != 0) {
-            const int err = errno;
-            if (fd >= 0) close(fd);
-            apm_pool_destroy(pool);
-            return fail(APM_EDEVICE, "cannot create %s: %s", path.c_str(), strerror(err));
-        }
-        pool->fd[st] = fd;
-    }
-    *out = pool;
-    return APM_OK;
+        *out = pool;
+        return APM_OK;
+    });
 }
 
 namespace apm {
@@ -228,133 +231,154 @@ int file_page_copy(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_p
 
 extern "C" int apm_tiered_create(apm_tiered** out, apm_pool* file, apm_pool* dev, int64_t batch_pages,
                                  int n_slots, int io_threads) {
-    if (!out || !file || !dev) return fail(APM_EINVAL, "NULL argument");
-    if (file->desc.device != APM_DEV_FILE || dev->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "expected a FILE pool and a GPU pool");
-    for (int st : {APM_P32, APM_M32, APM_V32}) if (!file->stores(st)) return fail(APM_ESTATE, "file pool lacks fp32 class %d", st);
-    for (int st : {APM_G16, APM_P16}) if (!dev->stores(st)) return fail(APM_ESTATE, "GPU pool lacks 16-bit class %d", st);
-    if (file->desc.page_elems != dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
-    if (file->desc.n_pages < dev->desc.n_pages) return fail(APM_EINVAL, "file pool has fewer pages than the GPU pool");
-    if (batch_pages < 1 || batch_pages > dev->desc.n_pages) return fail(APM_EINVAL, "batch_pages out of range");
-    if (n_slots < 2 || n_slots > 64) return fail(APM_EINVAL, "n_slots must be in [2, 64]");
-    if (io_threads < 1 || io_threads > 64) return fail(APM_EINVAL, "io_threads must be in [1, 64]");
-    APM_HIP(hipSetDevice(dev->desc.hip_device));
-    apm_tiered* t = new apm_tiered();
-    t->file = file; t->dev = dev; t->B = batch_pages; t->n_slots = n_slots;
-    const size_t bytes = (size_t)n_slots * (size_t)batch_pages * (size_t)dev->desc.page_elems * sizeof(float);
-    hipError_t e = hipSuccess;
-    for (int k = 0; k < 3 && e == hipSuccess; ++k) {
-        e = hipHostMalloc((void**)&t->win[k], bytes, hipHostMallocDefault);
-        if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&t->win_dev[k], t->win[k], 0);
-    }
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        free_tiered(t);
-        return fail(APM_ENOMEM, "allocating 3 x %zu bytes of pinned window failed: %s", bytes, hipGetErrorString(e));
-    }
-    e = hipStreamCreateWithFlags(&t->s_cmp, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&t->ev_start, hipEventDisableTiming);
-    t->ev_done.assign((size_t)n_slots, nullptr);
-    for (int k = 0; k < n_slots && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&t->ev_done[(size_t)k], hipEventDisableTiming);
-    if (e != hipSuccess) {
-        free_tiered(t);
-        return fail(APM_EDEVICE, "creating the stream / events failed: %s", hipGetErrorString(e));
-    }
-    e = hipMalloc((void**)&t->d_skip, (size_t)dev->desc.n_pages);
-    if (e == hipSuccess) e = hipHostMalloc((void**)&t->h_skip, (size_t)dev->desc.n_pages, hipHostMallocDefault);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        free_tiered(t);
-        return fail(APM_ENOMEM, "allocating the per-page skip flags failed: %s", hipGetErrorString(e));
-    }
-    int rc = ensure_scratch(dev);
-    if (rc != APM_OK) { free_tiered(t); return rc; }
-    t->io = new IoPool(io_threads);
-    const int fds[3] = {file->fd[APM_P32], file->fd[APM_M32], file->fd[APM_V32]};
-    t->chain = new WindowChain(t->io, fds, t->win, (size_t)dev->desc.page_elems * sizeof(float), batch_pages,
-                               n_slots, (file->desc.flags & APM_POOL_FILE_DIRECT) != 0);
-    *out = t;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!out || !file || !dev) return fail(APM_EINVAL, "NULL argument");
+        if (file->desc.device != APM_DEV_FILE || dev->desc.device != APM_DEV_GPU) return fail(APM_EDEVICE, "expected a FILE pool and a GPU pool");
+        for (int st : {APM_P32, APM_M32, APM_V32}) if (!file->stores(st)) return fail(APM_ESTATE, "file pool lacks fp32 class %d", st);
+        for (int st : {APM_G16, APM_P16}) if (!dev->stores(st)) return fail(APM_ESTATE, "GPU pool lacks 16-bit class %d", st);
+        if (file->desc.page_elems != dev->desc.page_elems) return fail(APM_EINVAL, "pools have different page sizes");
+        if (file->desc.n_pages < dev->desc.n_pages) return fail(APM_EINVAL, "file pool has fewer pages than the GPU pool");
+        if (batch_pages < 1 || batch_pages > dev->desc.n_pages) return fail(APM_EINVAL, "batch_pages out of range");
+        if (n_slots < 2 || n_slots > 64) return fail(APM_EINVAL, "n_slots must be in [2, 64]");
+        if (io_threads < 1 || io_threads > 64) return fail(APM_EINVAL, "io_threads must be in [1, 64]");
+        APM_HIP(hipSetDevice(dev->desc.hip_device));
+        apm_tiered* t = new apm_tiered();
+        t->file = file; t->dev = dev; t->B = batch_pages; t->n_slots = n_slots;
+        const size_t bytes = (size_t)n_slots * (size_t)batch_pages * (size_t)dev->desc.page_elems * sizeof(float);
+        hipError_t e = hipSuccess;
+        for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+            e = hipHostMalloc((void**)&t->win[k], bytes, hipHostMallocDefault);
+            if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&t->win_dev[k], t->win[k], 0);
+        }
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            free_tiered(t);
+            return fail(APM_ENOMEM, "allocating 3 x %zu bytes of pinned window failed: %s", bytes, hipGetErrorString(e));
+        }
+        e = hipStreamCreateWithFlags(&t->s_cmp, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&t->ev_start, hipEventDisableTiming);
+        t->ev_done.assign((size_t)n_slots, nullptr);
+        for (int k = 0; k < n_slots && e == hipSuccess; ++k) e = hipEventCreateWithFlags(&t->ev_done[(size_t)k], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            free_tiered(t);
+            return fail(APM_EDEVICE, "creating the stream / events failed: %s", hipGetErrorString(e));
+        }
+        e = hipMalloc((void**)&t->d_skip, (size_t)dev->desc.n_pages);
+        if (e == hipSuccess) e = hipHostMalloc((void**)&t->h_skip, (size_t)dev->desc.n_pages, hipHostMallocDefault);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            free_tiered(t);
+            return fail(APM_ENOMEM, "allocating the per-page skip flags failed: %s", hipGetErrorString(e));
+        }
+        int rc = ensure_scratch(dev);
+        if (rc != APM_OK) { free_tiered(t); return rc; }
+        try {
+            t->io = new IoPool(io_threads);
+            const int fds[3] = {file->fd[APM_P32], file->fd[APM_M32], file->fd[APM_V32]};
+            t->chain = new WindowChain(t->io, fds, t->win, (size_t)dev->desc.page_elems * sizeof(float), batch_pages,
+                                       n_slots, (file->desc.flags & APM_POOL_FILE_DIRECT) != 0);
+        } catch (...) {  // threads or memory ran out: give back what the handle holds, report through the guard
+            free_tiered(t);
+            throw;
+        }
+        *out = t;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_tiered_destroy(apm_tiered* t) {
-    if (!t) return APM_OK;
-    (void)hipSetDevice(t->dev->desc.hip_device);
-    free_tiered(t);
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!t) return APM_OK;
+        (void)hipSetDevice(t->dev->desc.hip_device);
+        free_tiered(t);
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_tiered_set_range(apm_tiered* t, int64_t first_page, int64_t n_pages) {
-    if (!t) return fail(APM_EINVAL, "NULL handle");
-    if (first_page < 0 || first_page > t->dev->desc.n_pages) return fail(APM_ERANGE, "first_page out of range");
-    int rc = join_updater(t);
-    if (rc != APM_OK) return rc;
-    t->first_page = first_page;
-    t->page_count = n_pages < 0 ? -1 : n_pages;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!t) return fail(APM_EINVAL, "NULL handle");
+        if (first_page < 0 || first_page > t->dev->desc.n_pages) return fail(APM_ERANGE, "first_page out of range");
+        int rc = join_updater(t);
+        if (rc != APM_OK) return rc;
+        t->first_page = first_page;
+        t->page_count = n_pages < 0 ? -1 : n_pages;
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_tiered_io_bytes(apm_tiered* t, int64_t* bytes_read, int64_t* bytes_written) {
-    if (!t) return fail(APM_EINVAL, "NULL handle");
-    t->chain->io_bytes(bytes_read, bytes_written);
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!t) return fail(APM_EINVAL, "NULL handle");
+        t->chain->io_bytes(bytes_read, bytes_written);
+        return APM_OK;
+    });
 }
 
 extern "C" int apm_tiered_step(apm_tiered* t, int64_t step, const apm_hyper* hyper, float* grad_norm,
                                uint8_t* skip_mask, void* stream) {
-    if (!t) return fail(APM_EINVAL, "NULL handle");
-    if (!t->dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
-    int rc = join_updater(t);
-    if (rc != APM_OK) return rc;
-    return tiered_run(t, step, hyper, nullptr, grad_norm, skip_mask, true, static_cast<hipStream_t>(stream));
+    return apm::guarded([&]() -> int {
+        if (!t) return fail(APM_EINVAL, "NULL handle");
+        if (!t->dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+        int rc = join_updater(t);
+        if (rc != APM_OK) return rc;
+        return tiered_run(t, step, hyper, nullptr, grad_norm, skip_mask, true, static_cast<hipStream_t>(stream));
+    });
 }
 
 extern "C" int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const apm_hyper* hyper,
                                        void* stream) {
-    if (!t) return fail(APM_EINVAL, "NULL handle");
-    apm_pool* dev = t->dev;
-    if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
-    AdamwLaunch probe{};
-    int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
-    if (rc != APM_OK) return rc;
-    APM_HIP(hipSetDevice(dev->desc.hip_device));
-    rc = ensure_delayed(dev);
-    if (rc != APM_OK) return rc;
-    for (int k = 0; k < 2 && new_g16; ++k)  // the updater reads the halves with no stream-side guard
-        if (new_g16 == static_cast<const void*>(dev->gbuf[k])) return fail(APM_EINVAL, "the zero-copy hand-over (apm_delayed_grad_buffer) is not available with file-resident state: pass the producer's own buffer");
-    // One updater at a time: the update handed over by the previous call must have finished
-    // before the next one starts (and before the half it read is staged into again).
-    rc = join_updater(t);
-    if (rc != APM_OK) return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dev->buffered) {
-        const int k = dev->cur;
-        dev->applied += 1;
-        dev->buffered = false;
-        t->updater_hyper = *hyper;
-        const int64_t step_no = dev->applied;
-        const uint16_t* g16 = dev->gbuf[k];
-        hipEvent_t staged = dev->ev_staged[k];
-        float* norm = dev->delayed_norm;
-        uint8_t* skip = dev->delayed_skip;
-        t->updater_running = true;
-        t->updater = std::thread([t, step_no, g16, staged, norm, skip] {
-            // Alg. 2's updating actor: waits for the handed-over gradient, then fetches, updates
-            // and offloads the states batch by batch.
-            int rc2 = APM_OK;
-            if (hipSetDevice(t->dev->desc.hip_device) != hipSuccess || hipEventSynchronize(staged) != hipSuccess)
-                rc2 = fail(APM_EDEVICE, "waiting for the staged gradient failed");
-            if (rc2 == APM_OK) rc2 = tiered_run(t, step_no, &t->updater_hyper, g16, norm, skip, false, nullptr);
-            t->updater_rc = rc2;
-            if (rc2 != APM_OK) t->updater_err = apm_last_error();
-        });
-    }
-    if (!new_g16) return join_updater(t);  // flush: the update has completed when this returns
-    const int nxt = dev->cur ^ 1;
-    const int64_t N = (int64_t)dev->plan.pages.size();
-    const size_t bytes = (size_t)N * (size_t)dev->desc.page_elems * 2u;
-    APM_HIP(hipMemcpyAsync(dev->gbuf[nxt], new_g16, bytes, hipMemcpyDeviceToDevice, s));
-    APM_HIP(hipEventRecord(dev->ev_staged[nxt], s));
-    dev->cur = nxt;
-    dev->buffered = true;
-    return APM_OK;
+    return apm::guarded([&]() -> int {
+        if (!t) return fail(APM_EINVAL, "NULL handle");
+        apm_pool* dev = t->dev;
+        if (!dev->has_layout) return fail(APM_ESTATE, "the GPU pool has no layout");
+        AdamwLaunch probe{};
+        int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
+        if (rc != APM_OK) return rc;
+        APM_HIP(hipSetDevice(dev->desc.hip_device));
+        rc = ensure_delayed(dev);
+        if (rc != APM_OK) return rc;
+        for (int k = 0; k < 2 && new_g16; ++k)  // the updater reads the halves with no stream-side guard
+            if (new_g16 == static_cast<const void*>(dev->gbuf[k])) return fail(APM_EINVAL, "the zero-copy hand-over (apm_delayed_grad_buffer) is not available with file-resident state: pass the producer's own buffer");
+        // One updater at a time: the update handed over by the previous call must have finished
+        // before the next one starts (and before the half it read is staged into again).
+        rc = join_updater(t);
+        if (rc != APM_OK) return rc;
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        if (dev->buffered) {
+            const int k = dev->cur;
+            t->updater_hyper = *hyper;
+            const int64_t step_no = dev->applied + 1;
+            const uint16_t* g16 = dev->gbuf[k];
+            hipEvent_t staged = dev->ev_staged[k];
+            float* norm = dev->delayed_norm;
+            uint8_t* skip = dev->delayed_skip;
+            try {
+                t->updater = std::thread([t, step_no, g16, staged, norm, skip] {
+                    // Alg. 2's updating actor: waits for the handed-over gradient, then fetches, updates
+                    // and offloads the states batch by batch.
+                    t->updater_rc = guarded([&]() -> int {
+                        if (hipSetDevice(t->dev->desc.hip_device) != hipSuccess || hipEventSynchronize(staged) != hipSuccess)
+                            return fail(APM_EDEVICE, "waiting for the staged gradient failed");
+                        return tiered_run(t, step_no, &t->updater_hyper, g16, norm, skip, false, nullptr);
+                    });
+                    if (t->updater_rc != APM_OK) t->updater_err = apm_last_error();
+                });
+            } catch (const std::system_error& e) {  // nothing has changed: the gradient stays buffered
+                return fail(APM_EDEVICE, "starting the updater thread failed: %s", e.what());
+            }
+            t->updater_running = true;
+            dev->applied = step_no;
+            dev->buffered = false;
+        }
+        if (!new_g16) return join_updater(t);  // flush: the update has completed when this returns
+        const int nxt = dev->cur ^ 1;
+        const int64_t N = (int64_t)dev->plan.pages.size();
+        const size_t bytes = (size_t)N * (size_t)dev->desc.page_elems * 2u;
+        APM_HIP(hipMemcpyAsync(dev->gbuf[nxt], new_g16, bytes, hipMemcpyDeviceToDevice, s));
+        APM_HIP(hipEventRecord(dev->ev_staged[nxt], s));
+        dev->cur = nxt;
+        dev->buffered = true;
+        return APM_OK;
+    });
 }
