@@ -480,7 +480,9 @@ int apm_tiered_step(apm_tiered* t, int64_t step, const apm_hyper* hyper, float* 
  * half of the GPU pool's ping-pong buffer on `stream` and returns; the caller produces the next
  * gradient while the updater fetches, updates and offloads the states.  new_g16 == NULL flushes:
  * the buffered gradient is applied and the call returns when that update is complete.
- * N calls + flush leave exactly the state of N apm_tiered_step calls.  While an update runs, the
+ * N calls + flush leave exactly the state of N apm_tiered_step calls with the same per-call
+ * hyper-parameters: a gradient is applied with the values of the call that brought it (copied
+ * then), not of the call that starts its update.  While an update runs, the
  * GPU pool's per-page scratch is in use: no other step call on that pool (apm_delayed_accumulate
  * into the gradient being collected is fine: Alg. 2's buffering actor).  The applied counter
  * and apm_delayed_set_outputs are those of the GPU pool; apm_delayed_grad_buffer is not available
@@ -499,9 +501,14 @@ int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const apm_hyper*
  *   (2) enqueues, on `stream`, the staging of new_g16 into the other half of the pool's ping-pong
  *       gradient buffer; the caller may reuse new_g16 once `stream` has passed this point.
  * new_g16 == NULL flushes: applies the buffered gradient if any and makes `stream` wait for the
- * update stream.  The page list (as in apm_page_adamw_step) must be the same on every call
- * between two flushes.  P16 is rewritten asynchronously by the update stream: a reader that does
- * not flush may see parameters one step stale, which is the mechanism's stated trade-off.
+ * update stream.
+ * A gradient is buffered together with the page list (as in apm_page_adamw_step; copied) and the
+ * hyper-parameters (copied) of the call that brings it, and is applied with those one call later:
+ * under a learning-rate schedule gradient t meets lr_t although call t+1 enqueues its update, so N
+ * calls and a flush leave exactly the state of N apm_page_adamw_step calls with the same
+ * per-call arguments.  The hyper-parameters passed with a flush are validated and otherwise unused.
+ * P16 is rewritten asynchronously by the update stream: a reader that does not flush may see
+ * parameters one step stale, which is the mechanism's stated trade-off.
  */
 int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
                      const apm_hyper* hyper, void* stream);
@@ -513,7 +520,8 @@ int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_pages, cons
  * new_g16 (page layout, as above; NULL flushes).  In direct mode the update occupies 64
  * wavefronts, so the producer's kernels on `stream` keep the rest of the GPU.  The ping-pong
  * halves, the applied counter, apm_delayed_grad_buffer, apm_delayed_accumulate and
- * apm_delayed_set_outputs are those of the streamer's GPU pool.
+ * apm_delayed_set_outputs are those of the streamer's GPU pool.  As with apm_step_delayed, a
+ * gradient is applied with the hyper-parameters of the call that brought it.
  */
 int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, const apm_hyper* hyper,
                               void* stream);

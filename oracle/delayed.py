@@ -5,9 +5,16 @@ the *buffered* gradient g' ("Update p32, m32, v32 via g'16"), then the buffer is
 16-bit parameters are refreshed by the cast; a newly produced gradient is accumulated into the
 cleared buffer (0 + g = g exactly, one gradient per update).  Each call applies the gradient handed
 over by the previous call; a call without a gradient flushes the buffer.
+
+A buffered gradient carries the hyper-parameters and the page list of the call that handed it over:
+it is the gradient of that iteration, so it is applied with that iteration's learning rate, decay
+and clipping even though the update runs one call later (otherwise N calls plus a flush would not
+equal N synchronous steps under a learning-rate schedule).  The hyper-parameters of the applying
+call, and of a flush, belong to the gradient that call brings (none for a flush).
 """
 from __future__ import annotations
 
+from dataclasses import replace
 from typing import Optional, Sequence
 
 import numpy as np
@@ -19,6 +26,8 @@ class DelayedStepper:
     def __init__(self, state: PagedAdamWState):
         self.state = state
         self.buffered: Optional[np.ndarray] = None   # g' (bf16 bits), None = empty
+        self.buffered_h: Optional[Hyper] = None       # hyper-parameters handed over with g'
+        self.buffered_pages: Optional[Sequence[int]] = None
         self.applied = 0                              # number of updates applied so far
 
     def step(self, new_g16_pages: Optional[np.ndarray], h: Hyper,
@@ -27,8 +36,13 @@ class DelayedStepper:
         out = None
         if self.buffered is not None:
             self.applied += 1
-            out = self.state.step(self.buffered, self.applied, h, pages)
-        self.buffered = None if new_g16_pages is None else new_g16_pages.copy()
+            out = self.state.step(self.buffered, self.applied, self.buffered_h, self.buffered_pages)
+        if new_g16_pages is None:
+            self.buffered = self.buffered_h = self.buffered_pages = None
+        else:
+            self.buffered = new_g16_pages.copy()
+            self.buffered_h = replace(h)      # a copy: the caller may change its own object
+            self.buffered_pages = None if pages is None else list(pages)
         return out
 
     def accumulate(self, g16_pages: np.ndarray) -> None:

@@ -204,6 +204,12 @@ struct apm_pool {
     int cur = 0;
     bool buffered = false;
     int64_t applied = 0;
+    // What the buffered gradient was handed over with: it is applied, one call later, with the
+    // hyper-parameters and the page list of the call that brought it.
+    apm_hyper buf_hyper{};
+    std::vector<int64_t> buf_pages;  // copy of the caller's list (unused if buf_pages_null)
+    bool buf_pages_null = true;      // the call listed pages [0, buf_n_pages)
+    int64_t buf_n_pages = 0;
     float* delayed_norm = nullptr;
     uint8_t* delayed_skip = nullptr;
 
@@ -231,11 +237,14 @@ int file_page_copy(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_p
 
 // The one-step-stale hand-over shared by apm_step_delayed and the streamer's delayed step:
 // applies the buffered gradient through `apply` (which enqueues one update reading the gradient
-// half it is given, with the step number it is given, on the pool's update stream), then stages
-// new_g16 into the other half on `caller` (nullptr = flush).
-using DelayedApply = std::function<int(const uint16_t* g16, int64_t step, hipStream_t upd_stream)>;
+// half it is given, with the step number, page list and hyper-parameters it is given -- those of
+// the call that handed that gradient over -- on the pool's update stream), then stages new_g16
+// into the other half on `caller` together with this call's page list and hyper-parameters
+// (nullptr = flush).
+using DelayedApply = std::function<int(const uint16_t* g16, int64_t step, hipStream_t upd_stream,
+                                       const int64_t* pages, int64_t n_pages, const apm_hyper* hyper)>;
 int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
-                 hipStream_t caller, const DelayedApply& apply);
+                 const apm_hyper* hyper, hipStream_t caller, const DelayedApply& apply);
 
 // Brackets one kernel launch with events when the pool's timing is on.
 struct ScopedTiming {

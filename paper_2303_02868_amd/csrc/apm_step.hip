@@ -253,7 +253,8 @@ int ensure_delayed(apm_pool* pool) {
 static int apply_buffered(apm_pool* pool, const DelayedApply& apply) {
     const int k = pool->cur;
     APM_HIP(hipStreamWaitEvent(pool->upd_stream, pool->ev_staged[k], 0));
-    int rc = apply(pool->gbuf[k], pool->applied + 1, pool->upd_stream);
+    int rc = apply(pool->gbuf[k], pool->applied + 1, pool->upd_stream,
+                   pool->buf_pages_null ? nullptr : pool->buf_pages.data(), pool->buf_n_pages, &pool->buf_hyper);
     if (rc != APM_OK) return rc;
     pool->applied += 1;
     APM_HIP(hipEventRecord(pool->ev_applied[k], pool->upd_stream));
@@ -262,7 +263,7 @@ static int apply_buffered(apm_pool* pool, const DelayedApply& apply) {
 }
 
 int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
-                 hipStream_t s, const DelayedApply& apply) {
+                 const apm_hyper* hyper, hipStream_t s, const DelayedApply& apply) {
     APM_HIP(hipSetDevice(pool->desc.hip_device));
     int rc = ensure_delayed(pool);
     if (rc != APM_OK) return rc;
@@ -280,6 +281,10 @@ int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const vo
     // two calls ago, which must have finished before it is overwritten.
     const int nxt = pool->cur ^ 1;
     const size_t pb = (size_t)pool->desc.page_elems * 2u;
+    // The gradient travels with the list and the hyper-parameters of this call (copied before
+    // anything is enqueued: an allocation failure leaves the pool as it was).
+    std::vector<int64_t> list_copy;
+    if (pages) list_copy.assign(pages, pages + n_pages);
     const char* src = static_cast<const char*>(new_g16);
     char* dst = reinterpret_cast<char*>(pool->gbuf[nxt]);
     // A producer that wrote its gradient straight into the half handed out by
@@ -295,6 +300,10 @@ int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const vo
         k += len;
     }
     APM_HIP(hipEventRecord(pool->ev_staged[nxt], s));
+    pool->buf_hyper = *hyper;
+    pool->buf_pages.swap(list_copy);
+    pool->buf_pages_null = pages == nullptr;
+    pool->buf_n_pages = n_pages;
     pool->cur = nxt;
     pool->buffered = true;
     return APM_OK;
@@ -338,9 +347,10 @@ extern "C" int apm_step_delayed(apm_pool* pool, const int64_t* pages, int64_t n_
         if (pages)
             for (int64_t k = 0; k < n_pages; ++k)
                 if (pages[k] < 0 || pages[k] >= pool->desc.n_pages) return fail(APM_ERANGE, "pages[%lld] out of range", (long long)k);
-        return delayed_call(pool, pages, n_pages, new_g16, static_cast<hipStream_t>(stream),
-                            [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
-                                return enqueue_step(pool, pages, n_pages, step, hyper, g16, pool->delayed_norm,
+        return delayed_call(pool, pages, n_pages, new_g16, hyper, static_cast<hipStream_t>(stream),
+                            [&](const uint16_t* g16, int64_t step, hipStream_t upd, const int64_t* b_pages,
+                                int64_t b_n, const apm_hyper* b_hyper) {
+                                return enqueue_step(pool, b_pages, b_n, step, b_hyper, g16, pool->delayed_norm,
                                                     pool->delayed_skip, upd);
                             });
     });

@@ -444,9 +444,10 @@ extern "C" int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, c
         int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
         if (rc != APM_OK) return rc;
         const int64_t N = (int64_t)dev->plan.pages.size();
-        return delayed_call(dev, nullptr, N, new_g16, static_cast<hipStream_t>(stream),
-                            [&](const uint16_t* g16, int64_t step, hipStream_t upd) {
-                                return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, hyper, dev->delayed_norm,
+        return delayed_call(dev, nullptr, N, new_g16, hyper, static_cast<hipStream_t>(stream),
+                            [&](const uint16_t* g16, int64_t step, hipStream_t upd, const int64_t*, int64_t,
+                                const apm_hyper* b_hyper) {
+                                return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, b_hyper, dev->delayed_norm,
                                                     dev->delayed_skip, upd, g16);
                             });
     });

@@ -347,7 +347,7 @@ extern "C" int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const
         hipStream_t s = static_cast<hipStream_t>(stream);
         if (dev->buffered) {
             const int k = dev->cur;
-            t->updater_hyper = *hyper;
+            t->updater_hyper = dev->buf_hyper;  // the values the buffered gradient was handed over with
             const int64_t step_no = dev->applied + 1;
             const uint16_t* g16 = dev->gbuf[k];
             hipEvent_t staged = dev->ev_staged[k];
@@ -377,6 +377,10 @@ extern "C" int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const
         const size_t bytes = (size_t)N * (size_t)dev->desc.page_elems * 2u;
         APM_HIP(hipMemcpyAsync(dev->gbuf[nxt], new_g16, bytes, hipMemcpyDeviceToDevice, s));
         APM_HIP(hipEventRecord(dev->ev_staged[nxt], s));
+        dev->buf_hyper = *hyper;
+        dev->buf_pages.clear();
+        dev->buf_pages_null = true;
+        dev->buf_n_pages = N;
         dev->cur = nxt;
         dev->buffered = true;
         return APM_OK;

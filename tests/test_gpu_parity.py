@@ -161,6 +161,50 @@ def test_delayed_small_with_page_list_and_outputs():
     dp.destroy()
 
 
+def test_delayed_applies_each_gradient_with_the_hyper_and_page_list_it_came_with():
+    # a learning-rate / decay / clip schedule and a page list that changes from call to call:
+    # N delayed calls + flush == N synchronous steps bit for bit, and == the oracle's stepper
+    E = 16384
+    numels = [3 * E + 5, 100, 2 * E, 9000, E]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=12, sigma_g=5e-3)
+    n, n_t = model.plan.n_pages, len(specs)
+    T = 6
+    hs = [oracle.Hyper(lr=1e-4 * (t + 1), weight_decay=0.01 * (t % 3), max_grad_norm=0.2 * (t + 1))
+          for t in range(T)]
+    lists = [None, [0, 2, 5], [1], None, [6, 0, 3, 1], [4]]
+    a = DevicePool(n, E)   # synchronous
+    b = DevicePool(n, E)   # one step stale
+    for dp in (a, b):
+        apm.apm_pack_tensors(dp.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    gbuf = DevicePool(n, E, states=(apm.APM_G16,))
+    pages = list(range(n))
+    used = [model.plan.pages[p].used for p in pages]
+    st = oracle.PagedAdamWState(model.host_pages(model.p_flat, pages).view(np.float32), used)
+    d = oracle.DelayedStepper(st)
+    for t in range(T):
+        g = model.grad_flat(t + 1)
+        apm.apm_pack_tensors(a.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(gbuf.pool, apm.APM_G16, model.tensors(g), n_t)
+        lst = lists[t]
+        k = n if lst is None else len(lst)
+        apm.apm_page_adamw_step(a.pool, lst, k, t + 1, to_hyper(hs[t]))
+        apm.apm_step_delayed(b.pool, lst, k, gbuf.reg[apm.APM_G16], to_hyper(hs[t]))
+        torch.cuda.synchronize()
+        d.step(model.host_pages(g, pages), hs[t], lst)
+    flush_h = to_hyper(oracle.Hyper(lr=7.0, weight_decay=0.5))   # belongs to no gradient
+    apm.apm_step_delayed(b.pool, None, n, None, flush_h)
+    d.step(None, oracle.Hyper(lr=7.0))
+    torch.cuda.synchronize()
+    assert apm.apm_delayed_applied(b.pool) == T
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32, apm.APM_P16):
+        assert torch.equal(a.reg[s_].view(torch.int16), b.reg[s_].view(torch.int16)), f"state {s_}: delayed != sync"
+    for name, s_, want in (("p", apm.APM_P32, st.p), ("m", apm.APM_M32, st.m), ("v", apm.APM_V32, st.v)):
+        check_state_close(name, b.rows_f32(s_, pages), want, used)
+    for dp in (a, b, gbuf):
+        dp.destroy()
+
+
 def test_delayed_zero_copy_handover_equals_sync():
     # the producer writes its gradient pages straight into the half handed out by
     # apm_delayed_grad_buffer (here: by packing into a pool whose G16 class aliases that half)

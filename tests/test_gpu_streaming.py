@@ -395,7 +395,9 @@ def test_streamer_delayed_calls_plus_flush_equal_synchronous_steps(mode):
     f, E = synth.WORKLOADS["gpt2_small_124m"]
     model = Model(f(), E, seed=6)
     n_pages, n_t = model.plan.n_pages, len(model.specs)
-    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    # a learning-rate schedule: gradient t must meet lr_t although call t+1 enqueues its update
+    hys = [to_hyper(oracle.Hyper(max_grad_norm=1.0, lr=1e-4 * t, weight_decay=0.01 * (t % 2))) for t in range(6)]
+    hy = hys[0]
     init = DevicePool(n_pages, E, states=(apm.APM_P32,))
     apm.apm_pack_tensors(init.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
     sides = []
@@ -417,9 +419,9 @@ def test_streamer_delayed_calls_plus_flush_equal_synchronous_steps(mode):
     for t in range(1, steps + 1):
         g = model.grad_flat(t)
         apm.apm_pack_tensors(dev_a.pool, apm.APM_G16, model.tensors(g), n_t)
-        apm.apm_streamer_step(st_a, t, hy, norm_a, None)
+        apm.apm_streamer_step(st_a, t, hys[t], norm_a, None)
         apm.apm_pack_tensors(produce.pool, apm.APM_G16, model.tensors(g), n_t)
-        apm.apm_streamer_step_delayed(st_b, produce.reg[apm.APM_G16], hy)
+        apm.apm_streamer_step_delayed(st_b, produce.reg[apm.APM_G16], hys[t])
         assert apm.apm_delayed_applied(dev_b.pool) == t - 1
         torch.cuda.synchronize()
     apm.apm_streamer_step_delayed(st_b, None, hy)
@@ -581,7 +583,8 @@ def test_file_tier_delayed_calls_plus_flush_equal_synchronous_steps(tmp_path):
     f, E = synth.WORKLOADS["gpt2_small_124m"]
     model = Model(f(), E, seed=9)
     n_pages, n_t = model.plan.n_pages, len(model.specs)
-    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    hys = [to_hyper(oracle.Hyper(max_grad_norm=1.0, lr=1e-4 * t, weight_decay=0.01 * (t % 2))) for t in range(6)]
+    hy = hys[0]
     init = DevicePool(n_pages, E, states=(apm.APM_P32,))
     apm.apm_pack_tensors(init.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
     host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=1 << apm.APM_P32)
@@ -604,9 +607,9 @@ def test_file_tier_delayed_calls_plus_flush_equal_synchronous_steps(tmp_path):
     for t in range(1, steps + 1):
         g = model.grad_flat(t)
         apm.apm_pack_tensors(dev_a.pool, apm.APM_G16, model.tensors(g), n_t)
-        apm.apm_tiered_step(tier_a, t, hy, norm_a, None)
+        apm.apm_tiered_step(tier_a, t, hys[t], norm_a, None)
         apm.apm_pack_tensors(produce.pool, apm.APM_G16, model.tensors(g), n_t)
-        apm.apm_tiered_step_delayed(tier_b, produce.reg[apm.APM_G16], hy)
+        apm.apm_tiered_step_delayed(tier_b, produce.reg[apm.APM_G16], hys[t])
         assert apm.apm_delayed_applied(dev_b.pool) == t - 1
     with pytest.raises(apm.ApmError) as e:          # the ping-pong halves are not handed out here
         apm.apm_tiered_step_delayed(tier_b, apm.apm_delayed_grad_buffer(dev_b.pool), hy)

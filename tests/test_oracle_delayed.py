@@ -51,6 +51,35 @@ def test_delayed_plus_flush_equals_sync():
     assert state_bytes(st) == snaps[T]
 
 
+def test_gradient_is_applied_with_the_hyper_and_page_list_it_came_with():
+    """A learning-rate / decay / clip schedule and a page list that changes from call to call: the
+    gradient of call t is applied (during call t+1) with call t's values, so N calls plus a flush
+    still equal N synchronous steps; the values passed with a flush are not used."""
+    T = 6
+    p32, used = make(6)
+    gs = grads(7, T, p32.shape)
+    hs = [oracle.Hyper(lr=1e-4 * (t + 1), weight_decay=0.01 * (t % 3), max_grad_norm=0.002 * (t + 1))
+          for t in range(T)]
+    lists = [None, [0, 2], [1], None, [2, 0, 1], [0]]
+
+    sync = oracle.PagedAdamWState(p32, used)
+    snaps = [state_bytes(sync)]
+    for t in range(T):
+        sync.step(gs[t], t + 1, hs[t], lists[t])
+        snaps.append(state_bytes(sync))
+    assert len(set(snaps)) == T + 1
+
+    st = oracle.PagedAdamWState(p32, used)
+    d = oracle.DelayedStepper(st)
+    for t in range(T):
+        h = oracle.Hyper(**vars(hs[t]))
+        d.step(gs[t], h, lists[t])
+        h.lr = 123.0                                  # the caller's object is its own again
+        assert state_bytes(st) == snaps[t]
+    d.step(None, oracle.Hyper(lr=7.0, weight_decay=0.5))   # flush: its values belong to no gradient
+    assert state_bytes(st) == snaps[T]
+
+
 def test_buffered_gradient_is_a_copy():
     p32, used = make(2)
     st = oracle.PagedAdamWState(p32, used)
