@@ -249,6 +249,30 @@ int apm_page_adamw_step_fused(apm_pool* pool, const int64_t* pages, int64_t n_pa
                               const apm_tensor* p16_tensors, int64_t n_tensors, float* grad_norm,
                               uint8_t* skip_mask, void* stream);
 
+/*
+ * apm_page_adamw_step for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same kernels and bit-identical results for the pages
+ * [0, n_pages) of a GPU pool that stores all five classes (no page list; every page is launched
+ * with a full page's grid, so nearly empty pages cost idle workgroups here).  The per-page scratch
+ * of the reduce and update kernels (page records, per-slice sums of squares and non-zero flags)
+ * lives in a fixed device array of apm_noalloc_scratch_bytes() bytes that the library holds on
+ * every GPU it runs on until the process ends, instead of buffers the pool allocates on first use;
+ * the call performs no hipMalloc / hipFree, creates no events or streams and allocates no host
+ * memory (apm_pool_set_timing does not cover it).  The array's device address is resolved on the
+ * first call on each device.
+ * All calls on one GPU share that array and it keeps the last call's contents (every entry a call
+ * reads it has written before, nothing needs clearing): calls that overlap on one GPU -- on
+ * different streams, or from different pools -- race; order them on one stream or with events.
+ * Errors: as apm_page_adamw_step; APM_ERANGE if n_pages exceeds apm_noalloc_max_pages(page_elems)
+ * (the scratch holds 32 + 12 * ceil(page_elems / 16384) bytes per page: 5241 pages of 2^20
+ * elements); nothing is enqueued then.
+ */
+int apm_page_adamw_step_noalloc(apm_pool* pool, int64_t n_pages, int64_t step,
+                                const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,
+                                void* stream);
+size_t apm_noalloc_scratch_bytes(void);
+int64_t apm_noalloc_max_pages(int64_t page_elems);
+
 /* ---- page movement (Page listing: move; Sec. 5 "Allocator": asynchronous GPU-CPU copies) --- */
 
 /*

@@ -33,6 +33,7 @@ EXPORTS = [
     "apm_page_copy_async",
     "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_io_bytes", "apm_tiered_set_range", "apm_streamer_set_page_count", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_cache_pages_that_fit", "apm_streamer_set_host_first_page", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
+    "apm_page_adamw_step_noalloc", "apm_noalloc_scratch_bytes", "apm_noalloc_max_pages",
 ]
 
 
@@ -112,6 +113,11 @@ def lib() -> C.CDLL:
     L.apm_page_adamw_step_fused.argtypes = [vp, P(i64), i64, i64, P(apm_hyper), P(apm_tensor),
                                             P(apm_tensor), i64, vp, vp, vp]
     L.apm_page_copy_async.argtypes = [vp, i64, vp, i64, i64, i32, vp]
+    L.apm_page_adamw_step_noalloc.argtypes = [vp, i64, i64, P(apm_hyper), vp, vp, vp]
+    L.apm_noalloc_scratch_bytes.argtypes = []
+    L.apm_noalloc_scratch_bytes.restype = C.c_size_t
+    L.apm_noalloc_max_pages.argtypes = [i64]
+    L.apm_noalloc_max_pages.restype = i64
     L.apm_schedule_plan.argtypes = [P(i64), P(i64), P(i64), i64, P(i64), i64, i64, i64, P(apm_task), P(i64), P(i64)]
     L.apm_streamer_step_scheduled.argtypes = [vp, P(apm_task), i64, P(i64), i64, i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_step_delayed.argtypes = [vp, vp, P(apm_hyper), vp]
@@ -309,6 +315,20 @@ def apm_page_adamw_step_fused(pool: Pool, pages: Optional[Sequence[int]], n_page
     _check(lib().apm_page_adamw_step_fused(pool.handle, arr, n_pages, step, C.byref(hyper),
                                            grad_tensors, p16_tensors, n_tensors, _ptr(grad_norm),
                                            _ptr(skip_mask), _stream(stream)))
+
+
+def apm_page_adamw_step_noalloc(pool: Pool, n_pages: int, step: int, hyper: apm_hyper,
+                                grad_norm=None, skip_mask=None, stream=None) -> None:
+    _check(lib().apm_page_adamw_step_noalloc(pool.handle, n_pages, step, C.byref(hyper),
+                                             _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
+
+
+def apm_noalloc_scratch_bytes() -> int:
+    return lib().apm_noalloc_scratch_bytes()
+
+
+def apm_noalloc_max_pages(page_elems: int) -> int:
+    return lib().apm_noalloc_max_pages(page_elems)
 
 
 def apm_page_copy_async(dst: Pool, dst_page: int, src: Pool, src_page: int, n_pages: int,

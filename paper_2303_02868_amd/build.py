@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libapm.so")
 SOURCES = ["apm_host.cpp", "apm_pool.hip", "apm_adamw.hip", "apm_copy.hip", "apm_step.hip",
-           "apm_stream.hip", "apm_tier.hip"]
+           "apm_stream.hip", "apm_tier.hip", "apm_noalloc.hip"]
 HEADERS = [os.path.join(CSRC, "apm_internal.h"), os.path.join(CSRC, "apm_io.h"), os.path.join(ROOT, "include", "apm.h")]
 # Packed-fp32 instruction selection is switched off for all device code.
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",

@@ -34,6 +34,34 @@ def test_library_exports_every_declared_function():
     assert lib.apm_last_error() is not None
 
 
+def test_fixed_scratch_of_the_allocation_free_step_is_a_symbol_the_runtime_can_look_up(tmp_path):
+    """apm_page_adamw_step_noalloc asks the runtime for the device address of a static device
+    array by its symbol.  The runtime finds symbols of the code object's dynamic symbol table only,
+    and aborts the process on one it cannot find, so the array must be emitted there (the compiler
+    does that for a static device variable host code refers to, unless attributes get in the
+    way).  Checked on the device code of that source file, compiled here."""
+    import shutil
+    import subprocess
+    hipcc = "/opt/rocm/bin/hipcc"
+    bundler = "/opt/rocm/llvm/bin/clang-offload-bundler"
+    readelf = "/opt/rocm/llvm/bin/llvm-readelf"
+    for tool in (hipcc, bundler, readelf):
+        if not os.path.exists(tool):
+            pytest.skip(f"{tool} not present")
+    src = os.path.join(ROOT, "paper_2303_02868_amd", "csrc", "apm_noalloc.hip")
+    obj, elf = str(tmp_path / "dev.o"), str(tmp_path / "dev.elf")
+    subprocess.run([hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "--cuda-device-only", "-c",
+                    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                    "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(src), src, "-o", obj],
+                   check=True, capture_output=True)
+    subprocess.run([bundler, "--unbundle", "--type=o", f"--input={obj}", f"--output={elf}",
+                    "--targets=hipv4-amdgcn-amd-amdhsa--gfx950"], check=True, capture_output=True)
+    out = subprocess.run([readelf, "--dyn-syms", elf], check=True, capture_output=True, text=True).stdout
+    rows = [l.split() for l in out.splitlines() if l.split()[-1:] and l.split()[-1].endswith("scratch")]
+    assert rows, "the scratch array is not in the code object's dynamic symbol table:\n" + out
+    assert rows[0][3] == "OBJECT" and rows[0][4] == "GLOBAL" and int(rows[0][2]) == apm.apm_noalloc_scratch_bytes()
+
+
 def segs_of(plan):
     return [(s.tensor, s.tensor_off, s.page, s.page_off, s.n) for s in plan.segments]
 
