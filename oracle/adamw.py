@@ -5,6 +5,7 @@ The arithmetic lives in page_adamw.c; this file only marshals numpy arrays.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -40,7 +41,9 @@ class Hyper:
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(_build.build())
+        # ORACLE_LIBRARY: another build of page_adamw.c (the mutation test loads damaged copies
+        # this way to show that the pins catch them; it never edits the tracked source)
+        L = C.CDLL(os.environ.get("ORACLE_LIBRARY") or _build.build())
         L.oracle_bf16_rne.restype = C.c_uint16
         L.oracle_bf16_rne.argtypes = [C.c_uint32]
         L.oracle_bf16_rne_array.restype = None

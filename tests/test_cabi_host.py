@@ -82,6 +82,17 @@ def test_planner_matches_oracle_on_boundary_sizes_and_workloads():
         assert got.n_pages == want.n_pages
 
 
+def test_planner_reproduces_the_hand_worked_layout_with_two_handovers(golden_dir):
+    # the library's planner against the layout worked on paper, not against the oracle's planner:
+    # a misreading of the packing rule shared by the two planners would not get past this
+    from test_oracle_packer import read_worked_layout
+    E, numels, segs, pages, total = read_worked_layout(os.path.join(golden_dir, "packer_worked_layout_two_handovers.txt"))
+    res = apm.apm_pack_plan(E, numels)
+    assert res.segments == segs
+    assert res.n_pages == len(pages)
+    assert abs(res.fragmentation - (1 - total / (len(pages) * E))) < 1e-15
+
+
 def test_planner_argument_errors():
     L = apm.lib()
     n_segs = ctypes.c_int64(0)

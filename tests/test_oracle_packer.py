@@ -1,6 +1,7 @@
 """The oracle packer against a hand-worked layout, the page invariants the paper states, brute
 force over boundary sizes, and the pack -> unpack identity."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -38,6 +39,40 @@ def test_hand_worked_layout():
     assert plan.pages[2].tensor_id == [0, 2] and plan.pages[2].tensor_elems == [22, 40]
     assert plan.pages[3].tensor_id == [1, -1]
     assert plan.fragmentation == pytest.approx(1 - 397 / (9 * 64))
+
+
+def read_worked_layout(path):
+    E, numels, segs, pages, total = None, None, [], [], None
+    for line in open(path):
+        w = line.split()
+        if not w or w[0].startswith("#"):
+            continue
+        if w[0] == "E":
+            E = int(w[1])
+        elif w[0] == "numels":
+            numels = [int(x) for x in w[1:]]
+        elif w[0] == "seg":
+            segs.append(tuple(int(x) for x in w[1:]))
+        elif w[0] == "page":
+            pages.append(tuple(int(x) for x in w[1:]))
+        elif w[0] == "total":
+            total = int(w[1])
+    return E, numels, segs, pages, total
+
+
+def test_second_hand_worked_layout_two_handovers_in_a_row_and_a_page_aligned_tail(golden_dir):
+    # worked on paper (the file says how): an open page handed from tensor to tensor twice in a
+    # row, an empty tensor, a small tensor that must not close the open page, numel == E starting
+    # inside an open page, and a tensor whose end falls exactly on a page end (no open page after)
+    Ew, numels, segs, pages, total = read_worked_layout(os.path.join(golden_dir, "packer_worked_layout_two_handovers.txt"))
+    plan = oracle.plan_pack(numels, Ew)
+    assert seg_tuples(plan) == segs
+    assert plan.n_pages == len(pages) == 12
+    got = [(p.used, p.tensor_id[0], p.tensor_id[1], p.tensor_elems[0], p.tensor_elems[1]) for p in plan.pages]
+    assert got == pages
+    assert plan.total_elems == total == sum(numels)
+    assert plan.fragmentation == pytest.approx(1 - total / (12 * Ew))
+    check_invariants(numels, plan)
 
 
 def check_invariants(numels, plan):
