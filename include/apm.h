@@ -294,7 +294,7 @@ int apm_page_copy_async(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t 
  * n_slots: staging slots in HBM for the staged mode (>= 2); each holds batch_pages pages of the
  *          three fp32 classes.
  * The streamer starts in APM_STREAM_DIRECT if the GPU can address the host pool's memory (pinned
- * memory: always), else in APM_STREAM_STAGED; see apm_streamer_set_mode.
+ * memory: always), else in APM_STREAM_STAGED_DMA; see apm_streamer_set_mode.
  */
 int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool* dev, int64_t batch_pages,
                         int n_slots);
@@ -308,24 +308,30 @@ int apm_streamer_destroy(apm_streamer* s);
  *     workgroup and so a CU.  One per workgroup moves data fastest; more per workgroup occupy
  *     fewer CUs for the duration of the step, which disturbs concurrent kernels of the caller
  *     less (measured beside dense matrix products: 128 wavefronts, 16 per workgroup).
- *   APM_STREAM_STAGED: the pipeline copy-in / update / copy-out through HBM staging slots on
- *     three streams.  Its staging memory, events and copy streams are set up when the mode is
- *     first selected: which stream pairs overlap a host-to-device with a device-to-host copy
- *     depends on the runtime, so short concurrent copies are timed on a few candidate streams
- *     (the default stream among them) and the best pair is kept; this takes some tens of
- *     milliseconds and synchronises the device.
- * Both modes give bit-identical results.  Takes effect from the next apm_streamer_step.
+ *   APM_STREAM_STAGED: the double-buffered pipeline through HBM staging slots.  While batch b is
+ *     updated in its slot, ONE copy kernel of the library (direct_wavefronts wavefronts, as above)
+ *     brings batch b+1 from its host pages into the next slot and takes batch b-1 from the
+ *     previous slot back to its host pages, both directions at once; with two slots the two
+ *     directions are two kernels, one after the other.  One copy stream and one compute stream.
+ *     The staging memory is allocated when a staged mode is first selected.
+ *   APM_STREAM_STAGED_DMA: the same slot ring moved by the runtime's asynchronous copies:
+ *     copy-in / update / copy-out on three streams.  Which stream pairs overlap a host-to-device
+ *     with a device-to-host copy depends on the runtime, so when this mode is first selected
+ *     short concurrent copies are timed on a few candidate streams (the default stream among
+ *     them) and the best pair is kept; this takes some tens of milliseconds and synchronises the
+ *     device.  The only mode for host memory the GPU cannot address.
+ * All modes give bit-identical results.  Takes effect from the next apm_streamer_step.
  * apm_streamer_get_mode returns the current mode (or a negative status).
  */
-enum apm_stream_mode { APM_STREAM_STAGED = 0, APM_STREAM_DIRECT = 1 };
+enum apm_stream_mode { APM_STREAM_STAGED = 0, APM_STREAM_DIRECT = 1, APM_STREAM_STAGED_DMA = 2 };
 int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_wavefronts,
                           int wavefronts_per_workgroup);
 int apm_streamer_get_mode(const apm_streamer* s);
 
 /*
- * One AdamW step over all pages in use.  Staged mode: for batch b, H2D(b+1) on the copy-in stream
- * runs beside update(b) on the compute stream and D2H(b-1) on the copy-out stream, ordered by
- * events.  Direct mode: one reduce pass and one update kernel on the compute stream.
+ * One AdamW step over all pages in use.  Staged modes: for batch b, the copy-in of batch b+1 and
+ * the copy-out of batch b-1 run beside update(b) on the compute stream, ordered by events.
+ * Direct mode: one reduce pass and one update kernel on the compute stream.
  * The work starts after everything enqueued on `stream` so far, and `stream` is made to wait for
  * the step's completion; the host does not block.  grad_norm / skip_mask as in
  * apm_page_adamw_step (device pointers, one entry per page in use, nullable).
@@ -333,7 +339,7 @@ int apm_streamer_get_mode(const apm_streamer* s);
 int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, float* grad_norm,
                       uint8_t* skip_mask, void* stream);
 
-/* GB/s the staged mode's stream calibration measured on 32 MiB copies (zeros before it ran):
+/* GB/s the staged-DMA mode's stream calibration measured on 32 MiB copies (zeros before it ran):
  * copy-in alone, copy-out alone, and each way with both running on the chosen pair (host
  * pointers, nullable). */
 int apm_streamer_probe_rates(const apm_streamer* s, double* h2d, double* d2h, double* duplex_each_way);
@@ -370,7 +376,7 @@ int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_model_page);
 int apm_streamer_set_page_count(apm_streamer* s, int64_t n_pages);
 
 /*
- * Measurement aid (staged mode only): the same pipeline (streams, events, copy sizes, slot reuse)
+ * Measurement aid (staged modes only): the same pipeline (streams, events, copy sizes, slot reuse)
  * with the kernels left out.  directions: 1 = copy-in only, 2 = copy-out only, 3 = both.  The data make a round
  * trip host -> staging -> host, so the host pool's contents are unchanged (with 2 alone, staging
  * contents left by an earlier step are written back: call it only after 1 or 3, or a full step).
@@ -422,22 +428,30 @@ int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* layer_pages,
  * list of apm_schedule_plan, or any list that passes the checks below) instead of the staged
  * mode's fixed slot ring.  The model's layers are consecutive page ranges: layer i owns pages
  * [layer_first_page[i], layer_first_page[i+1]) (n_layers + 1 host entries, from 0 to the number of
- * pages in use), and every page is accessed by its own layer only (the optimizer pass).  The GPU
+ * pages in use) and updates them when it computes.  last_access (host pointer, one entry per page
+ * in use, nullable = each page's own layer) is the trace the schedule was planned with: a page
+ * stays in GPU memory until the layer last_access[page] >= its own layer has computed.  The GPU
  * memory of the schedule is the streamer's staging memory: n_slots * batch_pages page slots of
  * 12 * page_elems bytes (p, m, v).  APM_TASK_MOVE_TO_GPU copies a page's fp32 classes from the
  * host pool into the lowest free slot; APM_TASK_COMPUTE runs the reduce and update kernels on its
- * layer's pages, copies them back to the host pool and frees their slots.  Movement tasks over
- * consecutive pages and slots are merged into one copy per class.
+ * layer's pages, then copies the pages whose last access it is back to the host pool and frees
+ * their slots.  Movement tasks over consecutive pages and slots with one trigger id are merged
+ * into one copy per class.
+ * Dispatch is event-driven (Sec. 5 "Unified Scheduler"): a movement task is issued only when
+ * execution has reached its trigger_id -- the layer before it has computed (trigger 0: the start
+ * of the step) -- and the slots it moves into have been written back; a compute starts when the
+ * movements of its pages have completed; a write-back when its compute has.
  * The schedule is replayed on the host first and nothing is enqueued if it is unsound:
  * APM_ENOMEM (a movement task finds no free slot), APM_ESTATE (a layer computes before all its
  * pages were moved; a resident cache is set), APM_EINVAL (layers out of order, a page moved twice,
- * pages or layers left over).  Results are bit-identical to the other modes.  Stream semantics as
- * apm_streamer_step; does not depend on the streamer's mode.
+ * pages or layers left over, a trigger id beyond the layers that precede the task in the list,
+ * last_access before a page's own layer).  Results are bit-identical to the other modes.  Stream
+ * semantics as apm_streamer_step; does not depend on the streamer's mode.
  */
 int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
-                                const int64_t* layer_first_page, int64_t n_layers, int64_t step,
-                                const apm_hyper* hyper, float* grad_norm, uint8_t* skip_mask,
-                                void* stream);
+                                const int64_t* layer_first_page, int64_t n_layers,
+                                const int64_t* last_access, int64_t step, const apm_hyper* hyper,
+                                float* grad_norm, uint8_t* skip_mask, void* stream);
 
 /* ---- third tier: FP32 states in files (the device map's SSD, Sec. 4.1; Alg. 2 fetches the
  *      states from SSD, updates them and offloads them back) ---------------------------------- */

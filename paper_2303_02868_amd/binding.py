@@ -20,7 +20,7 @@ APM_P32, APM_M32, APM_V32, APM_G16, APM_P16, APM_N_STATES = 0, 1, 2, 3, 4, 5
 APM_SKIP_NONE, APM_SKIP_UNTOUCHED = 0, 1
 APM_POOL_NO_ZERO = 1
 APM_POOL_FILE_DIRECT = 2
-APM_STREAM_STAGED, APM_STREAM_DIRECT = 0, 1
+APM_STREAM_STAGED, APM_STREAM_DIRECT, APM_STREAM_STAGED_DMA = 0, 1, 2
 APM_K_REDUCE, APM_K_UPDATE, APM_K_SEGCOPY, APM_N_KERNEL_CLASSES = 0, 1, 2, 3
 ALL_STATES = 0b11111
 FP32_STATES = 0b00111
@@ -119,7 +119,7 @@ def lib() -> C.CDLL:
     L.apm_noalloc_max_pages.argtypes = [i64]
     L.apm_noalloc_max_pages.restype = i64
     L.apm_schedule_plan.argtypes = [P(i64), P(i64), P(i64), i64, P(i64), i64, i64, i64, P(apm_task), P(i64), P(i64)]
-    L.apm_streamer_step_scheduled.argtypes = [vp, P(apm_task), i64, P(i64), i64, i64, P(apm_hyper), vp, vp, vp]
+    L.apm_streamer_step_scheduled.argtypes = [vp, P(apm_task), i64, P(i64), i64, P(i64), i64, P(apm_hyper), vp, vp, vp]
     L.apm_streamer_step_delayed.argtypes = [vp, vp, P(apm_hyper), vp]
     L.apm_file_pool_create.argtypes = [P(vp), C.c_char_p, i32, i64, i64, C.c_uint32, C.c_uint32]
     L.apm_tiered_create.argtypes = [P(vp), vp, vp, i64, i32, i32]
@@ -450,13 +450,15 @@ def apm_streamer_step(s: Streamer, step: int, hyper: apm_hyper, grad_norm=None, 
 
 
 def apm_streamer_step_scheduled(s: Streamer, tasks: Sequence, layer_first_page: Sequence[int], step: int,
-                                hyper: apm_hyper, grad_norm=None, skip_mask=None, stream=None) -> None:
+                                hyper: apm_hyper, grad_norm=None, skip_mask=None, stream=None,
+                                last_access: Optional[Sequence[int]] = None) -> None:
     """tasks: [(op, target, trigger_id), ...] as apm_schedule_plan returns them."""
     arr = (apm_task * max(1, len(tasks)))()
     for i, (op, target, trig) in enumerate(tasks):
         arr[i].op, arr[i].target, arr[i].trigger_id = op, target, trig
     lf, n1 = _i64_array(layer_first_page)
-    _check(lib().apm_streamer_step_scheduled(s.handle, arr, len(tasks), lf, n1 - 1, step, C.byref(hyper),
+    la = _i64_array(last_access)[0] if last_access is not None else None
+    _check(lib().apm_streamer_step_scheduled(s.handle, arr, len(tasks), lf, n1 - 1, la, step, C.byref(hyper),
                                              _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
 
 

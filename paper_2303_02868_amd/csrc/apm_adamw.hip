@@ -183,8 +183,12 @@ __global__ __launch_bounds__(kThreads) void apm_grad_reduce_kernel(ReduceArgs a)
         segs = a.segs[i];
         const int k = (segs.n[1] > 0 && start >= segs.off[1]) ? 1 : 0;
         const int rel = start - segs.off[k];
-        // Wholly inside tenant k: address it like a page whose element 0 sits at g[k] - off[k].
-        if (rel >= 0 && rel + (end - start) <= segs.n[k]) g = segs.g[k] - segs.off[k];
+        // Wholly inside tenant k, counted in whole 8-element vectors (the fast path below loads
+        // 16 bytes at a time and must not read past the tensor's last element): address the
+        // tensor like a page whose element 0 sits at g[k] - off[k].  A slice that holds a tensor's
+        // ragged end takes the per-vector path, which reads that end element by element.
+        const int span8 = ((end - start) + 7) & ~7;
+        if (rel >= 0 && rel + span8 <= segs.n[k]) g = segs.g[k] - segs.off[k];
         else edge = true;
     }
 

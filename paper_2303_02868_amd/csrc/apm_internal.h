@@ -169,6 +169,18 @@ struct SegDesc {
 };
 hipError_t launch_seg_copy(const SegDesc* d_descs, int64_t n, int64_t max_bytes, hipStream_t s);
 
+// One kernel that moves an incoming batch (3 fp32 classes, in_bytes each, host -> staging) and an
+// outgoing batch (out_bytes each, staging -> host) at once; either byte count may be 0.  All
+// addresses are device-side addresses, 16-byte aligned; byte counts are multiples of 16.
+struct DuplexCopy {
+    const char* in_src[3];
+    char* in_dst[3];
+    const char* out_src[3];
+    char* out_dst[3];
+    int64_t in_bytes, out_bytes;
+};
+hipError_t launch_duplex_copy(const DuplexCopy& d, int wavefronts, int per_wg, hipStream_t s);
+
 // Fills the scalar fields of `a` from the hyper-parameters (all derived in double, rounded once).
 int prepare_hyper(const apm_hyper* h, int64_t step, AdamwLaunch* a);
 

@@ -2,8 +2,11 @@
 // (Sec. 4.2: overlap movement with computation; Sec. 5 "Allocator": asynchronous page copies; the
 // update is page-granular by Sec. 4.3's last paragraph).  Two ways across PCIe:
 //
-// Staged mode: the pages pass through a small ring of HBM staging slots, copy-in, update and
-// copy-out each on its own stream so that the three overlap.
+// Staged mode: the pages pass through a small ring of HBM staging slots.  While batch b is updated
+// in its slot on the compute stream, one copy kernel on the copy stream brings batch b+1 into the
+// next slot and takes batch b-1 out of the previous one, both directions at once
+// (apm_duplex_copy_kernel).  Staged-DMA mode is the same ring with the runtime's asynchronous
+// copies instead: copy-in, update and copy-out each on its own stream.
 //
 // Mixed residency (Sec. 4.2, the GPU cache of optimizer states): the first R pages may keep their
 // fp32 classes in a GPU pool; they are updated in place, in chunks interleaved with the streamed
@@ -13,7 +16,7 @@
 // p, m, v from the pinned host pages and writes them back across PCIe itself, with a small fixed
 // number of wavefronts; the link carries both directions at once inside one kernel.
 //
-// Slot life cycle for batch b (slot = b mod n_slots):
+// Slot life cycle for batch b (slot = b mod n_slots), staged-DMA mode:
 //   copy-in : wait D2H(b - n_slots) -> H2D p,m,v           -> record h2d[slot]
 //   compute : wait h2d[slot]        -> reduce + update      -> record cmp[slot]
 //   copy-out: wait cmp[slot]        -> D2H p,m,v            -> record d2h[slot]
@@ -35,6 +38,7 @@ struct apm_streamer {
     int n_slots = 0;
     float* stage[3] = {nullptr, nullptr, nullptr};  // each n_slots * B * E floats
     hipStream_t s_in = nullptr, s_cmp = nullptr, s_out = nullptr;
+    hipStream_t s_copy = nullptr;  // staged mode: the stream of the duplex copy kernels
     hipStream_t s_res = nullptr;  // direct mode: the resident pages' update, beside the host pages'
     hipEvent_t ev_res = nullptr;
     std::vector<hipEvent_t> ev_h2d, ev_cmp, ev_d2h;
@@ -63,6 +67,7 @@ void free_streamer(apm_streamer* s) {
     if (s->s_in && !s->in_is_null) (void)hipStreamDestroy(s->s_in);
     if (s->s_out && !s->out_is_null) (void)hipStreamDestroy(s->s_out);
     if (s->s_cmp) (void)hipStreamDestroy(s->s_cmp);
+    if (s->s_copy) (void)hipStreamDestroy(s->s_copy);
     if (s->s_res) (void)hipStreamDestroy(s->s_res);
     if (s->ev_res) (void)hipEventDestroy(s->ev_res);
     for (auto* v : {&s->ev_h2d, &s->ev_cmp, &s->ev_d2h, &s->sched_ev})
@@ -138,11 +143,22 @@ int pick_copy_streams(apm_streamer* s) {
     return APM_OK;
 }
 
-// Staging slots, the copy streams and the per-slot events: set up when the staged mode is first
-// asked for.
-int ensure_staged(apm_streamer* s) {
-    if (s->stage[0]) return APM_OK;
+int ensure_staging(apm_streamer* s);
+
+// Staging slots, the copy streams and the per-slot events: set up when a staged mode is first
+// asked for.  dma: the mode that uses the runtime's copies needs its calibrated stream pair; the
+// kernel-copy mode needs one more stream only.
+int ensure_staged(apm_streamer* s, bool dma) {
     APM_HIP(hipSetDevice(s->dev->desc.hip_device));
+    int rc = ensure_staging(s);
+    if (rc != APM_OK) return rc;
+    if (dma && !s->s_in) return pick_copy_streams(s);
+    if (!dma && !s->s_copy) APM_HIP(hipStreamCreateWithFlags(&s->s_copy, hipStreamNonBlocking));
+    return APM_OK;
+}
+
+int ensure_staging(apm_streamer* s) {
+    if (s->stage[0]) return APM_OK;
     const size_t bytes = (size_t)s->n_slots * (size_t)s->B * (size_t)s->dev->desc.page_elems * sizeof(float);
     hipError_t e = hipSuccess;
     for (int k = 0; k < 3 && e == hipSuccess; ++k) e = hipMalloc((void**)&s->stage[k], bytes);
@@ -156,10 +172,6 @@ int ensure_staged(apm_streamer* s) {
         (void)hipGetLastError();
         undo();
         return fail(APM_ENOMEM, "allocating 3 x %zu bytes of staging slots failed: %s", bytes, hipGetErrorString(e));
-    }
-    if (!s->s_in) {
-        int rc = pick_copy_streams(s);
-        if (rc != APM_OK) { undo(); return rc; }
     }
     auto mk_event = [&](hipEvent_t* ev) { return *ev ? hipSuccess : hipEventCreateWithFlags(ev, hipEventDisableTiming); };
     s->ev_h2d.resize((size_t)s->n_slots, nullptr);
@@ -219,7 +231,7 @@ extern "C" int apm_streamer_create(apm_streamer** out, apm_pool* host, apm_pool*
         int rc = ensure_scratch(dev);
         if (rc == APM_OK) {
             if (map_host_classes(s)) s->mode = APM_STREAM_DIRECT;
-            else { s->mode = APM_STREAM_STAGED; rc = ensure_staged(s); }
+            else { s->mode = APM_STREAM_STAGED_DMA; rc = ensure_staged(s, true); }
         }
         if (rc != APM_OK) { free_streamer(s); return rc; }
         *out = s;
@@ -259,10 +271,13 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     const size_t pb = (size_t)E * sizeof(float);
 
     const bool direct = s->mode == APM_STREAM_DIRECT;
-    if (direct && !(what & kDoUpdate)) return fail(APM_ESTATE, "the copy-only measurement belongs to the staged mode; this streamer is in direct mode");
+    if (direct && !(what & kDoUpdate)) return fail(APM_ESTATE, "the copy-only measurement belongs to the staged modes; this streamer is in direct mode");
     APM_HIP(hipEventRecord(s->ev_start, caller));
     APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_start, 0));
-    if (!direct) {
+    const bool kcopy = s->mode == APM_STREAM_STAGED;
+    if (kcopy) {
+        APM_HIP(hipStreamWaitEvent(s->s_copy, s->ev_start, 0));
+    } else if (!direct) {
         APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
         APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
     }
@@ -356,11 +371,84 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         r_done += nr;
         return APM_OK;
     };
+    hipStream_t s_last = kcopy ? s->s_copy : s->s_out;  // the stream the step ends on
     if (n_batches == 0) {
         rc = resident_chunk();
         if (rc != APM_OK) return rc;
         APM_HIP(hipEventRecord(s->ev_cmp[0], s->s_cmp));
-        APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_cmp[0], 0));
+        APM_HIP(hipStreamWaitEvent(s_last, s->ev_cmp[0], 0));
+    }
+    auto update_batch = [&](int64_t b) -> int {
+        const size_t slot = (size_t)(b % s->n_slots);
+        const int64_t first = R + b * s->B;
+        const int64_t nb = N - first < s->B ? N - first : s->B;
+        APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_h2d[slot], 0));
+        L.state_first = (int64_t)slot * s->B;
+        L.grad_first = first;
+        L.n_listed = nb;
+        L.grad_norm = grad_norm ? grad_norm + first : nullptr;
+        L.skip_mask = skip_mask ? skip_mask + first : nullptr;
+        if (what & kDoUpdate) {
+            if (need_reduce) APM_HIP(launch_grad_reduce(L, s->s_cmp));
+            else APM_HIP(launch_prepare(L, s->s_cmp));
+            APM_HIP(launch_adamw(L, s->s_cmp));
+        }
+        APM_HIP(hipEventRecord(s->ev_cmp[slot], s->s_cmp));
+        return APM_OK;
+    };
+    if (kcopy) {
+        // Iteration b: one copy kernel brings batch b+1 in and takes batch b-1 out while batch b is
+        // updated.  With three or more slots the three batches sit in different slots; with two,
+        // the incoming batch reuses the outgoing batch's slot, so the two directions become two
+        // kernels, one after the other.
+        auto exchange = [&](int64_t b_in, int64_t b_out) -> int {
+            DuplexCopy d{};
+            auto fill = [&](int64_t b, bool in) {
+                const size_t slot = (size_t)(b % s->n_slots);
+                const int64_t first = R + b * s->B;
+                const int64_t nb = N - first < s->B ? N - first : s->B;
+                const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
+                for (int k = 0; k < 3; ++k) {
+                    char* h = reinterpret_cast<char*>(s->host_dev[k]) + (size_t)(first - H0) * pb;
+                    char* g = reinterpret_cast<char*>(s->stage[k] + slot_off);
+                    if (in) { d.in_src[k] = h; d.in_dst[k] = g; }
+                    else { d.out_src[k] = g; d.out_dst[k] = h; }
+                }
+                (in ? d.in_bytes : d.out_bytes) = (int64_t)(pb * (size_t)nb);
+            };
+            if (b_in >= 0 && (what & kDoH2D)) fill(b_in, true);
+            if (b_out >= 0 && (what & kDoD2H)) fill(b_out, false);
+            APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_copy));
+            return APM_OK;
+        };
+        if (n_batches > 0) {
+            rc = exchange(0, -1);
+            if (rc != APM_OK) return rc;
+            APM_HIP(hipEventRecord(s->ev_h2d[0], s->s_copy));
+        }
+        for (int64_t b = 0; b < n_batches; ++b) {
+            const bool has_in = b + 1 < n_batches, has_out = b >= 1;
+            if (has_out) APM_HIP(hipStreamWaitEvent(s->s_copy, s->ev_cmp[(size_t)((b - 1) % s->n_slots)], 0));
+            if (has_in && has_out && s->n_slots < 3) {
+                rc = exchange(-1, b - 1);
+                if (rc == APM_OK) rc = exchange(b + 1, -1);
+            } else if (has_in || has_out) {
+                rc = exchange(has_in ? b + 1 : -1, has_out ? b - 1 : -1);
+            }
+            if (rc != APM_OK) return rc;
+            if (has_in) APM_HIP(hipEventRecord(s->ev_h2d[(size_t)((b + 1) % s->n_slots)], s->s_copy));
+            rc = resident_chunk();  // runs while this batch's neighbours are in flight
+            if (rc == APM_OK) rc = update_batch(b);
+            if (rc != APM_OK) return rc;
+        }
+        if (n_batches > 0) {
+            APM_HIP(hipStreamWaitEvent(s->s_copy, s->ev_cmp[(size_t)((n_batches - 1) % s->n_slots)], 0));
+            rc = exchange(-1, n_batches - 1);
+            if (rc != APM_OK) return rc;
+        }
+        APM_HIP(hipEventRecord(s->ev_done, s->s_copy));
+        APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
+        return APM_OK;
     }
     // Copy-in is enqueued one batch ahead of the update that consumes it: on this runtime the
     // device-to-host copy is a kernel whose enqueue blocks the host until the event it waits for
@@ -396,19 +484,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         }
 
         rc = resident_chunk();  // runs while this batch's copy-in is in flight
+        if (rc == APM_OK) rc = update_batch(b);
         if (rc != APM_OK) return rc;
-        APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_h2d[slot], 0));
-        L.state_first = (int64_t)slot * s->B;
-        L.grad_first = first;
-        L.n_listed = nb;
-        L.grad_norm = grad_norm ? grad_norm + first : nullptr;
-        L.skip_mask = skip_mask ? skip_mask + first : nullptr;
-        if (what & kDoUpdate) {
-            if (need_reduce) APM_HIP(launch_grad_reduce(L, s->s_cmp));
-            else APM_HIP(launch_prepare(L, s->s_cmp));
-            APM_HIP(launch_adamw(L, s->s_cmp));
-        }
-        APM_HIP(hipEventRecord(s->ev_cmp[slot], s->s_cmp));
 
         APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_cmp[slot], 0));
         for (int k = 0; k < 3 && (what & kDoD2H); ++k) {
@@ -457,16 +534,17 @@ extern "C" int apm_streamer_set_mode(apm_streamer* s, int mode, int direct_wavef
                                      int wavefronts_per_workgroup) {
     return apm::guarded([&]() -> int {
         if (!s) return fail(APM_EINVAL, "NULL streamer");
-        if (mode != APM_STREAM_STAGED && mode != APM_STREAM_DIRECT) return fail(APM_EINVAL, "unknown streamer mode %d", mode);
+        if (mode != APM_STREAM_STAGED && mode != APM_STREAM_DIRECT && mode != APM_STREAM_STAGED_DMA) return fail(APM_EINVAL, "unknown streamer mode %d", mode);
         if (direct_wavefronts < 0 || direct_wavefronts > (1 << 20)) return fail(APM_EINVAL, "direct_wavefronts out of range");
         if (wavefronts_per_workgroup < 0 || wavefronts_per_workgroup > 16) return fail(APM_EINVAL, "wavefronts_per_workgroup must be in [0, 16]");
         APM_HIP(hipSetDevice(s->dev->desc.hip_device));
-        if (mode == APM_STREAM_DIRECT) {
-            if (!map_host_classes(s)) return fail(APM_EDEVICE, "the host pool's memory is not mapped into the GPU's address space (not pinned?)");
+        if (mode == APM_STREAM_DIRECT || mode == APM_STREAM_STAGED) {
+            if (!map_host_classes(s)) return fail(APM_EDEVICE, "the host pool's memory is not mapped into the GPU's address space (not pinned?): only APM_STREAM_STAGED_DMA can serve it");
             s->direct_waves = direct_wavefronts > 0 ? direct_wavefronts : kDirectWavefronts;
             s->direct_per_wg = wavefronts_per_workgroup > 0 ? wavefronts_per_workgroup : 1;
-        } else {
-            int rc = ensure_staged(s);
+        }
+        if (mode != APM_STREAM_DIRECT) {
+            int rc = ensure_staged(s, mode == APM_STREAM_STAGED_DMA);
             if (rc != APM_OK) return rc;
         }
         s->mode = mode;
@@ -549,7 +627,8 @@ extern "C" int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_m
 // compute for the copy-ins of its pages, a write-back for its compute.
 extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
                                            const int64_t* layer_first_page, int64_t n_layers,
-                                           int64_t step, const apm_hyper* hyper, float* grad_norm,
+                                           const int64_t* last_access, int64_t step,
+                                           const apm_hyper* hyper, float* grad_norm,
                                            uint8_t* skip_mask, void* stream) {
     return apm::guarded([&]() -> int {
         if (!s) return fail(APM_EINVAL, "NULL streamer");
@@ -566,9 +645,21 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         AdamwLaunch L{};
         int rc = prepare_hyper(hyper, step, &L);
         if (rc != APM_OK) return rc;
-        rc = ensure_staged(s);
+        rc = ensure_staged(s, true);
         if (rc != APM_OK) return rc;
         APM_HIP(hipSetDevice(dev->desc.hip_device));
+
+        // The trace: the layer after whose compute a page's slot is free again (its own layer if
+        // no trace is given).  release_at[i] lists, in ascending order, the pages layer i releases.
+        std::vector<int64_t> own((size_t)N, 0);
+        for (int64_t i = 0; i < n_layers; ++i)
+            for (int64_t p = layer_first_page[i]; p < layer_first_page[i + 1]; ++p) own[(size_t)p] = i;
+        std::vector<std::vector<int64_t>> release_at((size_t)n_layers);
+        for (int64_t p = 0; p < N; ++p) {
+            const int64_t la = last_access ? last_access[p] : own[(size_t)p];
+            if (la < own[(size_t)p] || la >= n_layers) return fail(APM_EINVAL, "last_access[%lld] = %lld lies outside [its own layer %lld, %lld)", (long long)p, (long long)la, (long long)own[(size_t)p], (long long)n_layers);
+            release_at[(size_t)la].push_back(p);
+        }
 
         // ---- pass 1 (host only): replay the schedule against the slots -------------------------
         const int64_t n_slots = (int64_t)s->n_slots * s->B;
@@ -585,6 +676,10 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
             if (t.op == APM_TASK_MOVE_TO_GPU) {
                 if (t.target < 0 || t.target >= N) return fail(APM_ERANGE, "task %lld moves page %lld, out of range", (long long)k, (long long)t.target);
                 if (moved[(size_t)t.target]) return fail(APM_EINVAL, "task %lld moves page %lld a second time", (long long)k, (long long)t.target);
+                // A movement is issued when execution reaches its trigger id, i.e. once the layer
+                // before it has computed.  A trigger beyond the layers that precede the task in the
+                // list could never fire before the computes that wait for this very page.
+                if (t.trigger_id < 0 || t.trigger_id > next_layer) return fail(APM_EINVAL, "task %lld: trigger id %d is not in [0, %lld], the layers whose turn has come at this point of the list", (long long)k, t.trigger_id, (long long)next_layer);
                 if (free_slots.empty()) return fail(APM_ENOMEM, "task %lld: the schedule needs more than the %lld staging page slots", (long long)k, (long long)n_slots);
                 std::pop_heap(free_slots.begin(), free_slots.end(), cmp);
                 slot_seq[(size_t)t.target] = slot_of[(size_t)t.target] = free_slots.back();
@@ -593,8 +688,9 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                 ++n_moves;
             } else if (t.op == APM_TASK_COMPUTE) {
                 if (t.target != next_layer) return fail(APM_EINVAL, "task %lld computes layer %lld, expected layer %lld", (long long)k, (long long)t.target, (long long)next_layer);
-                for (int64_t p = layer_first_page[next_layer]; p < layer_first_page[next_layer + 1]; ++p) {
+                for (int64_t p = layer_first_page[next_layer]; p < layer_first_page[next_layer + 1]; ++p)
                     if (slot_of[(size_t)p] < 0) return fail(APM_ESTATE, "task %lld computes layer %lld before its page %lld was moved", (long long)k, (long long)next_layer, (long long)p);
+                for (int64_t p : release_at[(size_t)next_layer]) {  // moved: its own layer has computed
                     free_slots.push_back(slot_of[(size_t)p]);
                     std::push_heap(free_slots.begin(), free_slots.end(), cmp);
                     slot_of[(size_t)p] = -1;
@@ -657,15 +753,27 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
 
         std::vector<hipEvent_t> slot_free((size_t)n_slots, nullptr);  // write-back that last freed the slot
         std::vector<hipEvent_t> page_in((size_t)N, nullptr);          // copy-in that brought the page
+        // reached[t]: logical time t, the point of the compute stream where layer t - 1 has
+        // computed (t = 0: the start of the step).  A movement task waits for reached[trigger_id]
+        // (event-driven dispatch, Sec. 5 "Unified Scheduler") besides the slots it moves into.
+        std::vector<hipEvent_t> reached((size_t)n_layers + 1, nullptr);
+        int64_t copy_in_at = 0;  // the logical time the copy-in stream is known to have passed
+        hipEvent_t last_computed = nullptr;
         int64_t k = 0;
         while (k < n_tasks) {
             if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
-                // a run of movement tasks over consecutive pages and consecutive slots is one copy per class
+                // a run of movement tasks over consecutive pages and consecutive slots with one
+                // trigger id is one copy per class
                 const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
+                const int32_t trig = tasks[k].trigger_id;
                 int64_t n = 1;
                 while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
-                       slot_seq[(size_t)(p0 + n)] == s0 + n)
+                       slot_seq[(size_t)(p0 + n)] == s0 + n && tasks[k + n].trigger_id == trig)
                     ++n;
+                if (trig > copy_in_at) {  // the copy-in stream is in order: earlier waits still hold
+                    APM_HIP(hipStreamWaitEvent(s->s_in, reached[(size_t)trig], 0));
+                    copy_in_at = trig;
+                }
                 hipEvent_t last_wait = nullptr;
                 for (int64_t j = 0; j < n; ++j) {
                     hipEvent_t w = slot_free[(size_t)(s0 + j)];
@@ -689,46 +797,56 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
             const int64_t i = tasks[k].target;
             const int64_t first = layer_first_page[i], n = layer_first_page[i + 1] - first;
             ++k;
-            if (n == 0) continue;
-            hipEvent_t last_wait = nullptr;
-            for (int64_t j = 0; j < n; ++j) {
-                hipEvent_t w = page_in[(size_t)(first + j)];
-                if (w != last_wait) {
-                    APM_HIP(hipStreamWaitEvent(s->s_cmp, w, 0));
-                    last_wait = w;
+            if (n > 0) {
+                hipEvent_t last_wait = nullptr;
+                for (int64_t j = 0; j < n; ++j) {
+                    hipEvent_t w = page_in[(size_t)(first + j)];
+                    if (w != last_wait) {
+                        APM_HIP(hipStreamWaitEvent(s->s_cmp, w, 0));
+                        last_wait = w;
+                    }
                 }
+                AdamwLaunch C = L;
+                C.state_pages = d_slots + first;
+                C.grad_first = first;
+                C.n_listed = n;
+                C.grad_norm = grad_norm ? grad_norm + first : nullptr;
+                C.skip_mask = skip_mask ? skip_mask + first : nullptr;
+                if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
+                else APM_HIP(launch_prepare(C, s->s_cmp));
+                APM_HIP(launch_adamw(C, s->s_cmp));
             }
-            AdamwLaunch C = L;
-            C.state_pages = d_slots + first;
-            C.grad_first = first;
-            C.n_listed = n;
-            C.grad_norm = grad_norm ? grad_norm + first : nullptr;
-            C.skip_mask = skip_mask ? skip_mask + first : nullptr;
-            if (need_reduce) APM_HIP(launch_grad_reduce(C, s->s_cmp));
-            else APM_HIP(launch_prepare(C, s->s_cmp));
-            APM_HIP(launch_adamw(C, s->s_cmp));
-            hipEvent_t computed, written;
+            // logical time i + 1; also what the write-back of the pages released here waits for
+            hipEvent_t computed;
             rc = new_event(&computed);
-            if (rc == APM_OK) rc = new_event(&written);
             if (rc != APM_OK) return rc;
             APM_HIP(hipEventRecord(computed, s->s_cmp));
+            reached[(size_t)i + 1] = computed;
+            last_computed = computed;
+            const std::vector<int64_t>& rel = release_at[(size_t)i];
+            if (rel.empty()) continue;
+            hipEvent_t written;
+            rc = new_event(&written);
+            if (rc != APM_OK) return rc;
             APM_HIP(hipStreamWaitEvent(s->s_out, computed, 0));
-            for (int64_t j = 0; j < n;) {  // write back in runs of consecutive slots
-                const int64_t s0 = slot_seq[(size_t)(first + j)];
-                int64_t m = 1;
-                while (j + m < n && slot_seq[(size_t)(first + j + m)] == s0 + m) ++m;
+            for (size_t j = 0; j < rel.size();) {  // write back in runs of consecutive pages and slots
+                const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
+                size_t m = 1;
+                while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
                 for (int c = 0; c < 3; ++c) {
-                    char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)(first + j) * pb;
-                    APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * (size_t)m, hipMemcpyDeviceToHost, s->s_out));
+                    char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)q0 * pb;
+                    APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * m, hipMemcpyDeviceToHost, s->s_out));
                 }
                 j += m;
             }
             APM_HIP(hipEventRecord(written, s->s_out));
-            for (int64_t j = 0; j < n; ++j) slot_free[(size_t)slot_seq[(size_t)(first + j)]] = written;
+            for (int64_t q : rel) slot_free[(size_t)slot_seq[(size_t)q]] = written;
         }
         rc = dev->ring.seal(slots_ring_slot, s->s_cmp);
         if (rc != APM_OK) return rc;
-        // every copy-in feeds a compute and every compute a write-back: the copy-out stream ends last
+        // every copy-in feeds a compute and every page a write-back; the copy-out stream also waits
+        // for the last compute, so it ends last
+        if (last_computed) APM_HIP(hipStreamWaitEvent(s->s_out, last_computed, 0));
         APM_HIP(hipEventRecord(s->ev_done, s->s_out));
         APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
         return APM_OK;

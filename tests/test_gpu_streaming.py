@@ -34,9 +34,13 @@ def set_mode(streamer, mode):
         apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT, n, per)
         assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_DIRECT
     else:
+        # "staged[:<wavefronts>]": the library's duplex copy kernel moves the batches;
+        # "staged_dma": the runtime's asynchronous copies do
         assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_DIRECT   # pinned pool: the default
-        apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_STAGED)
-        assert apm.apm_streamer_get_mode(streamer) == apm.APM_STREAM_STAGED
+        parts = mode.split(":")
+        want = apm.APM_STREAM_STAGED_DMA if parts[0] == "staged_dma" else apm.APM_STREAM_STAGED
+        apm.apm_streamer_set_mode(streamer, want, int(parts[1]) if len(parts) > 1 else 0)
+        assert apm.apm_streamer_get_mode(streamer) == want
 
 
 def test_page_copy_roundtrip_bit_exact():
@@ -64,6 +68,8 @@ def test_page_copy_roundtrip_bit_exact():
 
 
 @pytest.mark.parametrize("batch,slots,clip,mode", [(4, 2, 0.0, "staged"), (7, 3, 1.0, "staged"), (64, 2, 1.0, "staged"),
+                                                   (5, 4, 1.0, "staged:7"), (200, 3, 0.0, "staged"),
+                                                   (4, 2, 0.0, "staged_dma"), (7, 3, 1.0, "staged_dma"),
                                                    (4, 2, 0.0, "direct"), (4, 2, 1.0, "direct:7"), (4, 2, 1.0, "direct:37:16"),
                                                    (4, 2, 0.0, "direct:128:8")])
 def test_streamed_equals_resident_bit_exact(batch, slots, clip, mode):
@@ -107,7 +113,8 @@ def test_streamed_equals_resident_bit_exact(batch, slots, clip, mode):
 
 @pytest.mark.parametrize("frac,mode,short_host", [(0.0, "staged", False), (0.35, "staged", False), (1.0, "staged", False),
                                                   (0.35, "direct", False), (1.0, "direct", False),
-                                                  (0.35, "direct", True), (0.35, "staged", True)])
+                                                  (0.35, "direct", True), (0.35, "staged", True),
+                                                  (0.35, "staged_dma", False)])
 def test_mixed_residency_equals_resident_bit_exact(frac, mode, short_host):
     # the first R pages keep their fp32 state in an HBM cache pool, the rest is streamed;
     # short_host: the host pool holds only the pages from H0 = R - 3 on (a model whose fp32 state
@@ -382,6 +389,76 @@ def test_scheduled_step_equals_resident_bit_exact(budget_layers):
         greedy = [(apm.APM_TASK_MOVE_TO_GPU, p, 0) for p in range(n_pages)] + [(apm.APM_TASK_COMPUTE, i, i) for i in range(len(bounds) - 1)]
         apm.apm_streamer_step_scheduled(st, greedy, bounds, 4, hy)
     assert e.value.code == apm.APM_ENOMEM
+    st.destroy()
+    host.destroy()
+    dev.destroy()
+    res.destroy()
+
+
+def test_scheduled_step_with_a_trace_that_keeps_pages_beyond_their_own_layer():
+    # Alg. 1's input is the trace: the layer after which a page's GPU memory is free again.  Here
+    # the first page of every layer but the last is accessed again by the layer two further on (and
+    # one page by the last layer), so the planner must keep those pages resident and defer others;
+    # the executor holds their slots until that later layer has computed, honours the trigger ids,
+    # and the result must still equal the resident update bit for bit.
+    f, E = synth.WORKLOADS["gpt2_small_124m"]
+    model = Model(f(), E, seed=14)
+    n_pages, n_t = model.plan.n_pages, len(model.specs)
+    bounds = layer_ranges(model)
+    n_layers = len(bounds) - 1
+    own = [i for i in range(n_layers) for _ in range(bounds[i], bounds[i + 1])]
+    last_access = list(own)
+    for i in range(n_layers - 1):
+        last_access[bounds[i]] = min(i + 2, n_layers - 1)
+    last_access[bounds[1] + 1] = n_layers - 1
+    largest = max(b - a for a, b in zip(bounds, bounds[1:]))
+    slots = 2 * largest + 6
+    page_bytes = 12 * E
+    layers = [(range(a, b), 0) for a, b in zip(bounds, bounds[1:])]
+    tasks, peak = apm.apm_schedule_plan(layers, last_access, page_bytes, slots * page_bytes)
+    assert peak <= slots * page_bytes
+    plain, _ = apm.apm_schedule_plan(layers, None, page_bytes, slots * page_bytes)
+    assert tasks != plain                                        # the trace changed the schedule
+    assert any(t[0] == apm.APM_TASK_MOVE_TO_GPU and t[2] > 0 for t in tasks)   # some movements are triggered later
+
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    st = apm.apm_streamer_create(host, dev.pool, (slots + 1) // 2, 2)
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 4):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, None)
+        apm.apm_streamer_step_scheduled(st, tasks, bounds, t, hy, norm_s, None, last_access=last_access)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s)
+    for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+        hv = host_view(host, s_, n_pages, E)
+        assert np.array_equal(hv.view(np.uint32), res.reg[s_].cpu().numpy().view(np.uint32)), f"state {s_}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+
+    def code(fn):
+        with pytest.raises(apm.ApmError) as e:
+            fn()
+        return e.value.code
+    # the schedule planned without the trace frees slots too early for it: refused, nothing runs
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, plain, bounds, 4, hy, last_access=last_access)) == apm.APM_ENOMEM
+    # a movement triggered by a layer that computes after it in the list could never be issued
+    k = next(i for i, t in enumerate(tasks) if t[0] == apm.APM_TASK_MOVE_TO_GPU)
+    late = list(tasks)
+    late[k] = (late[k][0], late[k][1], 1)
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, late, bounds, 4, hy, last_access=last_access)) == apm.APM_EINVAL
+    early = list(last_access)
+    early[bounds[3]] = 2                                         # before the page's own layer
+    assert code(lambda: apm.apm_streamer_step_scheduled(st, tasks, bounds, 4, hy, last_access=early)) == apm.APM_EINVAL
+    torch.cuda.synchronize()
     st.destroy()
     host.destroy()
     dev.destroy()
