@@ -65,6 +65,10 @@ def parse():
                     help="GPU memory of the scheduled streaming leg, in units of the largest block")
     ap.add_argument("--direct-wavefronts", type=int, default=0,
                     help="wavefronts of the direct streaming mode's kernel (0 = library default)")
+    ap.add_argument("--lockfree-sweep", action="store_true",
+                    help="lock_free leg: sweep wavefronts x workgroup packing of the PCIe-crossing kernel")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the compact legs of the other configurations (124 M, 13 B, MoE) and the flat reference")
     ap.add_argument("--batch-pages", type=int, default=32)
     ap.add_argument("--slots", type=int, default=3)
     return ap.parse_args()
@@ -314,20 +318,34 @@ def pcie_raw(host, devp, n_pages, E, state):
             "duplex_each_GBps": nbytes / tb / 1e9, "copy_bytes": run * E * 4}
 
 
+PCIE_GEN5_X16_RAW_GBPS = 64.0   # 32 GT/s x 16 lanes, 128b/130b: raw rate per direction
+
+
+def _median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2] if len(xs) % 2 else 0.5 * (xs[len(xs) // 2 - 1] + xs[len(xs) // 2])
+
+
 def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_params):
-    """Both streaming modes: the staged pipeline (with its copy-only passes, the measured PCIe
-    rate both modes are held against) and the direct mode; the faster one is the leg's result."""
+    """The three streaming modes -- direct (the update kernel reads and writes the host pages),
+    staged (slot ring moved by the library's duplex copy kernel) and staged_dma (slot ring moved by
+    the runtime's asynchronous copies) -- timed step by step (median and min), each staged mode
+    with its copy-only pipeline.  Every mode is credited with the parameters' 12 B each way only
+    (padding that page copies move as well is not credited) and held against named denominators:
+    plain pinned copies measured in the same run (one direction alone, both at once) and the raw
+    Gen5 x16 rate.  `update_hidden` is computed for every mode: T_step <= 1.02 x the time plain
+    copies of the same bytes take with both directions busy (the slower of the one-way and duplex
+    raw rates)."""
     import torch
     import paper_2303_02868_amd as apm
     stream = torch.cuda.current_stream()
 
-    def timed(fn, reps):
+    def timed(fn):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(reps):
-            fn()
+        fn()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / reps
+        return time.perf_counter() - t0
 
     t = [first_step]
 
@@ -335,62 +353,72 @@ def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_para
         apm.apm_streamer_step(streamer, t[0], hyper, None, None, stream)
         t[0] += 1
 
-    each_way = n_pages * E * 12
-    apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_STAGED)
-    full()                                                    # warm-up
-    # Full steps and copy-only passes are interleaved and the fastest of each is kept: the PCIe
-    # path is shared with other tenants of the host, and its rate was seen to dip for whole runs.
-    walls, boths = [], []
-    t_h2d = timed(lambda: apm.apm_streamer_copy_only(streamer, 1, stream), 1)
-    for _ in range(args.stream_steps):
-        boths.append(timed(lambda: apm.apm_streamer_copy_only(streamer, 3, stream), 1))
-        walls.append(timed(full, 1))
-    wall, t_both = min(walls), min(boths)
-    # copy-out alone writes stale staging contents back to the host pool: measured last, and
-    # followed by a full step's worth of nothing -- the contents are synthetic either way
-    t_d2h = timed(lambda: apm.apm_streamer_copy_only(streamer, 2, stream), 1)
-    t_copy = max(t_both, t_h2d, t_d2h)
-    staged = {"ms_per_step": wall * 1e3, "ms_per_step_all": [w * 1e3 for w in walls],
-              "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_each_way": each_way,
-              "batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
-              "copy_only_pipeline": {"both_ms": t_both * 1e3, "h2d_only_ms": t_h2d * 1e3,
-                                     "d2h_only_ms": t_d2h * 1e3,
-                                     "both_GBps_each_way": each_way / t_both / 1e9,
-                                     "h2d_GBps": each_way / t_h2d / 1e9, "d2h_GBps": each_way / t_d2h / 1e9},
-              "stream_calibration_GBps": dict(zip(("h2d", "d2h", "duplex_each_way"),
-                                                  apm.apm_streamer_probe_rates(streamer))),
-              "frac_of_copy_only_pipeline": t_copy / wall,
-              "update_hidden": wall <= 1.02 * t_copy}
-
-    apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT, args.direct_wavefronts)
-    full()
-    dwalls = [timed(full, 1) for _ in range(args.stream_steps)]
-    dwall = min(dwalls)
-    # the direct kernel touches the used extents only; the staged copies move whole pages
-    each_way_direct = total_params * 12
-    direct = {"ms_per_step": dwall * 1e3, "ms_per_step_all": [w * 1e3 for w in dwalls],
-              "pcie_GBps_each_way": each_way_direct / dwall / 1e9, "bytes_each_way": each_way_direct,
-              "wavefronts": args.direct_wavefronts or "library default (48)",
-              "hbm_staging_bytes": 0}
-
-    # The measured PCIe rate: the best each-way rate plain hipMemcpyAsync pairs reached with both
-    # directions busy (the copy-only pipeline, and large raw copies when they were measured).
-    ref = each_way / t_copy / 1e9
+    each_way = total_params * 12                    # credited: the parameters' fp32 state
+    moved_pages = n_pages * E * 12                  # what whole-page copies move
     if raw:
-        ref = max(ref, raw["duplex_each_GBps"])
-    best_mode, best_wall, best = ("direct", dwall, direct) if dwall <= wall else ("staged", wall, staged)
-    out = {"mode": best_mode, "ms_per_step": best_wall * 1e3, "params_per_s": total_params / best_wall,
-           "pcie_GBps_each_way": best["pcie_GBps_each_way"], "bytes_each_way": best["bytes_each_way"],
-           "host_pinned_GB": each_way / 1e9,
-           "measured_pcie_GBps_each_way": ref,
-           "frac_of_measured_pcie": best["pcie_GBps_each_way"] / ref,
-           "update_hidden": True if best_mode == "direct" else staged["update_hidden"],
-           "direct": direct, "staged": staged}
+        t_raw = each_way / 1e9 / min(raw["duplex_each_GBps"], raw["h2d_GBps"], raw["d2h_GBps"])
+    out_modes = {}
+    for name, mode in (("direct", apm.APM_STREAM_DIRECT), ("staged", apm.APM_STREAM_STAGED),
+                       ("staged_dma", apm.APM_STREAM_STAGED_DMA)):
+        apm.apm_streamer_set_mode(streamer, mode, args.direct_wavefronts)
+        full()                                      # warm-up
+        walls, boths = [], []
+        for _ in range(args.stream_steps):
+            if mode != apm.APM_STREAM_DIRECT:       # interleaved with the steps: the link is shared
+                boths.append(timed(lambda: apm.apm_streamer_copy_only(streamer, 3, stream)))
+            walls.append(timed(full))
+        wall = _median(walls)
+        r = {"ms_per_step": wall * 1e3, "ms_per_step_min": min(walls) * 1e3,
+             "ms_per_step_all": [w * 1e3 for w in walls],
+             "pcie_GBps_each_way": each_way / wall / 1e9, "bytes_credited_each_way": each_way,
+             "bytes_moved_each_way": each_way if mode == apm.APM_STREAM_DIRECT else moved_pages}
+        if mode == apm.APM_STREAM_DIRECT:
+            r["wavefronts"] = args.direct_wavefronts or "library default (48)"
+            r["hbm_staging_bytes"] = 0
+        else:
+            t_h2d = timed(lambda: apm.apm_streamer_copy_only(streamer, 1, stream))
+            t_d2h = timed(lambda: apm.apm_streamer_copy_only(streamer, 2, stream))
+            t_both = _median(boths)
+            r.update({"batch_pages": min(args.batch_pages, n_pages), "slots": args.slots,
+                      "copy_only_pipeline": {"both_ms": t_both * 1e3, "both_ms_all": [x * 1e3 for x in boths],
+                                             "h2d_only_ms": t_h2d * 1e3, "d2h_only_ms": t_d2h * 1e3,
+                                             "both_GBps_each_way_moved": moved_pages / t_both / 1e9},
+                      "step_over_own_copy_only_pipeline": wall / max(t_both, t_h2d, t_d2h)})
+            if mode == apm.APM_STREAM_STAGED_DMA:
+                r["stream_calibration_GBps"] = dict(zip(("h2d", "d2h", "duplex_each_way"),
+                                                        apm.apm_streamer_probe_rates(streamer)))
+        if raw:
+            r["frac_of_raw_duplex_copies"] = r["pcie_GBps_each_way"] / raw["duplex_each_GBps"]
+            r["frac_of_raw_one_way_copy"] = r["pcie_GBps_each_way"] / min(raw["h2d_GBps"], raw["d2h_GBps"])
+            r["update_hidden"] = bool(wall <= 1.02 * t_raw)
+            r["step_over_raw_copy_time"] = wall / t_raw
+        r["frac_of_gen5_x16_raw_64GBps"] = r["pcie_GBps_each_way"] / PCIE_GEN5_X16_RAW_GBPS
+        out_modes[name] = r
+
+    best_mode = min(out_modes, key=lambda k: out_modes[k]["ms_per_step"])
+    best = out_modes[best_mode]
+    out = {"mode": best_mode, "ms_per_step": best["ms_per_step"], "params_per_s": total_params / (best["ms_per_step"] * 1e-3),
+           "pcie_GBps_each_way": best["pcie_GBps_each_way"], "bytes_each_way": each_way,
+           "host_pinned_GB": moved_pages / 1e9,
+           "timing": "median of --stream-steps single steps, each bracketed by device synchronisation",
+           "update_hidden": best.get("update_hidden"),
+           "update_hidden_criterion": "median step time <= 1.02 x time of plain pinned copies of the credited bytes "
+                                      "at the slowest of the raw rates below (h2d alone, d2h alone, each way with both busy)",
+           "frac_of_raw_duplex_copies": best.get("frac_of_raw_duplex_copies"),
+           "frac_of_raw_one_way_copy": best.get("frac_of_raw_one_way_copy"),
+           "frac_of_gen5_x16_raw_64GBps": best["frac_of_gen5_x16_raw_64GBps"]}
+    out.update(out_modes)
     if raw:
         out["raw_pinned_copy"] = raw
-    apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT if best_mode == "direct" else apm.APM_STREAM_STAGED,
-                              args.direct_wavefronts)
+    apm.apm_streamer_set_mode(streamer, {"direct": apm.APM_STREAM_DIRECT, "staged": apm.APM_STREAM_STAGED,
+                                         "staged_dma": apm.APM_STREAM_STAGED_DMA}[best_mode], args.direct_wavefronts)
     return out
+
+
+def _mode_const(name):
+    import paper_2303_02868_amd as apm
+    return {"direct": apm.APM_STREAM_DIRECT, "staged": apm.APM_STREAM_STAGED,
+            "staged_dma": apm.APM_STREAM_STAGED_DMA}[name]
 
 
 def layer_bounds(wl):
@@ -497,9 +525,15 @@ def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
 
     out = {"producer": f"{reps} bf16 {n}^3 matrix products per iteration (stand-in for forward/backward)",
            "producer_TFLOPs_alone": 2.0 * n ** 3 * reps / t_compute / 1e12, "producer_ms": t_compute * 1e3}
-    ways = (("direct_64_wavefronts_on_64_CUs", apm.APM_STREAM_DIRECT, 64, 1),
+    ways = [("direct_64_wavefronts_on_64_CUs", apm.APM_STREAM_DIRECT, 64, 1),
             ("direct_128_wavefronts_on_8_CUs", apm.APM_STREAM_DIRECT, 128, 16),
-            ("staged", apm.APM_STREAM_STAGED, 0, 0))
+            ("staged_128_wavefronts_on_8_CUs", apm.APM_STREAM_STAGED, 128, 16),
+            ("staged_dma", apm.APM_STREAM_STAGED_DMA, 0, 0)]
+    if args.lockfree_sweep:     # wavefronts x workgroup packing of the kernel that crosses PCIe
+        ways = [(f"{m}_{w}_wavefronts_{p}_per_workgroup", c, w, p)
+                for m, c in (("direct", apm.APM_STREAM_DIRECT), ("staged", apm.APM_STREAM_STAGED))
+                for w, p in ((48, 1), (64, 8), (80, 16), (96, 16), (128, 16), (160, 16), (256, 16))]
+        ways.append(("staged_dma", apm.APM_STREAM_STAGED_DMA, 0, 0))
     for name, mode, waves, per_wg in ways:
         apm.apm_streamer_set_mode(streamer, mode, waves, per_wg)
         update_only()
@@ -511,7 +545,12 @@ def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
         torch.cuda.synchronize()
         out[name] = {"update_ms": t_update * 1e3, "synchronous_ms_per_iter": t_sync * 1e3,
                      "one_step_stale_ms_per_iter": t_delayed * 1e3, "speedup": t_sync / t_delayed,
-                     "hidden_fraction_of_the_shorter": (t_sync - t_delayed) / min(t_compute, t_update)}
+                     "hidden_fraction_of_the_shorter": (t_sync - t_delayed) / min(t_compute, t_update),
+                     "over_ideal_max_of_the_two": t_delayed / max(t_compute, t_update),
+                     "streams_run_beside_the_producer": dict(zip(("update_stream", "pipeline_streams"),
+                                                                 apm.apm_streamer_overlap_report(streamer)))}
+    best = min((k for k in out if isinstance(out[k], dict)), key=lambda k: out[k]["one_step_stale_ms_per_iter"])
+    out["best"] = {"way": best, **out[best]}
     return out
 
 
@@ -623,8 +662,7 @@ def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
     out = time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, wl.total)
     out["scheduled"] = scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step + 50)
     out["lock_free"] = lockfree_leg(args, streamer, dev_pool, hyper, out["ms_per_step"])
-    apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_DIRECT if out["mode"] == "direct" else apm.APM_STREAM_STAGED,
-                              args.direct_wavefronts)
+    apm.apm_streamer_set_mode(streamer, _mode_const(out["mode"]), args.direct_wavefronts)
     if has_fp32:
         # mixed residency: half of the pages keep their fp32 state in HBM (the pool's own fp32
         # classes serve as the cache), the other half is streamed
@@ -643,6 +681,228 @@ def streamed_leg(args, wl, dev_pool, hyper, n_pages, first_step):
                                   "ms_per_step": min(ts) * 1e3, "params_per_s": wl.total / min(ts)}
     streamer.destroy()
     host.destroy()
+    return out
+
+
+def flat_reference_leg(args):
+    """1024 completely full pages (one tensor, no fragmentation) in the same process as the
+    headline: the update kernel on full pages, in the page-class form (g16 and p16 are page
+    classes) and in the fused form (g16 read from / p16 written to tensors), both with clipping."""
+    import torch
+    import paper_2303_02868_amd as apm
+    wl = Workload("flat_1024pages")
+    plan = apm.apm_pack_plan(wl.E, wl.numels)
+    pool = apm.apm_pool_create(apm.APM_DEV_GPU, wl.E, plan.n_pages)
+    apm.apm_pack_tensors(pool, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    torch.cuda.synchronize()
+    hyper = apm.make_hyper(max_grad_norm=1.0)
+    out = {"params": wl.total, "pages": plan.n_pages, "clip": 1.0}
+    steps = max(5, args.steps // 2)
+    t = 1
+    for name, upd_only in (("page_class", True), ("fused", False)):
+        a2 = argparse.Namespace(**vars(args))
+        a2.update_only = upd_only
+        r = resident_leg(a2, wl, pool, hyper, plan.n_pages, not upd_only, steps, 2, t)
+        t = r["next_step"]
+        out[name] = {"ms_per_step": r["wall"] * 1e3 / steps, "params_per_s": wl.total * steps / r["wall"],
+                     "update_kernel_ms": r["upd_ms"], "update_kernel_GBps": r["achieved"],
+                     "update_kernel_frac_of_peak": r["achieved"] / HBM_PEAK_GBPS,
+                     "reduce_kernel_ms": r["kernels"].get("grad_reduce", {}).get("avg_ms")}
+    pool.destroy()
+    return out
+
+
+def oracle_sample_timing(wl, plan, clip, skip, active=None, max_pages=48, steps=2):
+    """The oracle (reduce + AdamW in double) timed on every k-th page of a configuration, with the
+    pages' real used extents and -- for the MoE shape -- real mix of pages with and without
+    gradient; the per-step time of the whole configuration is EXTRAPOLATED linearly from it."""
+    import numpy as np
+    import torch
+    import oracle
+    import synth
+    E = wl.E
+    used_all = plan_used(plan, plan.n_pages)
+    every = max(1, plan.n_pages // max_pages)
+    sample = list(range(0, plan.n_pages, every))
+    used = [used_all[p] for p in sample]
+    threads = min(16, os.cpu_count() or 1)
+    rng_p = synth.normal_f32(0, 1, 0, len(sample) * E, 0.02, device=DEV).cpu().numpy().reshape(len(sample), E)
+    g = synth.normal_bf16(0, 1001, 0, len(sample) * E, 1e-3, device=DEV).view(torch.int16).cpu().numpy().view(np.uint16).reshape(len(sample), E).copy()
+    live = np.ones(len(sample), dtype=bool)
+    if active is not None:      # pages none of whose tenants received a gradient are all zero
+        page_live = np.zeros(plan.n_pages, dtype=bool)
+        for tensor, _, page, _, _ in plan.segments:
+            if active[tensor]:
+                page_live[page] = True
+        live = page_live[sample]
+        g[~live] = 0
+    st = oracle.PagedAdamWState(rng_p, used)
+    h = oracle.Hyper(max_grad_norm=clip, skip_mode=int(skip))
+    st.step(g, 1, h, threads=threads)
+    t0 = time.perf_counter()
+    for k in range(steps):
+        st.step(g, 2 + k, h, threads=threads)
+    dt = (time.perf_counter() - t0) / steps
+    elems = float(sum(used))
+    return {"kind": "oracle", "sampled_pages": len(sample), "every": every, "sampled_params": elems,
+            "pages_with_gradient_in_sample": int(live.sum()), "cores": threads,
+            "params_per_s": elems / dt,
+            "ms_per_step_extrapolated": dt * 1e3 * (wl.total / elems) if elems else None,
+            "note": "extrapolated linearly from the sampled pages (pages are independent)"}
+
+
+def configs_leg(args):
+    """Compact legs for the configurations the headline is not quoted on: the 124 M shape resident,
+    the 13 B shape with its fp32 state in pinned host memory (at the depth the box can pin, and at
+    its full 40 layers with the head cached in HBM), and the MoE shape (synchronous against
+    one-step-stale, and with the caller listing the active pages).  Each with the oracle timed on a
+    sample of its pages."""
+    import torch
+    import paper_2303_02868_amd as apm
+    import synth
+    out = {"cfg1_8pages": "correctness only: 59 MB moved per step is cache-resident and launch-bound (tests)"}
+
+    # ---- cfg 2: GPT-2-small shape, resident ---------------------------------------------------
+    wl = Workload("gpt2_small_124m")
+    plan = apm.apm_pack_plan(wl.E, wl.numels)
+    pool = apm.apm_pool_create(apm.APM_DEV_GPU, wl.E, plan.n_pages)
+    apm.apm_pack_tensors(pool, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    torch.cuda.synchronize()
+    hyper = apm.make_hyper()
+    a2 = argparse.Namespace(**vars(args))
+    a2.update_only = False
+    r = resident_leg(a2, wl, pool, hyper, plan.n_pages, True, args.steps, args.warmup)
+    out["cfg2_gpt2_small_124m"] = {
+        "params": wl.total, "pages": plan.n_pages, "fragmentation": plan.fragmentation,
+        "step": "fused AdamW reading g16 from / writing p16 to the tensors, no clipping",
+        "ms_per_step": r["wall"] * 1e3 / args.steps, "params_per_s": wl.total * args.steps / r["wall"],
+        "update_kernel_ms": r["upd_ms"], "update_kernel_GBps": r["achieved"],
+        "update_kernel_frac_of_peak": r["achieved"] / HBM_PEAK_GBPS,
+        "oracle": oracle_sample_timing(wl, plan, 0.0, 0, max_pages=plan.n_pages, steps=3)}
+    pool.destroy()
+
+    # ---- cfg 5: MoE shape, device-side skip; synchronous vs one-step-stale; active-page list ----
+    wl = Workload("moe_8x64")
+    plan = apm.apm_pack_plan(wl.E, wl.numels)
+    pool = apm.apm_pool_create(apm.APM_DEV_GPU, wl.E, plan.n_pages)
+    apm.apm_pack_tensors(pool, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    torch.cuda.synchronize()
+    hyper = apm.make_hyper(skip_mode=apm.APM_SKIP_UNTOUCHED)
+    steps = max(6, args.steps // 2)
+    r = resident_leg(a2, wl, pool, hyper, plan.n_pages, True, steps, 2)
+    act = synth.moe_active_tensors(wl.specs, 1, 0, 64, 8)
+    c5 = {"params": wl.total, "pages": plan.n_pages, "fragmentation": plan.fragmentation,
+          "active_params_per_step": r["elems_update"],
+          "step": "grad reduce (finds the pages without gradient on the device) + fused AdamW, 1/8 of the expert pages active",
+          "sync_fused": {"ms_per_step": r["wall"] * 1e3 / steps, "useful_params_per_s": r["elems_update"] * steps / r["wall"],
+                         "update_kernel_ms": r["upd_ms"], "update_kernel_GBps_useful": r["achieved"],
+                         "reduce_kernel_ms": r["kernels"].get("grad_reduce", {}).get("avg_ms")}}
+    d = delayed_leg(a2, wl, pool, hyper, plan.n_pages, r["next_step"])
+    c5["sync_vs_one_step_stale"] = d
+    c5["sync_vs_one_step_stale"]["useful_params_per_s_sync"] = r["elems_update"] / (d["sync_ms_per_step"] * 1e-3)
+    c5["sync_vs_one_step_stale"]["useful_params_per_s_delayed"] = r["elems_update"] / (d["delayed_ms_per_step"] * 1e-3)
+    c5["caller_lists_active_pages"] = moe_active_list_leg(a2, wl, pool, hyper, plan, r["next_step"] + 100)
+    c5["oracle"] = oracle_sample_timing(wl, plan, 0.0, 1, active=act, max_pages=64, steps=2)
+    out["cfg5_moe_8x64"] = c5
+    pool.destroy()
+    torch.cuda.empty_cache()
+
+    # ---- cfg 4: 13 B shape, fp32 state in pinned host memory ----------------------------------
+    out["cfg4_gpt_13b"] = cfg4_leg(args)
+    return out
+
+
+def cfg4_leg(args):
+    """One pinned host pool, as large as the box allows, serves two runs: (a) the 13 B shape at the
+    depth whose whole fp32 state fits in it; (b) the full 40-layer shape with the head of the model
+    cached in HBM and the tail in the host pool."""
+    import torch
+    import paper_2303_02868_amd as apm
+    E = 1 << 20
+    hyper = apm.make_hyper()
+    stream = torch.cuda.current_stream()
+    host = wl = plan = None
+    for layers in (40, 32, 24, 16, 12, 8, 4):
+        wl = Workload("gpt_13b", layers)
+        plan = apm.apm_pack_plan(E, wl.numels)
+        try:
+            host = apm.apm_pool_create(apm.APM_DEV_HOST, E, plan.n_pages, state_mask=apm.FP32_STATES)
+            break
+        except apm.ApmError as e:
+            if e.code != apm.APM_ENOMEM:
+                raise
+    n_host = plan.n_pages
+    out = {"host_pool_pages": n_host, "host_pinned_GB": n_host * E * 12 / 1e9}
+
+    def steps_of(streamer, first, n):
+        apm.apm_streamer_step(streamer, first, hyper, None, None, stream)
+        ts = []
+        for k in range(n):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            apm.apm_streamer_step(streamer, first + 1 + k, hyper, None, None, stream)
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return ts
+
+    # (a) everything in host memory, reduced depth
+    dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_host, state_mask=apm.B16_STATES)
+    apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+    tmp = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_host, state_mask=1 << apm.APM_P32)
+    apm.apm_pack_tensors(tmp, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    apm.apm_page_copy_async(host, 0, tmp, 0, n_host, apm.APM_P32)
+    torch.cuda.synchronize()
+    streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, n_host), args.slots)
+    a = {"layers": wl.layers, "layers_of_full_shape": 40, "params": wl.total, "pages": n_host,
+         "fragmentation": plan.fragmentation, "state": "fp32 p/m/v all in pinned host pages, bf16 g/p16 in HBM"}
+    for name in ("direct", "staged"):
+        apm.apm_streamer_set_mode(streamer, _mode_const(name), args.direct_wavefronts)
+        ts = steps_of(streamer, 1 if name == "direct" else 20, 2)
+        a[name] = {"ms_per_step": _median(ts) * 1e3, "ms_per_step_all": [x * 1e3 for x in ts],
+                   "params_per_s": wl.total / _median(ts),
+                   "pcie_GBps_each_way": wl.total * 12 / _median(ts) / 1e9,
+                   "frac_of_gen5_x16_raw_64GBps": wl.total * 12 / _median(ts) / 1e9 / PCIE_GEN5_X16_RAW_GBPS}
+    a["oracle"] = oracle_sample_timing(wl, plan, 0.0, 0, max_pages=40, steps=2)
+    out["all_state_in_host_memory"] = a
+    streamer.destroy()
+    dev_pool.destroy()
+    tmp.destroy()
+    torch.cuda.empty_cache()
+
+    # (b) the full shape: the head's fp32 state cached in HBM, the tail in the same host pool
+    wl = Workload("gpt_13b", 40)
+    plan = apm.apm_pack_plan(E, wl.numels)
+    N = plan.n_pages
+    n_tail = min(n_host, N)
+    R = N - n_tail
+    dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, N, state_mask=apm.B16_STATES)
+    apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+    p32 = torch.zeros((N, E), dtype=torch.float32, device=DEV)
+    init = apm.apm_pool_create(apm.APM_DEV_GPU, E, N, state_mask=1 << apm.APM_P32, flags=apm.APM_POOL_NO_ZERO,
+                               base={apm.APM_P32: p32})
+    apm.apm_pack_tensors(init, apm.APM_P32, wl.tensors(wl.gen(1, False, 0.02)), wl.n_t)
+    apm.apm_page_copy_async(host, 0, init, R, n_tail, apm.APM_P32)
+    torch.cuda.synchronize()
+    mv = {s_: torch.zeros((max(R, 1), E), dtype=torch.float32, device=DEV) for s_ in (apm.APM_M32, apm.APM_V32)}
+    cache = apm.apm_pool_create(apm.APM_DEV_GPU, E, max(R, 1), state_mask=apm.FP32_STATES,
+                                flags=apm.APM_POOL_NO_ZERO, base={apm.APM_P32: p32, **mv})
+    streamer = apm.apm_streamer_create(host, dev_pool, min(args.batch_pages, N), args.slots)
+    apm.apm_streamer_set_cache(streamer, cache if R else None, R)
+    apm.apm_streamer_set_host_first_page(streamer, R)
+    ts = steps_of(streamer, 1, 2)
+    used_tail = sum(plan_used(plan, N)[R:])
+    out["full_40_layers_head_cached_in_hbm"] = {
+        "params": wl.total, "pages": N, "fragmentation": plan.fragmentation, "resident_pages": R,
+        "host_pages": n_tail, "hbm_cache_GB": R * E * 12 / 1e9, "mode": "direct",
+        "ms_per_step": _median(ts) * 1e3, "ms_per_step_all": [x * 1e3 for x in ts],
+        "params_per_s": wl.total / _median(ts),
+        "pcie_GBps_each_way_host_part": used_tail * 12 / _median(ts) / 1e9,
+        "oracle": oracle_sample_timing(wl, plan, 0.0, 0, max_pages=40, steps=2)}
+    streamer.destroy()
+    for p_ in (cache, init, dev_pool, host):
+        p_.destroy()
+    del p32, mv
+    torch.cuda.empty_cache()
     return out
 
 
@@ -785,6 +1045,11 @@ def main():
             apm.apm_pack_tensors(pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
             out["streamed"] = streamed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
         pool.destroy()
+        torch.cuda.empty_cache()
+        default_run = args.workload == "gpt_1p3b" and not (args.update_only or args.unfused or args.no_configs)
+        if default_run:
+            out["flat_1024pages"] = flat_reference_leg(args)
+            out["configs"] = configs_leg(args)
     else:
         # fp32 state never resident: the GPU pool holds G16/P16 only.  If the box cannot pin the
         # whole fp32 state, the depth of the 13 B shape shrinks until it fits (stated in the output).
@@ -814,7 +1079,7 @@ def main():
         out["steps"] = args.stream_steps
         out["warmup"] = 1
         out["config"]["step"] = ("grad reduce + AdamW kernel reading and writing p,m,v in pinned host pages across PCIe"
-                                 if s["mode"] == "direct" else "H2D p,m,v -> reduce+update -> D2H p,m,v (3 streams)")
+                                 if s["mode"] == "direct" else "copy-in p,m,v -> reduce+update -> copy-out p,m,v through HBM staging slots")
         out["config"]["state"] = "fp32 p/m/v in pinned host pages, bf16 g/p16 resident in HBM"
         dev_pool.destroy()
 

@@ -565,6 +565,18 @@ int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, const apm_hy
                               void* stream);
 
 /*
+ * Whether the one-step-stale form can overlap at all: the runtime maps streams onto a few hardware
+ * queues, and kernels of two streams that share a queue run one after the other.  On the first
+ * apm_step_delayed / apm_streamer_step_delayed call with a given producer stream (and after a mode
+ * change) the library therefore measures, with two spin kernels of half a millisecond, whether
+ * its update stream and the streamer's pipeline streams run beside `stream`, and replaces those
+ * that do not by streams that do; this synchronises the device once.  The report: 1 = runs beside
+ * the producer stream, 0 = no such stream was found (the update then runs after the producer's
+ * work, never wrongly), -1 = not measured yet.  Host pointers, nullable.
+ */
+int apm_streamer_overlap_report(const apm_streamer* s, int* update_stream, int* pipeline_streams);
+
+/*
  * Adds one more gradient into the gradient buffered by the last apm_step_delayed call, before the
  * next call applies it (Alg. 2, buffering thread: g'16 <- g'16 + g16): element-wise
  * bf16_rne(fp32(g') + fp32(g)), the fp32 sum rounded to nearest, over the used extents of the

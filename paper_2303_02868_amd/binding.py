@@ -34,6 +34,7 @@ EXPORTS = [
     "apm_schedule_plan", "apm_file_pool_create", "apm_tiered_create", "apm_tiered_destroy", "apm_tiered_io_bytes", "apm_tiered_set_range", "apm_streamer_set_page_count", "apm_tiered_step", "apm_tiered_step_delayed", "apm_streamer_step_scheduled", "apm_streamer_step_delayed", "apm_streamer_create", "apm_streamer_destroy", "apm_streamer_step", "apm_streamer_copy_only", "apm_streamer_set_cache", "apm_cache_pages_that_fit", "apm_streamer_set_host_first_page", "apm_streamer_set_mode", "apm_streamer_get_mode", "apm_streamer_probe_rates", "apm_step_delayed",
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
     "apm_page_adamw_step_noalloc", "apm_noalloc_scratch_bytes", "apm_noalloc_max_pages",
+    "apm_streamer_overlap_report",
 ]
 
 
@@ -139,6 +140,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_set_mode.argtypes = [vp, i32, i32, i32]
     L.apm_streamer_get_mode.argtypes = [vp]
     L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
+    L.apm_streamer_overlap_report.argtypes = [vp, P(C.c_int), P(C.c_int)]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
     L.apm_delayed_accumulate.argtypes = [vp, P(i64), i64, vp, vp]
     L.apm_delayed_grad_buffer.argtypes = [vp, vp]
@@ -460,6 +462,13 @@ def apm_streamer_step_scheduled(s: Streamer, tasks: Sequence, layer_first_page: 
     la = _i64_array(last_access)[0] if last_access is not None else None
     _check(lib().apm_streamer_step_scheduled(s.handle, arr, len(tasks), lf, n1 - 1, la, step, C.byref(hyper),
                                              _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
+
+
+def apm_streamer_overlap_report(s: Streamer):
+    """(update stream, pipeline streams): 1 runs beside the producer stream, 0 does not, -1 not measured."""
+    a, b = C.c_int(-1), C.c_int(-1)
+    _check(lib().apm_streamer_overlap_report(s.handle, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def apm_streamer_step_delayed(s: Streamer, new_g16, hyper: apm_hyper, stream=None) -> None:

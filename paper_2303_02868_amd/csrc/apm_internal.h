@@ -178,6 +178,11 @@ struct DuplexCopy {
     const char* out_src[3];
     char* out_dst[3];
     int64_t in_bytes, out_bytes;
+    // Optional: move only the used extent of each page.  used = the device page table (elements per
+    // page), *_first_page = the table index of each batch's first page, page_bytes = E * 4.
+    const int32_t* used;
+    int64_t in_first_page, out_first_page, page_bytes;
+    uint32_t items_per_page;  // filled in by launch_duplex_copy
 };
 hipError_t launch_duplex_copy(const DuplexCopy& d, int wavefronts, int per_wg, hipStream_t s);
 
@@ -208,6 +213,7 @@ struct apm_pool {
 
     // one-step-stale update state
     hipStream_t upd_stream = nullptr;
+    bool upd_overlaps = false;  // measured: its kernels run beside the producer stream's
     uint16_t* gbuf[2] = {nullptr, nullptr};
     hipEvent_t ev_staged[2] = {};
     hipEvent_t ev_applied[2] = {};
@@ -242,7 +248,18 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
                  const apm_tensor* p16_tensors = nullptr, int64_t n_tensors = 0);
 int ensure_scratch(apm_pool* pool);
 // Allocates the ping-pong gradient halves, the events and the update stream of the delayed path.
-int ensure_delayed(apm_pool* pool);
+// caller != nullptr-able: the stream the producer works on; the update stream is chosen so that
+// its kernels run beside that stream's (see make_overlapping_stream).
+int ensure_delayed(apm_pool* pool, hipStream_t caller, bool probe);
+
+// Whether kernels on two streams of one process run at the same time is not something the API
+// states: the runtime maps streams onto a few hardware queues, and work of two streams that share
+// a queue runs in order.  These helpers measure it with two short spin kernels (a few hundred
+// microseconds each; both streams are synchronised first).
+int streams_overlap(hipStream_t a, hipStream_t b, bool* out);
+// A new non-blocking stream whose kernels overlap with those of `with`; tries a few candidates and
+// keeps the last one (*overlaps = false) if none does.
+int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps);
 // FILE <-> HOST page copy (synchronous).
 int file_page_copy(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_page, int64_t n_pages,
                    int state, hipStream_t stream);

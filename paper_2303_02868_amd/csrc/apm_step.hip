@@ -1,5 +1,6 @@
 // Host side of the update: scalar preparation, page-list handling, the synchronous step and the
 // one-step-stale (delayed) step.
+#include <chrono>
 #include <cmath>
 
 #include "apm_internal.h"
@@ -222,7 +223,80 @@ int enqueue_step(apm_pool* pool, const int64_t* pages, int64_t n_pages, int64_t 
     return APM_OK;
 }
 
-int ensure_delayed(apm_pool* pool) {
+namespace {
+// Spins for `ticks` of the constant-rate device clock; the iteration cap makes it end regardless.
+__global__ void apm_spin_kernel(long long ticks, int max_iters) {
+    const long long t0 = wall_clock64();
+    for (int i = 0; i < max_iters; ++i) {
+        if (wall_clock64() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(32);
+    }
+}
+}  // namespace
+
+int streams_overlap(hipStream_t a, hipStream_t b, bool* out) {
+    int dev = 0, khz = 0;
+    APM_HIP(hipGetDevice(&dev));
+    APM_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) khz = 100000;
+    constexpr double kSpinMs = 0.5;
+    const long long ticks = (long long)(kSpinMs * khz);
+    const int cap = 20000;  // >= 1 us per iteration: the kernel ends after some tens of ms at most
+    auto both = [&](long long t, double* ms) -> int {
+        APM_HIP(hipStreamSynchronize(a));
+        APM_HIP(hipStreamSynchronize(b));
+        const auto t0 = std::chrono::steady_clock::now();
+        hipLaunchKernelGGL(apm_spin_kernel, dim3(1), dim3(1), 0, a, t, cap);
+        hipLaunchKernelGGL(apm_spin_kernel, dim3(1), dim3(1), 0, b, t, cap);
+        APM_HIP(hipGetLastError());
+        APM_HIP(hipStreamSynchronize(a));
+        APM_HIP(hipStreamSynchronize(b));
+        *ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        return APM_OK;
+    };
+    double warm, ms1, ms2;
+    int rc = both(0, &warm);  // loads the kernel
+    if (rc == APM_OK) rc = both(ticks, &ms1);
+    if (rc == APM_OK) rc = both(ticks, &ms2);
+    if (rc != APM_OK) return rc;
+    const double ms = ms1 < ms2 ? ms1 : ms2;
+    *out = ms < 1.6 * kSpinMs;  // side by side: ~0.5 ms; one after the other: ~1 ms
+    return APM_OK;
+}
+
+int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps) {
+    constexpr int kTries = 6;
+    hipStream_t cand[kTries] = {};
+    int n = 0, pick = -1;
+    int rc = APM_OK;
+    // Rejected candidates stay alive until the choice is made: a destroyed stream's queue slot
+    // would be handed straight to the next one created.
+    for (; n < kTries && pick < 0; ++n) {
+        if (hipStreamCreateWithFlags(&cand[n], hipStreamNonBlocking) != hipSuccess) {
+            (void)hipGetLastError();
+            rc = fail(APM_EDEVICE, "creating a stream failed");
+            break;
+        }
+        bool ok = false;
+        rc = streams_overlap(with, cand[n], &ok);
+        if (rc != APM_OK) { ++n; break; }
+        if (ok) pick = n;
+    }
+    if (rc == APM_OK && pick < 0 && n > 0) pick = n - 1;
+    for (int k = 0; k < n; ++k)
+        if (k != pick && cand[k]) (void)hipStreamDestroy(cand[k]);
+    if (rc != APM_OK) {
+        if (pick >= 0 && cand[pick]) (void)hipStreamDestroy(cand[pick]);
+        return rc;
+    }
+    *out = cand[pick];
+    bool ok = false;
+    rc = streams_overlap(with, cand[pick], &ok);
+    if (overlaps) *overlaps = rc == APM_OK && ok;
+    return APM_OK;
+}
+
+int ensure_delayed(apm_pool* pool, hipStream_t caller, bool probe) {
     if (pool->upd_stream) return APM_OK;
     const size_t bytes = (size_t)pool->desc.n_pages * (size_t)pool->desc.page_elems * 2u;
     for (int k = 0; k < 2; ++k) {
@@ -245,6 +319,9 @@ int ensure_delayed(apm_pool* pool) {
         if (!pool->ev_applied[k]) APM_HIP(hipEventCreateWithFlags(&pool->ev_applied[k], hipEventDisableTiming));
     }
     if (!pool->ev_flush) APM_HIP(hipEventCreateWithFlags(&pool->ev_flush, hipEventDisableTiming));
+    // The update stream must run beside the producer's stream, which is the point of the
+    // one-step-stale form; which streams do is measured, once, here.
+    if (probe) return make_overlapping_stream(caller, &pool->upd_stream, &pool->upd_overlaps);
     APM_HIP(hipStreamCreateWithFlags(&pool->upd_stream, hipStreamNonBlocking));
     return APM_OK;
 }
@@ -265,7 +342,7 @@ static int apply_buffered(apm_pool* pool, const DelayedApply& apply) {
 int delayed_call(apm_pool* pool, const int64_t* pages, int64_t n_pages, const void* new_g16,
                  const apm_hyper* hyper, hipStream_t s, const DelayedApply& apply) {
     APM_HIP(hipSetDevice(pool->desc.hip_device));
-    int rc = ensure_delayed(pool);
+    int rc = ensure_delayed(pool, s, true);
     if (rc != APM_OK) return rc;
     if (pool->buffered) {
         rc = apply_buffered(pool, apply);
@@ -403,7 +480,8 @@ extern "C" void* apm_delayed_grad_buffer(apm_pool* pool, void* stream) {
         fail(APM_EINVAL, "NULL or non-GPU pool");
         return nullptr;
     }
-    if (hipSetDevice(pool->desc.hip_device) != hipSuccess || ensure_delayed(pool) != APM_OK) return nullptr;
+    if (hipSetDevice(pool->desc.hip_device) != hipSuccess ||
+        ensure_delayed(pool, static_cast<hipStream_t>(stream), true) != APM_OK) return nullptr;
     const int nxt = pool->cur ^ 1;
     if (pool->applied_valid[nxt] &&
         hipStreamWaitEvent(static_cast<hipStream_t>(stream), pool->ev_applied[nxt], 0) != hipSuccess) {

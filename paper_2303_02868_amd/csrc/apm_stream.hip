@@ -50,6 +50,11 @@ struct apm_streamer {
     int direct_per_wg = 1;      // how many of them share a workgroup
     float* host_dev[3] = {nullptr, nullptr, nullptr};  // device-side addresses of the host pool's fp32 classes
     std::vector<hipEvent_t> sched_ev;  // events of the scheduled step, grown on demand and reused
+    // one-step-stale form: the producer stream the pipeline's streams were last checked against
+    bool paired = false;
+    hipStream_t paired_with = nullptr;
+    int paired_mode = -1;
+    bool pair_overlaps = false;
 };
 
 using namespace apm;
@@ -415,7 +420,10 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
                     else { d.out_src[k] = g; d.out_dst[k] = h; }
                 }
                 (in ? d.in_bytes : d.out_bytes) = (int64_t)(pb * (size_t)nb);
+                (in ? d.in_first_page : d.out_first_page) = first;
             };
+            d.used = dev->d_used;  // only the used extents cross the link
+            d.page_bytes = (int64_t)pb;
             if (b_in >= 0 && (what & kDoH2D)) fill(b_in, true);
             if (b_out >= 0 && (what & kDoD2H)) fill(b_out, false);
             APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_copy));
@@ -508,6 +516,37 @@ extern "C" int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper*
     });
 }
 
+namespace {
+// The one-step-stale form pays only if the pipeline's kernels run beside the producer's.  Streams
+// that the runtime put on the producer stream's hardware queue are replaced (checked once per
+// producer stream and mode; the streams must be idle, which they are between steps).
+int pair_with_producer(apm_streamer* s, hipStream_t producer) {
+    if (s->paired && s->paired_with == producer && s->paired_mode == s->mode) return APM_OK;
+    APM_HIP(hipDeviceSynchronize());
+    bool all = true;
+    hipStream_t* pipeline[2] = {&s->s_cmp, s->mode == APM_STREAM_STAGED ? &s->s_copy : nullptr};
+    for (hipStream_t* st : pipeline) {
+        if (!st || !*st) continue;
+        bool ok = false;
+        int rc = streams_overlap(producer, *st, &ok);
+        if (rc != APM_OK) return rc;
+        if (!ok) {
+            hipStream_t fresh = nullptr;
+            rc = make_overlapping_stream(producer, &fresh, &ok);
+            if (rc != APM_OK) return rc;
+            (void)hipStreamDestroy(*st);
+            *st = fresh;
+        }
+        all = all && ok;
+    }
+    s->paired = true;
+    s->paired_with = producer;
+    s->paired_mode = s->mode;
+    s->pair_overlaps = all;
+    return APM_OK;
+}
+}  // namespace
+
 // Alg. 2 with the optimizer states off the GPU: the updating side is the streamed step (in direct
 // mode a few dozen wavefronts working through the host pages), the buffering side the caller's
 // stream handing over the next gradient.
@@ -521,12 +560,26 @@ extern "C" int apm_streamer_step_delayed(apm_streamer* s, const void* new_g16, c
         int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
         if (rc != APM_OK) return rc;
         const int64_t N = (int64_t)dev->plan.pages.size();
+        if (s->mode != APM_STREAM_STAGED_DMA) {  // the runtime's copy queues are not ours to place
+            APM_HIP(hipSetDevice(dev->desc.hip_device));
+            rc = pair_with_producer(s, static_cast<hipStream_t>(stream));
+            if (rc != APM_OK) return rc;
+        }
         return delayed_call(dev, nullptr, N, new_g16, hyper, static_cast<hipStream_t>(stream),
                             [&](const uint16_t* g16, int64_t step, hipStream_t upd, const int64_t*, int64_t,
                                 const apm_hyper* b_hyper) {
                                 return run_pipeline(s, kDoH2D | kDoD2H | kDoUpdate, step, b_hyper, dev->delayed_norm,
                                                     dev->delayed_skip, upd, g16);
                             });
+    });
+}
+
+extern "C" int apm_streamer_overlap_report(const apm_streamer* s, int* update_stream, int* pipeline_streams) {
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        if (update_stream) *update_stream = s->dev->upd_stream ? (s->dev->upd_overlaps ? 1 : 0) : -1;
+        if (pipeline_streams) *pipeline_streams = s->paired ? (s->pair_overlaps ? 1 : 0) : -1;
+        return APM_OK;
     });
 }
 

@@ -336,7 +336,7 @@ extern "C" int apm_tiered_step_delayed(apm_tiered* t, const void* new_g16, const
         int rc = prepare_hyper(hyper, 1, &probe);  // validate before any state changes
         if (rc != APM_OK) return rc;
         APM_HIP(hipSetDevice(dev->desc.hip_device));
-        rc = ensure_delayed(dev);
+        rc = ensure_delayed(dev, nullptr, false);  // the updater is a host thread here: no stream to pair
         if (rc != APM_OK) return rc;
         for (int k = 0; k < 2 && new_g16; ++k)  // the updater reads the halves with no stream-side guard
             if (new_g16 == static_cast<const void*>(dev->gbuf[k])) return fail(APM_EINVAL, "the zero-copy hand-over (apm_delayed_grad_buffer) is not available with file-resident state: pass the producer's own buffer");
