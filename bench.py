@@ -1046,7 +1046,8 @@ def main():
             out["streamed"] = streamed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
         pool.destroy()
         torch.cuda.empty_cache()
-        default_run = args.workload == "gpt_1p3b" and not (args.update_only or args.unfused or args.no_configs)
+        default_run = args.workload == "gpt_1p3b" and not (args.update_only or args.unfused or args.no_configs or
+                                                            args.no_streamed)
         if default_run:
             out["flat_1024pages"] = flat_reference_leg(args)
             out["configs"] = configs_leg(args)

@@ -446,7 +446,9 @@ int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* layer_pages,
  * pages were moved; a resident cache is set), APM_EINVAL (layers out of order, a page moved twice,
  * pages or layers left over, a trigger id beyond the layers that precede the task in the list,
  * last_access before a page's own layer).  Results are bit-identical to the other modes.  Stream
- * semantics as apm_streamer_step; does not depend on the streamer's mode.
+ * semantics as apm_streamer_step.  Pages move by the library's copy kernel (used extents only;
+ * incoming and outgoing pages are separate tasks, so one kernel per direction), or by the
+ * runtime's copies if the streamer is in APM_STREAM_STAGED_DMA mode.
  */
 int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
                                 const int64_t* layer_first_page, int64_t n_layers,

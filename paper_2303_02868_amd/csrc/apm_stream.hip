@@ -158,7 +158,12 @@ int ensure_staged(apm_streamer* s, bool dma) {
     int rc = ensure_staging(s);
     if (rc != APM_OK) return rc;
     if (dma && !s->s_in) return pick_copy_streams(s);
-    if (!dma && !s->s_copy) APM_HIP(hipStreamCreateWithFlags(&s->s_copy, hipStreamNonBlocking));
+    if (!dma && !s->s_copy) {
+        // The copy kernels must run beside the update kernels of the compute stream, which streams
+        // that share a hardware queue do not: the copy stream is chosen by measurement.
+        bool ok = false;
+        return make_overlapping_stream(s->s_cmp, &s->s_copy, &ok);
+    }
     return APM_OK;
 }
 
@@ -311,8 +316,10 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         // The resident pages (HBM speed) and the host pages (PCIe speed) are updated side by side
         // on two streams; each part has its own range of the per-page scratch.
         const bool two = R > 0 && R < N;
-        if (two && !s->s_res) {
-            APM_HIP(hipStreamCreateWithFlags(&s->s_res, hipStreamNonBlocking));
+        if (two && !s->s_res) {  // a stream whose kernels run beside the compute stream's (measured)
+            bool ok = false;
+            rc = make_overlapping_stream(s->s_cmp, &s->s_res, &ok);
+            if (rc != APM_OK) return rc;
             APM_HIP(hipEventCreateWithFlags(&s->ev_res, hipEventDisableTiming));
         }
         if (two) APM_HIP(hipStreamWaitEvent(s->s_res, s->ev_start, 0));
@@ -701,6 +708,10 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         rc = ensure_staged(s, true);
         if (rc != APM_OK) return rc;
         APM_HIP(hipSetDevice(dev->desc.hip_device));
+        // The page movement is the library's copy kernel (one per direction: the two directions are
+        // separate tasks here) unless the streamer is in staged-DMA mode or the GPU cannot address
+        // the host pool; then it is the runtime's copies.
+        const bool kcopy = s->mode != APM_STREAM_STAGED_DMA && map_host_classes(s);
 
         // The trace: the layer after whose compute a page's slot is free again (its own layer if
         // no trace is given).  release_at[i] lists, in ascending order, the pages layer i releases.
@@ -835,9 +846,22 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                         last_wait = w;
                     }
                 }
-                for (int c = 0; c < 3; ++c) {
-                    const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
-                    APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s->s_in));
+                if (kcopy) {  // the library's copy kernel, incoming side only: the pages' used extents
+                    DuplexCopy d{};
+                    for (int c = 0; c < 3; ++c) {
+                        d.in_src[c] = reinterpret_cast<const char*>(s->host_dev[c]) + (size_t)p0 * pb;
+                        d.in_dst[c] = reinterpret_cast<char*>(s->stage[c] + (size_t)s0 * (size_t)E);
+                    }
+                    d.in_bytes = (int64_t)(pb * (size_t)n);
+                    d.in_first_page = p0;
+                    d.used = dev->d_used;
+                    d.page_bytes = (int64_t)pb;
+                    APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_in));
+                } else {
+                    for (int c = 0; c < 3; ++c) {
+                        const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
+                        APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s->s_in));
+                    }
                 }
                 hipEvent_t done;
                 rc = new_event(&done);
@@ -886,9 +910,22 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                 const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
                 size_t m = 1;
                 while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
-                for (int c = 0; c < 3; ++c) {
-                    char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)q0 * pb;
-                    APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * m, hipMemcpyDeviceToHost, s->s_out));
+                if (kcopy) {
+                    DuplexCopy d{};
+                    for (int c = 0; c < 3; ++c) {
+                        d.out_src[c] = reinterpret_cast<const char*>(s->stage[c] + (size_t)s0 * (size_t)E);
+                        d.out_dst[c] = reinterpret_cast<char*>(s->host_dev[c]) + (size_t)q0 * pb;
+                    }
+                    d.out_bytes = (int64_t)(pb * m);
+                    d.out_first_page = q0;
+                    d.used = dev->d_used;
+                    d.page_bytes = (int64_t)pb;
+                    APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_out));
+                } else {
+                    for (int c = 0; c < 3; ++c) {
+                        char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)q0 * pb;
+                        APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * m, hipMemcpyDeviceToHost, s->s_out));
+                    }
                 }
                 j += m;
             }

@@ -337,8 +337,8 @@ def layer_ranges(model):
     return bounds
 
 
-@pytest.mark.parametrize("budget_layers", [1.0, 2.5, 100.0])
-def test_scheduled_step_equals_resident_bit_exact(budget_layers):
+@pytest.mark.parametrize("budget_layers,mover", [(1.0, "kernel"), (2.5, "kernel"), (100.0, "kernel"), (2.5, "dma")])
+def test_scheduled_step_equals_resident_bit_exact(budget_layers, mover):
     # the page movement follows the life-time based schedule (Alg. 1 phase 1) planned for a GPU
     # memory of `budget_layers` times the largest layer; results must not depend on it
     f, E = synth.WORKLOADS["gpt2_small_124m"]
@@ -363,6 +363,8 @@ def test_scheduled_step_equals_resident_bit_exact(budget_layers):
     apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
     apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
     st = apm.apm_streamer_create(host, dev.pool, (slots + 1) // 2, 2)   # staging: at least the planned slots
+    if mover == "dma":          # pages moved by the runtime's copies instead of the library's copy kernel
+        apm.apm_streamer_set_mode(st, apm.APM_STREAM_STAGED_DMA)
     norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
     for t in range(1, 4):
