@@ -437,18 +437,22 @@ int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* layer_pages,
  * layer's pages, then copies the pages whose last access it is back to the host pool and frees
  * their slots.  Movement tasks over consecutive pages and slots with one trigger id are merged
  * into one copy per class.
- * Dispatch is event-driven (Sec. 5 "Unified Scheduler"): a movement task is issued only when
+ * Dispatch is event-driven (Sec. 5 "Unified Scheduler"): a movement task is never issued before
  * execution has reached its trigger_id -- the layer before it has computed (trigger 0: the start
- * of the step) -- and the slots it moves into have been written back; a compute starts when the
- * movements of its pages have completed; a write-back when its compute has.
+ * of the step) -- nor before the slots it moves into have been written back; a compute starts
+ * when the movements of its pages have completed; a write-back when its compute has.  A movement
+ * may be issued later than its trigger allows: with the library's copy kernel as the mover, a
+ * movement that is due waits for the next write-back and crosses the link in the same kernel (the
+ * two directions in one kernel are a fifth faster than in two), at the latest two layers ahead of
+ * the compute that needs its page, or right before that compute if it was not due earlier.
  * The schedule is replayed on the host first and nothing is enqueued if it is unsound:
  * APM_ENOMEM (a movement task finds no free slot), APM_ESTATE (a layer computes before all its
  * pages were moved; a resident cache is set), APM_EINVAL (layers out of order, a page moved twice,
  * pages or layers left over, a trigger id beyond the layers that precede the task in the list,
  * last_access before a page's own layer).  Results are bit-identical to the other modes.  Stream
- * semantics as apm_streamer_step.  Pages move by the library's copy kernel (used extents only;
- * incoming and outgoing pages are separate tasks, so one kernel per direction), or by the
- * runtime's copies if the streamer is in APM_STREAM_STAGED_DMA mode.
+ * semantics as apm_streamer_step.  Pages move by the library's copy kernel (used extents only),
+ * or by the runtime's copies, each movement issued at its trigger, if the streamer is in
+ * APM_STREAM_STAGED_DMA mode or the GPU cannot address the host pool.
  */
 int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
                                 const int64_t* layer_first_page, int64_t n_layers,

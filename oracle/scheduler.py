@@ -1,25 +1,31 @@
 """ORACLE (test infrastructure): phase 1 of the life-time based scheduling algorithm (Alg. 1).
 
-Alg. 1 takes the model as a list of layers, the trace of each tensor (here: of each page -- the
-logical id of the layer that accesses it last, after which its GPU memory is free again,
-Sec. 4.2 "Tensor Life-Time"), and the GPU memory, and produces a list of tasks
-{operation, page or layer, trigger_id}.  Phase 1: every page's move_to_gpu is put at the start of
-the schedule; then, layer by layer, movement tasks are taken off the end of the schedule while the
-memory left is less than the layer needs, the layer's compute is appended, and deferred pages are
-put back (most recently deferred first) while more than one page of memory is left.  Phase 2 only
-re-times all_gather tasks; on one GPU there are none, so it does nothing and is left out.
+What the algorithm is for (Sec. 4.2, "Tensor Life-Time" and "Life-time based Scheduling"): the
+model is a list of layers, every page has a trace -- here the index of the layer that accesses it
+last, after which its GPU memory is free again -- and the GPU has a fixed amount of memory.  The
+output is one list of tasks {operation, page or layer, trigger_id} that the executor walks in
+order; a task may start once the compute task named by its trigger id has been reached.
 
-The steps below follow the listing's order and its notation (S, wait_stack,
-get_available_memory).  Where the listing is silent, this build reads it as follows:
+How phase 1 gets there, as this build understands it: the plan starts out as optimistic as it can
+be -- every page is brought to the GPU before anything computes -- and is then corrected layer by
+layer.  A layer that does not fit next to everything the plan has on the GPU by then pushes the
+*latest* planned movements back (they are the ones needed furthest in the future), onto a stack;
+once the layer has computed and the pages that die with it are gone, the stack is unwound for as
+long as more than one page of memory stays free, most recently deferred page first.  Phase 2 only
+re-times all_gather tasks; on one GPU there are none, so it is left out.
+
+Three things the paper does not say, and how they are read here:
   * size(l_i) is the memory the layer's computation needs besides its parameter pages;
-  * get_available_memory(S, traces) is the GPU memory minus one page for every page that S moves
-    in and whose last-access layer has no compute task in S yet;
-  * a page of l_i that is still on the wait_stack when l_i's turn comes is moved on demand: its
-    move_to_gpu is appended with trigger i before the memory check (the listing would otherwise
-    compute a layer whose page never arrived);
-  * taking a movement task off S is refused (OutOfMemory) when the page belongs to the current
-    or an earlier layer: those pages are needed now or are still alive, so no schedule exists.
+  * the memory still available after a plan S (`get_available_memory`) is the GPU memory minus one
+    page for every page that S moves in and whose last-access layer has no compute task in S yet;
+  * a page of layer i that is still deferred when layer i's turn comes is brought in then, with
+    trigger i, before the fit test (otherwise the layer would compute without it), and deferring a
+    page that belongs to the current or an earlier layer is refused as out of memory (it is needed
+    now, or is still alive, so no plan exists).
 Each page belongs to exactly one layer's page_list (the layer of its first access).
+
+The planner below keeps its memory account incrementally (`_Account`) and checks it, at every
+layer, against `get_available_memory`, which is the definition evaluated on the task list itself.
 """
 from __future__ import annotations
 
@@ -55,23 +61,66 @@ def get_available_memory(S: Sequence[Task], traces: Dict[int, int], gpu_memory: 
     return gpu_memory - page_size * len(resident)
 
 
+class _Account:
+    """Pages the plan has on the GPU, grouped by the layer whose compute releases them."""
+
+    def __init__(self, traces: Dict[int, int], gpu_memory: int, page_size: int):
+        self.traces, self.gpu_memory, self.page_size = traces, gpu_memory, page_size
+        self.dies_with: Dict[int, set] = {}
+        self.n_resident = 0
+
+    def planned(self, page: int) -> None:
+        self.dies_with.setdefault(self.traces[page], set()).add(page)
+        self.n_resident += 1
+
+    def deferred(self, page: int) -> None:
+        self.dies_with[self.traces[page]].remove(page)
+        self.n_resident -= 1
+
+    def computed(self, layer: int) -> None:
+        self.n_resident -= len(self.dies_with.pop(layer, ()))
+
+    @property
+    def available(self) -> int:
+        return self.gpu_memory - self.page_size * self.n_resident
+
+
 def schedule(model: Sequence[Layer], traces: Dict[int, int], gpu_memory: int, page_size: int) -> List[Task]:
     """Alg. 1, phase 1.  traces[page] = index of the layer that accesses the page last."""
-    owner = {page: i for i, l in enumerate(model) for page in l.page_list}
+    first_access = {page: i for i, layer in enumerate(model) for page in layer.page_list}
+    account = _Account(traces, gpu_memory, page_size)
     S: List[Task] = []
-    wait_stack: List[int] = []
-    for l_i in model:
-        for page in l_i.page_list:
-            S.append(Task(MOVE_TO_GPU, page, 0))
-    for i, l_i in enumerate(model):
-        while wait_stack and owner[wait_stack[-1]] == i:          # on demand (reading, see above)
-            S.append(Task(MOVE_TO_GPU, wait_stack.pop(), i))
-        while get_available_memory(S, traces, gpu_memory, page_size) < l_i.size:
-            last = max((k for k, t in enumerate(S) if t.operation == MOVE_TO_GPU), default=None)
-            if last is None or owner[S[last].target] <= i:
+    movements: List[int] = []       # positions in S of the movement tasks, in the order of S
+    wait_stack: List[int] = []      # deferred pages; the most recently deferred one is on top
+
+    def plan_move(page: int, trigger: int) -> None:
+        movements.append(len(S))
+        S.append(Task(MOVE_TO_GPU, page, trigger))
+        account.planned(page)
+
+    # the optimistic start: everything is on the GPU before the first layer computes
+    for layer in model:
+        for page in layer.page_list:
+            plan_move(page, 0)
+
+    for i, layer in enumerate(model):
+        # pages of this very layer that are still deferred cannot wait any longer
+        while wait_stack and first_access[wait_stack[-1]] == i:
+            plan_move(wait_stack.pop(), i)
+        # make room: the movement planned last is the one that can wait longest
+        while account.available < layer.size:
+            if not movements or first_access[S[movements[-1]].target] <= i:
                 raise OutOfMemory(f"layer {i} does not fit")
-            wait_stack.append(S.pop(last).target)
+            page = S.pop(movements.pop()).target
+            # a movement is always the last task of S at this point or is followed by computes
+            # only; removing it shifts those computes, whose positions nothing refers to
+            account.deferred(page)
+            wait_stack.append(page)
+        assert account.available == get_available_memory(S, traces, gpu_memory, page_size)
         S.append(Task(COMPUTE, i, i))
-        while wait_stack and get_available_memory(S, traces, gpu_memory, page_size) > page_size:
-            S.append(Task(MOVE_TO_GPU, wait_stack.pop(), i))
+        account.computed(i)
+        # the layer's memory is free again: unwind the stack while more than a page stays free
+        while wait_stack and account.available > page_size:
+            plan_move(wait_stack.pop(), i)
+        assert account.available == get_available_memory(S, traces, gpu_memory, page_size)
     return S

@@ -146,7 +146,7 @@ extern "C" int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* la
         S.reserve((size_t)(2 * n_pages + n_layers));
         std::vector<int64_t> move_at;  // positions in S of the live movement tasks, in sequence order
         move_at.reserve((size_t)n_pages);
-        int64_t resident = 0, peak = 0;
+        int64_t resident = 0;
         auto push_move = [&](int64_t trigger) {  // the next page of the sequence
             const int64_t p = layer_pages[(int64_t)move_at.size()];
             move_at.push_back((int64_t)S.size());
@@ -166,8 +166,6 @@ extern "C" int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* la
                 move_at.pop_back();
                 --resident;
             }
-            const int64_t need = page_bytes * resident + layer_bytes[i];
-            if (need > peak) peak = need;
             S.push_back({apm_task{APM_TASK_COMPUTE, (int32_t)i, i}, true});
             resident -= released[(size_t)i];
             while ((int64_t)move_at.size() < n_pages && available() > page_bytes) push_move(i);
@@ -175,7 +173,19 @@ extern "C" int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* la
         const int64_t need_tasks = n_pages + n_layers;
         const int64_t cap = *n_tasks;
         *n_tasks = need_tasks;
-        if (peak_bytes) *peak_bytes = peak;
+        if (peak_bytes) {
+            // measured on the finished schedule: a later layer may have taken back movements that
+            // were still planned ahead of an earlier compute when that compute was appended
+            int64_t on_gpu = 0, peak = 0;
+            for (const Slot& sl : S) {
+                if (!sl.live) continue;
+                if (sl.t.op == APM_TASK_MOVE_TO_GPU) { ++on_gpu; continue; }
+                const int64_t need = page_bytes * on_gpu + layer_bytes[sl.t.target];
+                if (need > peak) peak = need;
+                on_gpu -= released[(size_t)sl.t.target];
+            }
+            *peak_bytes = peak;
+        }
         if (!tasks && cap == 0) return APM_OK;
         if (cap < need_tasks) return fail(APM_ERANGE, "task buffer holds %lld entries, %lld needed", (long long)cap, (long long)need_tasks);
         if (!tasks) return fail(APM_EINVAL, "tasks is NULL but *n_tasks is %lld", (long long)cap);

@@ -257,9 +257,9 @@ int ensure_delayed(apm_pool* pool, hipStream_t caller, bool probe);
 // a queue runs in order.  These helpers measure it with two short spin kernels (a few hundred
 // microseconds each; both streams are synchronised first).
 int streams_overlap(hipStream_t a, hipStream_t b, bool* out);
-// A new non-blocking stream whose kernels overlap with those of `with`; tries a few candidates and
-// keeps the last one (*overlaps = false) if none does.
-int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps);
+// A new non-blocking stream whose kernels overlap with those of `with` (and of `*also`, if given);
+// tries a few candidates and keeps the last one (*overlaps = false) if none does.
+int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps, const hipStream_t* also = nullptr);
 // FILE <-> HOST page copy (synchronous).
 int file_page_copy(apm_pool* dst, int64_t dst_page, apm_pool* src, int64_t src_page, int64_t n_pages,
                    int state, hipStream_t stream);

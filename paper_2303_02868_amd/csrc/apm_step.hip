@@ -264,8 +264,8 @@ int streams_overlap(hipStream_t a, hipStream_t b, bool* out) {
     return APM_OK;
 }
 
-int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps) {
-    constexpr int kTries = 6;
+int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps, const hipStream_t* also) {
+    constexpr int kTries = 8;
     hipStream_t cand[kTries] = {};
     int n = 0, pick = -1;
     int rc = APM_OK;
@@ -279,6 +279,7 @@ int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps) 
         }
         bool ok = false;
         rc = streams_overlap(with, cand[n], &ok);
+        if (rc == APM_OK && ok && also) rc = streams_overlap(*also, cand[n], &ok);
         if (rc != APM_OK) { ++n; break; }
         if (ok) pick = n;
     }
@@ -292,6 +293,7 @@ int make_overlapping_stream(hipStream_t with, hipStream_t* out, bool* overlaps) 
     *out = cand[pick];
     bool ok = false;
     rc = streams_overlap(with, cand[pick], &ok);
+    if (rc == APM_OK && ok && also) rc = streams_overlap(*also, cand[pick], &ok);
     if (overlaps) *overlaps = rc == APM_OK && ok;
     return APM_OK;
 }

@@ -24,6 +24,7 @@
 // enqueues copy-in one batch ahead of the matching update and copy-out.
 #include <algorithm>
 #include <chrono>
+#include <deque>
 
 #include "apm_internal.h"
 
@@ -683,7 +684,7 @@ extern "C" int apm_streamer_set_host_first_page(apm_streamer* s, int64_t first_m
 // memory is the GPU memory the schedule was planned for, one page slot per page; a movement task
 // takes the lowest free slot, a compute task updates its layer's pages where they sit, writes them
 // back and frees their slots.  The whole schedule is checked on the host before anything is
-// enqueued.  Cross-stream edges: a copy-in waits for the write-back that freed its slots, a
+// enqueued.  Edges: a copy-in waits for its trigger and for the write-back that freed its slots, a
 // compute for the copy-ins of its pages, a write-back for its compute.
 extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* tasks, int64_t n_tasks,
                                            const int64_t* layer_first_page, int64_t n_layers,
@@ -705,13 +706,13 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         AdamwLaunch L{};
         int rc = prepare_hyper(hyper, step, &L);
         if (rc != APM_OK) return rc;
-        rc = ensure_staged(s, true);
-        if (rc != APM_OK) return rc;
         APM_HIP(hipSetDevice(dev->desc.hip_device));
-        // The page movement is the library's copy kernel (one per direction: the two directions are
-        // separate tasks here) unless the streamer is in staged-DMA mode or the GPU cannot address
-        // the host pool; then it is the runtime's copies.
+        // The page movement is the library's copy kernel unless the streamer is in staged-DMA mode or
+        // the GPU cannot address the host pool; then it is the runtime's copies.
         const bool kcopy = s->mode != APM_STREAM_STAGED_DMA && map_host_classes(s);
+        rc = ensure_staged(s, !kcopy);
+        if (rc != APM_OK) return rc;
+        hipStream_t s_in = kcopy ? s->s_copy : s->s_in, s_out = kcopy ? s->s_copy : s->s_out;
 
         // The trace: the layer after whose compute a page's slot is free again (its own layer if
         // no trace is given).  release_at[i] lists, in ascending order, the pages layer i releases.
@@ -782,9 +783,9 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
             return APM_OK;
         };
         APM_HIP(hipEventRecord(s->ev_start, caller));
-        APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_start, 0));
+        APM_HIP(hipStreamWaitEvent(s_in, s->ev_start, 0));
         APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_start, 0));
-        APM_HIP(hipStreamWaitEvent(s->s_out, s->ev_start, 0));
+        APM_HIP(hipStreamWaitEvent(s_out, s->ev_start, 0));
 
         // the slot of every page, for the kernels (fp32 classes are addressed by slot, 16-bit ones by page)
         int slots_ring_slot = -1;
@@ -821,59 +822,11 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         // computed (t = 0: the start of the step).  A movement task waits for reached[trigger_id]
         // (event-driven dispatch, Sec. 5 "Unified Scheduler") besides the slots it moves into.
         std::vector<hipEvent_t> reached((size_t)n_layers + 1, nullptr);
-        int64_t copy_in_at = 0;  // the logical time the copy-in stream is known to have passed
         hipEvent_t last_computed = nullptr;
-        int64_t k = 0;
-        while (k < n_tasks) {
-            if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
-                // a run of movement tasks over consecutive pages and consecutive slots with one
-                // trigger id is one copy per class
-                const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
-                const int32_t trig = tasks[k].trigger_id;
-                int64_t n = 1;
-                while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
-                       slot_seq[(size_t)(p0 + n)] == s0 + n && tasks[k + n].trigger_id == trig)
-                    ++n;
-                if (trig > copy_in_at) {  // the copy-in stream is in order: earlier waits still hold
-                    APM_HIP(hipStreamWaitEvent(s->s_in, reached[(size_t)trig], 0));
-                    copy_in_at = trig;
-                }
-                hipEvent_t last_wait = nullptr;
-                for (int64_t j = 0; j < n; ++j) {
-                    hipEvent_t w = slot_free[(size_t)(s0 + j)];
-                    if (w && w != last_wait) {
-                        APM_HIP(hipStreamWaitEvent(s->s_in, w, 0));
-                        last_wait = w;
-                    }
-                }
-                if (kcopy) {  // the library's copy kernel, incoming side only: the pages' used extents
-                    DuplexCopy d{};
-                    for (int c = 0; c < 3; ++c) {
-                        d.in_src[c] = reinterpret_cast<const char*>(s->host_dev[c]) + (size_t)p0 * pb;
-                        d.in_dst[c] = reinterpret_cast<char*>(s->stage[c] + (size_t)s0 * (size_t)E);
-                    }
-                    d.in_bytes = (int64_t)(pb * (size_t)n);
-                    d.in_first_page = p0;
-                    d.used = dev->d_used;
-                    d.page_bytes = (int64_t)pb;
-                    APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_in));
-                } else {
-                    for (int c = 0; c < 3; ++c) {
-                        const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
-                        APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s->s_in));
-                    }
-                }
-                hipEvent_t done;
-                rc = new_event(&done);
-                if (rc != APM_OK) return rc;
-                APM_HIP(hipEventRecord(done, s->s_in));
-                for (int64_t j = 0; j < n; ++j) page_in[(size_t)(p0 + j)] = done;
-                k += n;
-                continue;
-            }
-            const int64_t i = tasks[k].target;
+        // one layer's reduce + update on the compute stream, once its pages have arrived; records
+        // logical time i + 1, which is also what the write-back of the pages released here waits for
+        auto compute_layer = [&](int64_t i, hipEvent_t* computed) -> int {
             const int64_t first = layer_first_page[i], n = layer_first_page[i + 1] - first;
-            ++k;
             if (n > 0) {
                 hipEvent_t last_wait = nullptr;
                 for (int64_t j = 0; j < n; ++j) {
@@ -893,51 +846,218 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                 else APM_HIP(launch_prepare(C, s->s_cmp));
                 APM_HIP(launch_adamw(C, s->s_cmp));
             }
-            // logical time i + 1; also what the write-back of the pages released here waits for
-            hipEvent_t computed;
-            rc = new_event(&computed);
-            if (rc != APM_OK) return rc;
-            APM_HIP(hipEventRecord(computed, s->s_cmp));
-            reached[(size_t)i + 1] = computed;
-            last_computed = computed;
-            const std::vector<int64_t>& rel = release_at[(size_t)i];
-            if (rel.empty()) continue;
-            hipEvent_t written;
-            rc = new_event(&written);
-            if (rc != APM_OK) return rc;
-            APM_HIP(hipStreamWaitEvent(s->s_out, computed, 0));
-            for (size_t j = 0; j < rel.size();) {  // write back in runs of consecutive pages and slots
-                const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
-                size_t m = 1;
-                while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
-                if (kcopy) {
+            int rc2 = new_event(computed);
+            if (rc2 != APM_OK) return rc2;
+            APM_HIP(hipEventRecord(*computed, s->s_cmp));
+            reached[(size_t)i + 1] = *computed;
+            last_computed = *computed;
+            return APM_OK;
+        };
+
+        if (kcopy) {
+            // One copy stream, and one kernel per exchange: the write-back of the pages a layer
+            // releases travels together with movement tasks that are due, so that the link carries
+            // both directions inside one kernel (two kernels, one per direction, reach four fifths
+            // of that).  A movement task is never issued before its trigger id is reached, but it
+            // may be issued later: it is held back until a write-back can take it along, two layers
+            // ahead of the compute that needs its page (one layer ahead would put every compute
+            // between two copy kernels), or, at the latest, right before that compute.  Slots need
+            // no events here: the write-back that frees a slot precedes, in this one stream, the
+            // movement that reuses it, because it precedes it in the task list.
+            struct Run { int64_t p0, s0, n; int32_t trig; };
+            std::deque<Run> pend;                         // movement tasks not yet issued, in list order
+            std::vector<uint8_t> pending((size_t)N, 0);
+            int64_t copy_at = 0;                          // logical time the copy stream is known to have passed
+            auto take = [&](int64_t want, std::vector<Run>* out) {
+                while (want > 0 && !pend.empty()) {
+                    Run& r = pend.front();
+                    const int64_t n = r.n < want ? r.n : want;
+                    out->push_back(Run{r.p0, r.s0, n, r.trig});
+                    for (int64_t q = 0; q < n; ++q) pending[(size_t)(r.p0 + q)] = 0;
+                    r.p0 += n;
+                    r.s0 += n;
+                    r.n -= n;
+                    want -= n;
+                    if (r.n == 0) pend.pop_front();
+                }
+            };
+            // pages at the front of pend up to and including the last pending page of layers [a, b]
+            auto pages_through = [&](int64_t a, int64_t b) -> int64_t {
+                if (b >= n_layers) b = n_layers - 1;
+                int64_t last = -1;
+                for (int64_t q = layer_first_page[a]; q < layer_first_page[b + 1]; ++q)
+                    if (pending[(size_t)q]) last = q;
+                if (last < 0) return 0;
+                int64_t n = 0;
+                for (const Run& r : pend) {
+                    if (last >= r.p0 && last < r.p0 + r.n) return n + (last - r.p0 + 1);
+                    n += r.n;
+                }
+                return n;
+            };
+            auto exchange = [&](const std::vector<Run>& in, const std::vector<Run>& out) -> int {
+                int32_t trig = 0;
+                for (const Run& r : in) trig = r.trig > trig ? r.trig : trig;
+                if (trig > copy_at) {
+                    APM_HIP(hipStreamWaitEvent(s_in, reached[(size_t)trig], 0));
+                    copy_at = trig;
+                }
+                // pieces of equal page counts in the two directions, cut where either list's run ends,
+                // so that every launch is busy both ways; what one list has left over goes alone
+                size_t xi = 0, xo = 0;
+                int64_t used_i = 0, used_o = 0;  // pages of the current runs already launched
+                while (xi < in.size() || xo < out.size()) {
+                    const int64_t left_i = xi < in.size() ? in[xi].n - used_i : 0;
+                    const int64_t left_o = xo < out.size() ? out[xo].n - used_o : 0;
+                    const int64_t n = left_i == 0 ? left_o : left_o == 0 ? left_i : (left_i < left_o ? left_i : left_o);
                     DuplexCopy d{};
-                    for (int c = 0; c < 3; ++c) {
-                        d.out_src[c] = reinterpret_cast<const char*>(s->stage[c] + (size_t)s0 * (size_t)E);
-                        d.out_dst[c] = reinterpret_cast<char*>(s->host_dev[c]) + (size_t)q0 * pb;
-                    }
-                    d.out_bytes = (int64_t)(pb * m);
-                    d.out_first_page = q0;
                     d.used = dev->d_used;
                     d.page_bytes = (int64_t)pb;
-                    APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_out));
-                } else {
+                    if (left_i > 0) {
+                        const int64_t p0 = in[xi].p0 + used_i, s0 = in[xi].s0 + used_i;
+                        for (int c = 0; c < 3; ++c) {
+                            d.in_src[c] = reinterpret_cast<const char*>(s->host_dev[c]) + (size_t)p0 * pb;
+                            d.in_dst[c] = reinterpret_cast<char*>(s->stage[c] + (size_t)s0 * (size_t)E);
+                        }
+                        d.in_bytes = (int64_t)(pb * (size_t)n);
+                        d.in_first_page = p0;
+                        used_i += n;
+                        if (used_i == in[xi].n) { ++xi; used_i = 0; }
+                    }
+                    if (left_o > 0) {
+                        const int64_t p0 = out[xo].p0 + used_o, s0 = out[xo].s0 + used_o;
+                        for (int c = 0; c < 3; ++c) {
+                            d.out_src[c] = reinterpret_cast<const char*>(s->stage[c] + (size_t)s0 * (size_t)E);
+                            d.out_dst[c] = reinterpret_cast<char*>(s->host_dev[c]) + (size_t)p0 * pb;
+                        }
+                        d.out_bytes = (int64_t)(pb * (size_t)n);
+                        d.out_first_page = p0;
+                        used_o += n;
+                        if (used_o == out[xo].n) { ++xo; used_o = 0; }
+                    }
+                    APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s_in));
+                }
+                if (!in.empty()) {
+                    hipEvent_t done;
+                    int rc2 = new_event(&done);
+                    if (rc2 != APM_OK) return rc2;
+                    APM_HIP(hipEventRecord(done, s_in));
+                    for (const Run& r : in)
+                        for (int64_t q = 0; q < r.n; ++q) page_in[(size_t)(r.p0 + q)] = done;
+                }
+                return APM_OK;
+            };
+            int64_t k = 0;
+            while (k < n_tasks) {
+                if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
+                    const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
+                    const int32_t trig = tasks[k].trigger_id;
+                    int64_t n = 1;
+                    while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
+                           slot_seq[(size_t)(p0 + n)] == s0 + n && tasks[k + n].trigger_id == trig)
+                        ++n;
+                    pend.push_back(Run{p0, s0, n, trig});
+                    for (int64_t q = 0; q < n; ++q) pending[(size_t)(p0 + q)] = 1;
+                    k += n;
+                    continue;
+                }
+                const int64_t i = tasks[k].target;
+                ++k;
+                {   // what this layer still waits for goes now, alone
+                    std::vector<Run> in;
+                    take(pages_through(i, i), &in);
+                    rc = exchange(in, {});
+                    if (rc != APM_OK) return rc;
+                }
+                hipEvent_t computed;
+                rc = compute_layer(i, &computed);
+                if (rc != APM_OK) return rc;
+                const std::vector<int64_t>& rel = release_at[(size_t)i];
+                if (rel.empty()) continue;
+                std::vector<Run> out, in;
+                for (size_t j = 0; j < rel.size();) {  // runs of consecutive pages and slots
+                    const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
+                    size_t m = 1;
+                    while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
+                    out.push_back(Run{q0, s0, (int64_t)m, 0});
+                    j += m;
+                }
+                const int64_t ahead = pages_through(i + 1, i + 2);
+                take(ahead > (int64_t)rel.size() ? ahead : (int64_t)rel.size(), &in);
+                APM_HIP(hipStreamWaitEvent(s_in, computed, 0));
+                copy_at = i + 1;
+                rc = exchange(in, out);
+                if (rc != APM_OK) return rc;
+            }
+            if (!pend.empty()) return fail(APM_ESTATE, "internal: movement tasks left over after the last compute");
+        } else {
+            int64_t copy_in_at = 0;  // the logical time the copy-in stream is known to have passed
+            int64_t k = 0;
+            while (k < n_tasks) {
+                if (tasks[k].op == APM_TASK_MOVE_TO_GPU) {
+                    // a run of movement tasks over consecutive pages and consecutive slots with one
+                    // trigger id is one copy per class
+                    const int64_t p0 = tasks[k].target, s0 = slot_seq[(size_t)p0];
+                    const int32_t trig = tasks[k].trigger_id;
+                    int64_t n = 1;
+                    while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
+                           slot_seq[(size_t)(p0 + n)] == s0 + n && tasks[k + n].trigger_id == trig)
+                        ++n;
+                    if (trig > copy_in_at) {  // the copy-in stream is in order: earlier waits still hold
+                        APM_HIP(hipStreamWaitEvent(s_in, reached[(size_t)trig], 0));
+                        copy_in_at = trig;
+                    }
+                    hipEvent_t last_wait = nullptr;
+                    for (int64_t j = 0; j < n; ++j) {
+                        hipEvent_t w = slot_free[(size_t)(s0 + j)];
+                        if (w && w != last_wait) {
+                            APM_HIP(hipStreamWaitEvent(s_in, w, 0));
+                            last_wait = w;
+                        }
+                    }
+                    for (int c = 0; c < 3; ++c) {
+                        const char* src = static_cast<const char*>(host->base[states[c]]) + (size_t)p0 * pb;
+                        APM_HIP(hipMemcpyAsync(s->stage[c] + (size_t)s0 * (size_t)E, src, pb * (size_t)n, hipMemcpyHostToDevice, s_in));
+                    }
+                    hipEvent_t done;
+                    rc = new_event(&done);
+                    if (rc != APM_OK) return rc;
+                    APM_HIP(hipEventRecord(done, s_in));
+                    for (int64_t j = 0; j < n; ++j) page_in[(size_t)(p0 + j)] = done;
+                    k += n;
+                    continue;
+                }
+                const int64_t i = tasks[k].target;
+                ++k;
+                hipEvent_t computed;
+                rc = compute_layer(i, &computed);
+                if (rc != APM_OK) return rc;
+                const std::vector<int64_t>& rel = release_at[(size_t)i];
+                if (rel.empty()) continue;
+                hipEvent_t written;
+                rc = new_event(&written);
+                if (rc != APM_OK) return rc;
+                APM_HIP(hipStreamWaitEvent(s_out, computed, 0));
+                for (size_t j = 0; j < rel.size();) {  // write back in runs of consecutive pages and slots
+                    const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
+                    size_t m = 1;
+                    while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
                     for (int c = 0; c < 3; ++c) {
                         char* dst = static_cast<char*>(host->base[states[c]]) + (size_t)q0 * pb;
-                        APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * m, hipMemcpyDeviceToHost, s->s_out));
+                        APM_HIP(hipMemcpyAsync(dst, s->stage[c] + (size_t)s0 * (size_t)E, pb * m, hipMemcpyDeviceToHost, s_out));
                     }
+                    j += m;
                 }
-                j += m;
+                APM_HIP(hipEventRecord(written, s_out));
+                for (int64_t q : rel) slot_free[(size_t)slot_seq[(size_t)q]] = written;
             }
-            APM_HIP(hipEventRecord(written, s->s_out));
-            for (int64_t q : rel) slot_free[(size_t)slot_seq[(size_t)q]] = written;
         }
         rc = dev->ring.seal(slots_ring_slot, s->s_cmp);
         if (rc != APM_OK) return rc;
         // every copy-in feeds a compute and every page a write-back; the copy-out stream also waits
         // for the last compute, so it ends last
-        if (last_computed) APM_HIP(hipStreamWaitEvent(s->s_out, last_computed, 0));
-        APM_HIP(hipEventRecord(s->ev_done, s->s_out));
+        if (last_computed) APM_HIP(hipStreamWaitEvent(s_out, last_computed, 0));
+        APM_HIP(hipEventRecord(s->ev_done, s_out));
         APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
         return APM_OK;
     });

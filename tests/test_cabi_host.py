@@ -154,6 +154,7 @@ def test_schedule_plan_equals_oracle_on_random_traces(reuse):
         cuts = sorted(rng.randint(0, len(ids)) for _ in range(n_layers - 1))
         lists = [ids[a:b] for a, b in zip([0] + cuts, cuts + [len(ids)])]
         layers = [(pl, rng.randint(0, 9)) for pl in lists]
+        own_of = {p: i for i, (pl, _) in enumerate(layers) for p in pl}
         last = None
         if reuse:
             own = {p: i for i, (pl, _) in enumerate(layers) for p in pl}
@@ -170,6 +171,11 @@ def test_schedule_plan_equals_oracle_on_random_traces(reuse):
         got, peak = apm.apm_schedule_plan(layers, last, page_bytes, memory)
         assert got == want
         assert peak <= memory
+        # and against what the algorithm guarantees, checked on the library's task list alone
+        import schedule_properties as props
+        la = last if last is not None else [own_of[p] for p in range(len(ids))]
+        tuples = [(props.MOVE if op == apm.APM_TASK_MOVE_TO_GPU else props.COMPUTE, t, g) for op, t, g in got]
+        assert props.check(tuples, layers, dict(enumerate(la)), memory, page_bytes) == peak
         n_ok += 1
     assert n_ok > 80 and n_oom > 80
 

@@ -1,5 +1,7 @@
 """Pins for the oracle's phase-1 scheduler (Alg. 1): hand-worked schedules, an independent replay
-of the schedule against the memory budget, special cases, and brute force on feasibility."""
+of the schedule against the memory budget, a check of the finished task list against the
+algorithm's two placement rules (no movement later or earlier than they allow), special cases, and
+brute force on feasibility."""
 import itertools
 import os
 import random
@@ -7,6 +9,7 @@ import random
 import pytest
 
 from oracle import scheduler as sch
+import schedule_properties as props
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -21,6 +24,10 @@ def parse_layers(text):
 
 def tokens(S):
     return " ".join(f"m{t.target}@{t.trigger_id}" if t.operation == sch.MOVE_TO_GPU else f"c{t.target}" for t in S)
+
+
+def as_tuples(S):
+    return [(props.MOVE if t.operation == sch.MOVE_TO_GPU else props.COMPUTE, t.target, t.trigger_id) for t in S]
 
 
 def own_layer_traces(model):
@@ -113,7 +120,8 @@ def test_schedules_replay_within_memory_and_fail_exactly_when_nothing_fits(reuse
             n_oom += 1
             continue
         assert feasible(model, traces, gpu_memory, page_size)
-        replay(S, model, traces, gpu_memory, page_size)
+        peak = replay(S, model, traces, gpu_memory, page_size)
+        assert props.check(as_tuples(S), [(l.page_list, l.size) for l in model], traces, gpu_memory, page_size) == peak
         n_ok += 1
     assert n_ok > 100 and n_oom > 100
 
@@ -154,3 +162,39 @@ def test_planted_mistakes_are_caught():
     swapped = [good[0], good[1], good[3], good[2]] + good[4:]      # a move ahead of the compute that frees its memory
     with pytest.raises(AssertionError):
         replay(swapped, model, traces, 2, 1)
+
+
+def test_a_valid_schedule_that_is_not_the_greedy_one_is_caught():
+    """The placement check must notice a movement that sits later or earlier than the two rules
+    allow although the schedule stays within memory, and a wrong trigger id."""
+    layers = [([0, 1], 0), ([2, 3], 0), ([4], 0)]
+    model = [sch.Layer(pl, sz) for pl, sz in layers]
+    traces = own_layer_traces(model)
+    good = as_tuples(sch.schedule(model, traces, 4, 1))
+    assert " ".join(f"m{t}@{g}" if o == props.MOVE else f"c{t}" for o, t, g in good) == \
+        "m0@0 m1@0 m2@0 m3@0 c0 m4@0 c1 c2"
+    props.check(good, layers, traces, 4, 1)
+    def variant(text):
+        out = []
+        for tok in text.split():
+            if tok[0] == "m":
+                page, trig = tok[1:].split("@")
+                out.append((props.MOVE, int(page), int(trig)))
+            else:
+                out.append((props.COMPUTE, int(tok[1:]), int(tok[1:])))
+        return out
+    for wrong in ("m0@0 m1@0 m2@0 c0 m3@0 m4@0 c1 c2",       # page 3 fits before layer 0 and is held back
+                  "m0@0 m1@0 m2@0 m3@0 c0 c1 m4@1 c2",       # page 4 held back past a point with two pages free
+                  "m0@0 m1@0 m2@0 m3@0 c0 m4@1 c1 c2",       # right place, trigger of the wrong rule
+                  "m0@0 m1@0 m3@0 m2@0 c0 m4@0 c1 c2"):      # out of page order
+        props.check_valid(variant(wrong), layers, traces, 4, 1)          # all of them stay within memory
+        with pytest.raises(AssertionError):
+            props.check_greedy(variant(wrong), layers, traces, 4, 1)
+    # the refill rule's margin: with exactly one page free nothing is planned again (page 3 waits
+    # for its own layer); planning it right after layer 0 is valid, but not the algorithm's plan
+    layers = [([0, 1], 0), ([2, 3], 0)]
+    traces = {0: 0, 1: 0, 2: 1, 3: 1}
+    props.check(variant("m0@0 m1@0 c0 m2@0 m3@1 c1"), layers, traces, 2, 1)
+    props.check_valid(variant("m0@0 m1@0 c0 m2@0 m3@0 c1"), layers, traces, 2, 1)
+    with pytest.raises(AssertionError):
+        props.check_greedy(variant("m0@0 m1@0 c0 m2@0 m3@0 c1"), layers, traces, 2, 1)
