@@ -84,50 +84,111 @@ __global__ __launch_bounds__(kThreads) void apm_seg_copy_kernel(const SegDesc* d
 constexpr int kDuplexItem = 4096;  // bytes per class, direction and wavefront iteration
 constexpr int kDuplexU = kDuplexItem / (64 * 16);
 
-// Bytes of item `item` of a batch that lie inside its page's used extent (<= 0: none).  With a
-// page table, a page is a whole number of items (items_per_page), so an item lies in one page.
-__device__ __forceinline__ int duplex_limit(const DuplexCopy& a, unsigned item, unsigned batch_items,
-                                            int64_t batch_bytes, int64_t first_page) {
-    if (item >= batch_items) return 0;
-    if (!a.used) {
-        const int64_t left = batch_bytes - (int64_t)item * kDuplexItem;
-        return left < kDuplexItem ? (int)left : kDuplexItem;
-    }
-    const unsigned page = item / a.items_per_page;
-    const int64_t in_page = (int64_t)(item - page * a.items_per_page) * kDuplexItem;
-    const int64_t used_bytes = (((int64_t)a.used[first_page + page] + 7) & ~(int64_t)7) * 4;
-    const int64_t left = used_bytes - in_page;  // pages go up to 2^30 elements: 64-bit
-    return left < kDuplexItem ? (int)(left < 0 ? 0 : left) : kDuplexItem;
+// A wavefront's position in one direction's run of pages.  A wavefront visits the items congruent
+// to its number modulo the wavefront count, and of those only the ones that hold used bytes: items
+// beyond a page's used extent are not visited one by one, the cursor hops along its stride to the
+// next page.  Skipping them (instead of spending an iteration on an item that is empty in one
+// direction) keeps the two directions of an exchange in step when their nearly empty pages sit at
+// different positions -- a fifth of the items of a 32-page exchange on a GPT-shaped layout.
+// With a page table a page is a whole number of items (items_per_page), so an item lies in one
+// page; without one the run is treated as a single page.
+struct DuplexCursor {
+    unsigned item;        // index in the run (>= n_items: nothing left)
+    unsigned page;        // page of the run the item lies in
+    unsigned in_page;     // index of the item within that page
+    unsigned page_items;  // items of that page that hold used bytes
+    int tail;             // bytes of the last of them
+    int limit;            // bytes of the current item to move (0: nothing left)
+};
+
+struct DuplexRun {
+    const int32_t* used;  // page table entry of the run's first page, or nullptr
+    unsigned n_items, items_per_page, stride;
+    int64_t bytes;
+};
+
+__device__ __forceinline__ void duplex_page(const DuplexRun& r, DuplexCursor& c) {
+    // The page table does not change while the kernel runs; read through the constant address
+    // space it is a scalar load that only its own use waits for (as a plain global load it is a
+    // vector load followed by a wait for every outstanding memory operation).
+    typedef const int32_t __attribute__((address_space(4))) * ConstTable;
+    const int64_t used_bytes = (((int64_t)((ConstTable)r.used)[c.page] + 7) & ~(int64_t)7) * 4;  // up to 2^32
+    c.page_items = (unsigned)((used_bytes + kDuplexItem - 1) / kDuplexItem);
+    c.tail = (int)(used_bytes - (int64_t)(c.page_items ? c.page_items - 1 : 0) * kDuplexItem);
 }
 
+// Settles the cursor on the first item at or after its position, on its stride, that holds used
+// bytes.  Every turn of the loop either returns or moves on to a later page of the run.
+__device__ __forceinline__ void duplex_settle(const DuplexRun& r, DuplexCursor& c) {
+#pragma unroll 1
+    for (;;) {
+        if (c.item >= r.n_items) {
+            c.limit = 0;
+            return;
+        }
+        if (c.in_page >= r.items_per_page) {  // crossed into the next page (item < n_items: it exists)
+            c.in_page -= r.items_per_page;
+            ++c.page;
+            duplex_page(r, c);
+            continue;
+        }
+        if (c.in_page < c.page_items) {
+            c.limit = c.in_page + 1 == c.page_items ? c.tail : kDuplexItem;
+            return;
+        }
+        const unsigned hops = (r.items_per_page - c.in_page + r.stride - 1) / r.stride;  // >= 1
+        c.item += hops * r.stride;
+        c.in_page += hops * r.stride;
+    }
+}
+
+__device__ __forceinline__ void duplex_start(const DuplexRun& r, DuplexCursor& c, unsigned worker) {
+    c.item = c.in_page = worker;
+    c.page = 0;
+    c.limit = 0;
+    if (r.used) {
+        c.page_items = 0;
+        c.tail = 0;
+        if (r.n_items > 0) duplex_page(r, c);
+    } else {
+        c.page_items = r.n_items;
+        c.tail = (int)(r.bytes - (int64_t)(r.n_items ? r.n_items - 1 : 0) * kDuplexItem);
+    }
+    duplex_settle(r, c);
+}
+
+typedef const u32x4 __attribute__((address_space(1))) * DuplexIn;
+typedef u32x4 __attribute__((address_space(1))) * DuplexOut;
+
+// One item of each direction: all loads, then all stores, in one basic block (FULL) so that the
+// stores wait for their own loads only, in issue order.
 template <bool FULL>
-__device__ __forceinline__ void duplex_item(const DuplexCopy& a, int64_t base, int lane_off, int lim_in, int lim_out) {
-    typedef const u32x4 __attribute__((address_space(1))) * In;
-    typedef u32x4 __attribute__((address_space(1))) * Out;
+__device__ __forceinline__ void duplex_item(const DuplexCopy& a, int64_t base_in, int64_t base_out, int lane_off,
+                                            int lim_in, int lim_out) {
     u32x4 vin[3][kDuplexU], vout[3][kDuplexU];
 #pragma unroll
     for (int k = 0; k < 3; ++k)
 #pragma unroll
         for (int u = 0; u < kDuplexU; ++u)
-            if (FULL || lane_off + u * 1024 < lim_in) vin[k][u] = __builtin_nontemporal_load((In)(a.in_src[k] + base + u * 1024));
+            if (FULL || lane_off + u * 1024 < lim_in) vin[k][u] = __builtin_nontemporal_load((DuplexIn)(a.in_src[k] + base_in + u * 1024));
     __builtin_amdgcn_sched_barrier(0);  // keep the order written here: host reads first
 #pragma unroll
     for (int k = 0; k < 3; ++k)
 #pragma unroll
         for (int u = 0; u < kDuplexU; ++u)
-            if (FULL || lane_off + u * 1024 < lim_out) vout[k][u] = __builtin_nontemporal_load((In)(a.out_src[k] + base + u * 1024));
+            if (FULL || lane_off + u * 1024 < lim_out) vout[k][u] = __builtin_nontemporal_load((DuplexIn)(a.out_src[k] + base_out + u * 1024));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k = 0; k < 3; ++k)
 #pragma unroll
         for (int u = 0; u < kDuplexU; ++u)
-            if (FULL || lane_off + u * 1024 < lim_out) __builtin_nontemporal_store(vout[k][u], (Out)(a.out_dst[k] + base + u * 1024));
+            if (FULL || lane_off + u * 1024 < lim_out) __builtin_nontemporal_store(vout[k][u], (DuplexOut)(a.out_dst[k] + base_out + u * 1024));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k = 0; k < 3; ++k)
 #pragma unroll
         for (int u = 0; u < kDuplexU; ++u)
-            if (FULL || lane_off + u * 1024 < lim_in) __builtin_nontemporal_store(vin[k][u], (Out)(a.in_dst[k] + base + u * 1024));
+            if (FULL || lane_off + u * 1024 < lim_in) __builtin_nontemporal_store(vin[k][u], (DuplexOut)(a.in_dst[k] + base_in + u * 1024));
 }
 
 __global__ __launch_bounds__(1024) void apm_duplex_copy_kernel(DuplexCopy a, int n_workers) {
@@ -137,24 +198,33 @@ __global__ __launch_bounds__(1024) void apm_duplex_copy_kernel(DuplexCopy a, int
     if (worker >= n_workers) return;
     const unsigned in_items = (unsigned)((a.in_bytes + kDuplexItem - 1) / kDuplexItem);
     const unsigned out_items = (unsigned)((a.out_bytes + kDuplexItem - 1) / kDuplexItem);
-    const unsigned n_items = in_items > out_items ? in_items : out_items;
     const int lane_off = lane * 16;
-    // The used extents of the next item are looked up (two dependent scalar loads) while the
-    // current item's data is in flight, so the lookup never delays the issue of the data loads.
-    unsigned item = (unsigned)worker;
-    int lim_in = duplex_limit(a, item, in_items, a.in_bytes, a.in_first_page);
-    int lim_out = duplex_limit(a, item, out_items, a.out_bytes, a.out_first_page);
+    // Each direction has its own cursor over the items that hold used bytes; the next positions
+    // are worked out (scalar arithmetic, a scalar load per page) before the current item's data moves.
+    const unsigned ipp = a.used ? a.items_per_page : 0xffffffffu;
+    const DuplexRun rin{a.used ? a.used + a.in_first_page : nullptr, in_items, ipp, (unsigned)n_workers, a.in_bytes};
+    const DuplexRun rout{a.used ? a.used + a.out_first_page : nullptr, out_items, ipp, (unsigned)n_workers, a.out_bytes};
+    DuplexCursor in, out;
+    duplex_start(rin, in, (unsigned)worker);
+    duplex_start(rout, out, (unsigned)worker);
 #pragma unroll 1
-    while (item < n_items) {
-        const unsigned next = item + (unsigned)n_workers;
-        const int64_t base = (int64_t)item * kDuplexItem + lane_off;
-        const int cur_in = lim_in, cur_out = lim_out;
-        lim_in = duplex_limit(a, next, in_items, a.in_bytes, a.in_first_page);
-        lim_out = duplex_limit(a, next, out_items, a.out_bytes, a.out_first_page);
+    while (in.limit > 0 || out.limit > 0) {
         // byte counts and used extents are multiples of 16: a 16-byte vector is wholly in or out
-        if (cur_in >= kDuplexItem && cur_out >= kDuplexItem) duplex_item<true>(a, base, lane_off, cur_in, cur_out);
-        else if (cur_in > 0 || cur_out > 0) duplex_item<false>(a, base, lane_off, cur_in, cur_out);
-        item = next;
+        const int cur_in = in.limit, cur_out = out.limit;
+        const int64_t base_in = (int64_t)in.item * kDuplexItem + lane_off;
+        const int64_t base_out = (int64_t)out.item * kDuplexItem + lane_off;
+        if (cur_in > 0) {
+            in.item += (unsigned)n_workers;
+            in.in_page += (unsigned)n_workers;
+            duplex_settle(rin, in);
+        }
+        if (cur_out > 0) {
+            out.item += (unsigned)n_workers;
+            out.in_page += (unsigned)n_workers;
+            duplex_settle(rout, out);
+        }
+        if (cur_in >= kDuplexItem && cur_out >= kDuplexItem) duplex_item<true>(a, base_in, base_out, lane_off, cur_in, cur_out);
+        else duplex_item<false>(a, base_in, base_out, lane_off, cur_in, cur_out);
     }
 }
 
