@@ -397,6 +397,55 @@ def test_scheduled_step_equals_resident_bit_exact(budget_layers, mover):
     res.destroy()
 
 
+@pytest.mark.parametrize("E", [8, 520, 1024, 2048, 5120])
+@pytest.mark.parametrize("waves", [3, 200])
+def test_copy_kernel_movers_on_small_and_odd_page_sizes(E, waves):
+    # The copy kernel works on 4 KiB items: pages that are not a whole number of items (8 and 520
+    # elements: it then moves whole runs without the page table), pages of exactly one item, of
+    # two, and of five; fewer wavefronts than items per page and more wavefronts than items in a
+    # run; tensors that leave pages full, nearly empty (a tiny tensor alone) and ending mid-item.
+    # The ring and the schedule-driven step alternate on one host pool; both must match the
+    # resident update bit for bit, unused tails included.
+    numels = [3 * E + 8, 8, E, 2 * E - 8, 16, E // 2, 5 * E + 24, 8, 8, 4 * E, 24, max(8, E - 8)]
+    specs = [synth.TensorSpec(i, f"t{i}", n) for i, n in enumerate(numels)]
+    model = Model(specs, E, seed=9)
+    n_pages, n_t = model.plan.n_pages, len(specs)
+    hy = to_hyper(oracle.Hyper(max_grad_norm=1.0))
+    res = DevicePool(n_pages, E)
+    apm.apm_pack_tensors(res.pool, apm.APM_P32, model.tensors(model.p_flat), n_t)
+    dev = DevicePool(n_pages, E, states=(apm.APM_G16, apm.APM_P16))
+    host = apm.apm_pool_create(apm.APM_DEV_HOST, E, n_pages, state_mask=apm.FP32_STATES)
+    apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
+    apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
+    st = apm.apm_streamer_create(host, dev.pool, 5, 3)
+    set_mode(st, f"staged:{waves}")
+    per = 4
+    bounds = list(range(0, n_pages, per)) + [n_pages]
+    layers = [(range(a, b), 0) for a, b in zip(bounds, bounds[1:])]
+    tasks, _ = apm.apm_schedule_plan(layers, None, 12 * E, 11 * 12 * E)     # 11 of the 15 slots
+    norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    norm_s = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
+    for t in range(1, 5):
+        g = model.grad_flat(t)
+        apm.apm_pack_tensors(res.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_pack_tensors(dev.pool, apm.APM_G16, model.tensors(g), n_t)
+        apm.apm_page_adamw_step(res.pool, None, n_pages, t, hy, norm_r, None)
+        if t % 2:
+            apm.apm_streamer_step(st, t, hy, norm_s, None)
+        else:
+            apm.apm_streamer_step_scheduled(st, tasks, bounds, t, hy, norm_s, None)
+        torch.cuda.synchronize()
+        assert torch.equal(norm_r, norm_s), f"step {t}"
+        for s_ in (apm.APM_P32, apm.APM_M32, apm.APM_V32):
+            hv = host_view(host, s_, n_pages, E)
+            assert np.array_equal(hv.view(np.uint32), res.reg[s_].cpu().numpy().view(np.uint32)), f"step {t} state {s_}"
+    assert torch.equal(dev.reg[apm.APM_P16].view(torch.int16), res.reg[apm.APM_P16].view(torch.int16))
+    st.destroy()
+    host.destroy()
+    dev.destroy()
+    res.destroy()
+
+
 def test_scheduled_step_with_a_trace_that_keeps_pages_beyond_their_own_layer():
     # Alg. 1's input is the trace: the layer after which a page's GPU memory is free again.  Here
     # the first page of every layer but the last is accessed again by the layer two further on (and
