@@ -312,7 +312,10 @@ int apm_streamer_destroy(apm_streamer* s);
  *     updated in its slot, ONE copy kernel of the library (direct_wavefronts wavefronts, as above)
  *     brings batch b+1 from its host pages into the next slot and takes batch b-1 from the
  *     previous slot back to its host pages, both directions at once; with two slots the two
- *     directions are two kernels, one after the other.  One copy stream and one compute stream.
+ *     directions are two kernels, one after the other.  One copy stream and one compute stream;
+ *     streams that share a hardware queue would run the update behind each copy kernel, so the
+ *     copy stream is chosen, when the mode is first selected, by timing a pair of short kernels
+ *     on each of a few candidates (about a millisecond each; synchronises the device).
  *     The staging memory is allocated when a staged mode is first selected.
  *   APM_STREAM_STAGED_DMA: the same slot ring moved by the runtime's asynchronous copies:
  *     copy-in / update / copy-out on three streams.  Which stream pairs overlap a host-to-device
