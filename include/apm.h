@@ -312,7 +312,10 @@ int apm_streamer_destroy(apm_streamer* s);
  *     updated in its slot, ONE copy kernel of the library (direct_wavefronts wavefronts, as above)
  *     brings batch b+1 from its host pages into the next slot and takes batch b-1 from the
  *     previous slot back to its host pages, both directions at once; with two slots the two
- *     directions are two kernels, one after the other.  One copy stream and one compute stream;
+ *     directions are two kernels, one after the other.  A batch here is at most batch_pages
+ *     pages: the batches are cut so that each holds about as many used elements as the emptiest
+ *     run of batch_pages pages (an exchange lasts as long as its longer direction, and the kernel
+ *     moves used extents only).  One copy stream and one compute stream;
  *     streams that share a hardware queue would run the update behind each copy kernel, so the
  *     copy stream is chosen, when the mode is first selected, by timing a pair of short kernels
  *     on each of a few candidates (about a millisecond each; synchronises the device).

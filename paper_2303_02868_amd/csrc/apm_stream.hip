@@ -363,7 +363,37 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
         return APM_OK;
     }
-    const int64_t n_batches = (N - R + s->B - 1) / s->B;
+    // Batches: runs of at most B consecutive pages from page R on.  The runtime's copies move
+    // whole pages, so there every batch has B pages.  The copy kernel moves used extents, and an
+    // exchange takes as long as its longer direction, so there the batches are cut to hold about
+    // the same number of used elements each: as many as the emptiest window of B pages holds (a
+    // GPT layout has a nearly empty page in every seven or eight; with B pages per batch the two
+    // directions of an exchange differed by 7 % on average, and the step was that much longer).
+    std::vector<int64_t> batch_at;  // first page of batch b; one entry more than there are batches
+    batch_at.push_back(R);
+    if (kcopy && N - R > s->B) {
+        const auto used_of = [&](int64_t p) { return (int64_t)dev->plan.pages[(size_t)p].used; };
+        int64_t window = 0, emptiest = INT64_MAX;
+        for (int64_t p = R; p < N; ++p) {
+            window += used_of(p);
+            if (p - R >= s->B) window -= used_of(p - s->B);
+            if (p - R >= s->B - 1 && window < emptiest) emptiest = window;
+        }
+        int64_t in_batch = 0;
+        for (int64_t p = R; p < N; ++p) {
+            const int64_t u = used_of(p), n_here = p - batch_at.back();
+            if (n_here > 0 && (n_here == s->B || in_batch + u / 2 > emptiest)) {  // nearest to the target
+                batch_at.push_back(p);
+                in_batch = 0;
+            }
+            in_batch += u;
+        }
+        batch_at.push_back(N);
+    } else {
+        for (int64_t p = R + s->B; p < N; p += s->B) batch_at.push_back(p);
+        if (N > R) batch_at.push_back(N);
+    }
+    const int64_t n_batches = (int64_t)batch_at.size() - 1;
     // resident pages are updated in n_batches chunks (one chunk if nothing is streamed)
     const int64_t chunk = n_batches > 0 ? (R + n_batches - 1) / n_batches : R;
     int64_t r_done = 0;
@@ -393,8 +423,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     }
     auto update_batch = [&](int64_t b) -> int {
         const size_t slot = (size_t)(b % s->n_slots);
-        const int64_t first = R + b * s->B;
-        const int64_t nb = N - first < s->B ? N - first : s->B;
+        const int64_t first = batch_at[(size_t)b];
+        const int64_t nb = batch_at[(size_t)b + 1] - first;
         APM_HIP(hipStreamWaitEvent(s->s_cmp, s->ev_h2d[slot], 0));
         L.state_first = (int64_t)slot * s->B;
         L.grad_first = first;
@@ -418,8 +448,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
             DuplexCopy d{};
             auto fill = [&](int64_t b, bool in) {
                 const size_t slot = (size_t)(b % s->n_slots);
-                const int64_t first = R + b * s->B;
-                const int64_t nb = N - first < s->B ? N - first : s->B;
+                const int64_t first = batch_at[(size_t)b];
+                const int64_t nb = batch_at[(size_t)b + 1] - first;
                 const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
                 for (int k = 0; k < 3; ++k) {
                     char* h = reinterpret_cast<char*>(s->host_dev[k]) + (size_t)(first - H0) * pb;
@@ -473,8 +503,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     // after the other, 28 instead of 48 GB/s each way, so one it is.)
     auto copy_in = [&](int64_t b) -> int {
         const size_t slot = (size_t)(b % s->n_slots);
-        const int64_t first = R + b * s->B;
-        const int64_t nb = N - first < s->B ? N - first : s->B;
+        const int64_t first = batch_at[(size_t)b];
+        const int64_t nb = batch_at[(size_t)b + 1] - first;
         const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
         if (b >= s->n_slots) APM_HIP(hipStreamWaitEvent(s->s_in, s->ev_d2h[slot], 0));
         for (int k = 0; k < 3 && (what & kDoH2D); ++k) {
@@ -491,8 +521,8 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
     }
     for (int64_t b = 0; b < n_batches; ++b) {
         const size_t slot = (size_t)(b % s->n_slots);
-        const int64_t first = R + b * s->B;
-        const int64_t nb = N - first < s->B ? N - first : s->B;
+        const int64_t first = batch_at[(size_t)b];
+        const int64_t nb = batch_at[(size_t)b + 1] - first;
         const size_t slot_off = slot * (size_t)s->B * (size_t)E;  // floats
         if (b + ahead < n_batches) {  // its slot's previous copy-out is already enqueued
             rc = copy_in(b + ahead);
