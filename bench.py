@@ -482,34 +482,106 @@ def scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step):
             "pcie_GBps_each_way": each_way / med / 1e9, "bytes_credited_each_way": each_way}
 
 
+def one_way_traffic_beside_a_producer(streamer, iters):
+    """Why the overlap is incomplete: an elementwise producer (gelu over 2^28 bf16 values, many short
+    HBM-bound kernels) timed alone and beside the staged pipeline's page traffic in one direction
+    only, then both (the copy-only pipeline: no update kernels).  Pages arriving (PCIe reads) barely
+    disturb it; pages leaving (a kernel's writes to host memory) stretch it."""
+    import torch
+    import paper_2303_02868_amd as apm
+    side = _stream_beside_the_current_one()
+    x = torch.randn(1 << 28, device=DEV, dtype=torch.bfloat16)
+    one = lambda: torch.nn.functional.gelu(x)
+    apm.apm_streamer_set_mode(streamer, apm.APM_STREAM_STAGED, 0, 0)
+
+    def timed(fn):
+        ts = []
+        for _ in range(iters):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return statistics.median(ts)
+
+    for _ in range(10):
+        one()
+    per = timed(lambda: [one() for _ in range(50)]) / 50
+    reps = max(1, int(0.65 / per))           # about twice one pass of the pages: the traffic ends inside it
+
+    def prod():
+        for _ in range(reps):
+            one()
+
+    t_p = timed(prod)
+    out = {"producer": f"{reps} gelu calls over 2^28 bf16 values", "producer_alone_ms": t_p * 1e3}
+    for d, name, wt in ((1, "host_to_device_only", False), (2, "device_to_host_only", False), (3, "both_directions", False),
+                        (2, "device_to_host_only_written_through", True), (3, "both_directions_written_through", True)):
+        apm.apm_streamer_set_host_write_through(streamer, wt)
+        apm.apm_streamer_copy_only(streamer, d, side)
+        t_c = timed(lambda: apm.apm_streamer_copy_only(streamer, d, side))
+
+        def together():
+            apm.apm_streamer_copy_only(streamer, d, side)
+            prod()
+
+        t_b = timed(together)
+        out[name] = {"traffic_alone_ms": t_c * 1e3, "together_ms": t_b * 1e3,
+                     "producer_stretched_by_ms": (t_b - t_p) * 1e3}
+    apm.apm_streamer_set_host_write_through(streamer, False)
+    del x
+    return out
+
+
+def _stream_beside_the_current_one():
+    """A side stream whose work runs beside the current stream's.  Streams that the runtime maps
+    onto one hardware queue run their work in order -- an event wait on one holds up the kernels of
+    the other -- so candidates are tried with a pair of short sleeps until one overlaps."""
+    import torch
+    cycles = 2_000_000
+
+    def both(side):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(side):
+            torch.cuda._sleep(cycles)
+        torch.cuda._sleep(cycles)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    torch.cuda._sleep(cycles)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    torch.cuda._sleep(cycles)
+    torch.cuda.synchronize()
+    one = time.perf_counter() - t0
+    kept = []
+    for _ in range(6):
+        side = torch.cuda.Stream()
+        kept.append(side)               # rejected ones stay alive: a freed queue slot would be handed out again
+        both(side)
+        if min(both(side), both(side)) < 1.6 * one:
+            return side
+    return kept[-1]
+
+
 def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
     """Alg. 2's point on one GPU: the update of host-resident state runs beside the producer of the
     next gradient instead of after it.  The producer here is a stand-in for forward/backward (which
     this build does not have): dense bf16 matrix products through the BLAS library, sized to take
     about as long as one streamed update.  Synchronous: products, then apm_streamer_step.
     One-step-stale: apm_streamer_step_delayed (applies the previous gradient on the update stream),
-    then the products.  Measured for three ways of streaming."""
+    then the products.  Measured for four ways of streaming.  The library's large matrix products
+    are a hard neighbour: they run 1.65-1.85x slower beside ANY second kernel, even one idle
+    thread spinning on one CU (attention and elementwise kernels do not care), so the two
+    kernel-driven ways are measured beside an attention producer as well (causal scaled-dot-product
+    attention, 8 x 32 heads x 2048 x 128, through the framework's fused kernel)."""
     import torch
     import paper_2303_02868_amd as apm
     stream = torch.cuda.current_stream()
-    n = 8192
-    a = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
-    b = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
-    c = torch.empty(n, n, device=DEV, dtype=torch.bfloat16)
-
-    def products(reps):
-        for _ in range(reps):
-            torch.matmul(a, b, out=c)
-
-    products(10)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    products(50)
-    torch.cuda.synchronize()
-    per = (time.perf_counter() - t0) / 50
-    reps = max(1, int(round(update_ms * 1e-3 / per)))
     g16 = apm.apm_pool_state_ptr(dev_pool, apm.APM_G16)
     iters = max(3, args.stream_steps)
+    step = [1000]
 
     def timed(fn):
         torch.cuda.synchronize()
@@ -519,49 +591,81 @@ def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / iters
 
-    t_compute = timed(lambda: products(reps))
-    step = [1000]
-
     def update_only():
         apm.apm_streamer_step(streamer, step[0], hyper, None, None, stream)
         step[0] += 1
 
-    def sync_iter():
-        products(reps)
-        update_only()
+    def measure(kind, ways):
+        if kind == "attention":
+            q = torch.randn(8, 32, 2048, 128, device=DEV, dtype=torch.bfloat16)
+            one = lambda: torch.nn.functional.scaled_dot_product_attention(q, q, q, is_causal=True)
+            what, flops = "causal attention calls (8 x 32 heads x 2048 x 128)", 2.0 * 8 * 32 * 2048 * 2048 * 128
+        else:
+            n = 8192
+            a = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
+            b = torch.randn(n, n, device=DEV, dtype=torch.bfloat16)
+            c = torch.empty(n, n, device=DEV, dtype=torch.bfloat16)
+            one = lambda: torch.matmul(a, b, out=c)
+            what, flops = f"bf16 {n}^3 matrix products", 2.0 * n ** 3
 
-    def delayed_iter():
-        apm.apm_streamer_step_delayed(streamer, g16, hyper, stream)
-        products(reps)
+        def products(reps):
+            for _ in range(reps):
+                one()
 
-    out = {"producer": f"{reps} bf16 {n}^3 matrix products per iteration (stand-in for forward/backward)",
-           "producer_TFLOPs_alone": 2.0 * n ** 3 * reps / t_compute / 1e12, "producer_ms": t_compute * 1e3}
-    ways = [("direct_64_wavefronts_on_64_CUs", apm.APM_STREAM_DIRECT, 64, 1),
-            ("direct_128_wavefronts_on_8_CUs", apm.APM_STREAM_DIRECT, 128, 16),
-            ("staged_128_wavefronts_on_8_CUs", apm.APM_STREAM_STAGED, 128, 16),
-            ("staged_dma", apm.APM_STREAM_STAGED_DMA, 0, 0)]
+        products(10)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        products(50)
+        torch.cuda.synchronize()
+        per = (time.perf_counter() - t0) / 50
+        reps = max(1, int(round(update_ms * 1e-3 / per)))
+        t_compute = timed(lambda: products(reps))
+
+        def sync_iter():
+            products(reps)
+            update_only()
+
+        def delayed_iter():
+            apm.apm_streamer_step_delayed(streamer, g16, hyper, stream)
+            products(reps)
+
+        out = {"producer": f"{reps} {what} per iteration (stand-in for forward/backward)",
+               "producer_TFLOPs_alone": flops * reps / t_compute / 1e12, "producer_ms": t_compute * 1e3}
+        for name, mode, waves, per_wg in ways:
+            apm.apm_streamer_set_mode(streamer, mode, waves, per_wg)
+            apm.apm_streamer_set_host_write_through(streamer, name.endswith("written_through"))
+            update_only()
+            t_update = timed(update_only)
+            t_sync = timed(sync_iter)
+            apm.apm_streamer_step_delayed(streamer, g16, hyper, stream)      # fill the pipeline
+            t_delayed = timed(delayed_iter)
+            apm.apm_streamer_step_delayed(streamer, None, hyper, stream)     # flush
+            torch.cuda.synchronize()
+            out[name] = {"update_ms": t_update * 1e3, "synchronous_ms_per_iter": t_sync * 1e3,
+                         "one_step_stale_ms_per_iter": t_delayed * 1e3, "speedup": t_sync / t_delayed,
+                         "hidden_fraction_of_the_shorter": (t_sync - t_delayed) / min(t_compute, t_update),
+                         "over_ideal_max_of_the_two": t_delayed / max(t_compute, t_update),
+                         "streams_run_beside_the_producer": dict(zip(("update_stream", "pipeline_streams"),
+                                                                     apm.apm_streamer_overlap_report(streamer)))}
+        apm.apm_streamer_set_host_write_through(streamer, False)
+        best = min((k for k in out if isinstance(out[k], dict)), key=lambda k: out[k]["one_step_stale_ms_per_iter"])
+        out["best"] = {"way": best, **out[best]}
+        return out
+
+    kernel_ways = [("direct_128_wavefronts_on_8_CUs", apm.APM_STREAM_DIRECT, 128, 16),
+                   ("staged_128_wavefronts_on_8_CUs", apm.APM_STREAM_STAGED, 128, 16)]
+    ways = [("direct_64_wavefronts_on_64_CUs", apm.APM_STREAM_DIRECT, 64, 1)] + kernel_ways + \
+           [("staged_dma", apm.APM_STREAM_STAGED_DMA, 0, 0)]
     if args.lockfree_sweep:     # wavefronts x workgroup packing of the kernel that crosses PCIe
         ways = [(f"{m}_{w}_wavefronts_{p}_per_workgroup", c, w, p)
                 for m, c in (("direct", apm.APM_STREAM_DIRECT), ("staged", apm.APM_STREAM_STAGED))
                 for w, p in ((48, 1), (64, 8), (80, 16), (96, 16), (128, 16), (160, 16), (256, 16))]
         ways.append(("staged_dma", apm.APM_STREAM_STAGED_DMA, 0, 0))
-    for name, mode, waves, per_wg in ways:
-        apm.apm_streamer_set_mode(streamer, mode, waves, per_wg)
-        update_only()
-        t_update = timed(update_only)
-        t_sync = timed(sync_iter)
-        apm.apm_streamer_step_delayed(streamer, g16, hyper, stream)      # fill the pipeline
-        t_delayed = timed(delayed_iter)
-        apm.apm_streamer_step_delayed(streamer, None, hyper, stream)     # flush
-        torch.cuda.synchronize()
-        out[name] = {"update_ms": t_update * 1e3, "synchronous_ms_per_iter": t_sync * 1e3,
-                     "one_step_stale_ms_per_iter": t_delayed * 1e3, "speedup": t_sync / t_delayed,
-                     "hidden_fraction_of_the_shorter": (t_sync - t_delayed) / min(t_compute, t_update),
-                     "over_ideal_max_of_the_two": t_delayed / max(t_compute, t_update),
-                     "streams_run_beside_the_producer": dict(zip(("update_stream", "pipeline_streams"),
-                                                                 apm.apm_streamer_overlap_report(streamer)))}
-    best = min((k for k in out if isinstance(out[k], dict)), key=lambda k: out[k]["one_step_stale_ms_per_iter"])
-    out["best"] = {"way": best, **out[best]}
+    wt_way = [("direct_128_wavefronts_on_8_CUs_host_stores_written_through", apm.APM_STREAM_DIRECT, 128, 16),
+              ("staged_128_wavefronts_on_8_CUs_host_stores_written_through", apm.APM_STREAM_STAGED, 128, 16)]
+    out = measure("matmul", ways + wt_way)
+    out["beside_attention"] = measure("attention", kernel_ways + wt_way)
+    out["elementwise_producer_beside_page_traffic_one_way"] = one_way_traffic_beside_a_producer(streamer, iters)
     return out
 
 

@@ -345,6 +345,20 @@ int apm_streamer_get_mode(const apm_streamer* s);
 int apm_streamer_step(apm_streamer* s, int64_t step, const apm_hyper* hyper, float* grad_norm,
                       uint8_t* skip_mask, void* stream);
 
+/*
+ * How the kernels that write the host pool (the direct mode's update kernel, the staged mode's and
+ * the scheduled step's copy kernel) store: non-temporal (on = 0, the default: fastest when nothing
+ * else runs on the GPU) or written through at system scope (on != 0).  A non-temporal store to host
+ * memory may rest in the GPU's L2 as a dirty line; the write-back at the end of every kernel of any
+ * other stream then has to push such lines across PCIe, so kernels that run beside the update are
+ * stretched by its writes (measured: elementwise kernels beside the outbound half of the staged
+ * pipeline ran 150 ms longer per 290 ms of traffic, beside written-through stores 10 ms).  Written
+ * through, the step alone is about a tenth slower.  Meant for the one-step-stale forms, whose
+ * update runs beside the caller's kernels.  Results are bit-identical.  Takes effect from the next
+ * step.
+ */
+int apm_streamer_set_host_write_through(apm_streamer* s, int on);
+
 /* GB/s the staged-DMA mode's stream calibration measured on 32 MiB copies (zeros before it ran):
  * copy-in alone, copy-out alone, and each way with both running on the chosen pair (host
  * pointers, nullable). */

@@ -35,6 +35,7 @@ EXPORTS = [
     "apm_delayed_applied", "apm_delayed_set_outputs", "apm_delayed_grad_buffer", "apm_delayed_accumulate", "apm_pool_set_timing", "apm_pool_read_timing",
     "apm_page_adamw_step_noalloc", "apm_noalloc_scratch_bytes", "apm_noalloc_max_pages",
     "apm_streamer_overlap_report",
+    "apm_streamer_set_host_write_through",
 ]
 
 
@@ -141,6 +142,7 @@ def lib() -> C.CDLL:
     L.apm_streamer_get_mode.argtypes = [vp]
     L.apm_streamer_probe_rates.argtypes = [vp, P(C.c_double), P(C.c_double), P(C.c_double)]
     L.apm_streamer_overlap_report.argtypes = [vp, P(C.c_int), P(C.c_int)]
+    L.apm_streamer_set_host_write_through.argtypes = [vp, C.c_int]
     L.apm_step_delayed.argtypes = [vp, P(i64), i64, vp, P(apm_hyper), vp]
     L.apm_delayed_accumulate.argtypes = [vp, P(i64), i64, vp, vp]
     L.apm_delayed_grad_buffer.argtypes = [vp, vp]
@@ -462,6 +464,10 @@ def apm_streamer_step_scheduled(s: Streamer, tasks: Sequence, layer_first_page: 
     la = _i64_array(last_access)[0] if last_access is not None else None
     _check(lib().apm_streamer_step_scheduled(s.handle, arr, len(tasks), lf, n1 - 1, la, step, C.byref(hyper),
                                              _ptr(grad_norm), _ptr(skip_mask), _stream(stream)))
+
+
+def apm_streamer_set_host_write_through(s: Streamer, on: bool) -> None:
+    _check(lib().apm_streamer_set_host_write_through(s.handle, int(bool(on))))
 
 
 def apm_streamer_overlap_report(s: Streamer):

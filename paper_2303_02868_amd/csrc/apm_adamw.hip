@@ -375,7 +375,20 @@ constexpr int kUpdTile = kUpdThreads * 4 * kUpdU;  // elements per workgroup
 // block the compiler must assume the worst about what is outstanding -- with a predicate per
 // vector, each vector's arithmetic began with a wait for every earlier memory operation, the
 // previous vector's stores included, i.e. three extra store round trips per wavefront.
-template <bool EDGE_G, bool EDGE_Q, bool FULL>
+// Stores of the fp32 state: non-temporal, or -- WT, for state in host memory while other kernels
+// run on the GPU -- written through at system scope.  A non-temporal store to host memory may rest
+// in the L2 as a dirty line; the write-back that ends every kernel of any other stream then has
+// to push it across PCIe, so those kernels pay for this kernel's writes.
+template <bool WT>
+__device__ __forceinline__ void store_state(f32x4 x, f32x4* q) {
+    // Hand-written because no builtin takes a cache policy for a 128-bit global store; the wait
+    // states keep the next instruction off the data registers, which a store of more than 64 bits
+    // still reads right after issue (the compiler does that for its own stores, not for this one).
+    if (WT) asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(q), "v"(x) : "memory");
+    else __builtin_nontemporal_store(x, q);
+}
+
+template <bool EDGE_G, bool EDGE_Q, bool FULL, bool WT = false>
 __device__ __forceinline__ void slice_body(const UpdateArgs& a, const PageSegs& segs, float scale, int nvec, int v0,
                                            f32x4* __restrict__ P, f32x4* __restrict__ M, f32x4* __restrict__ V,
                                            const u32x2* __restrict__ G_, u32x2* __restrict__ P16_) {
@@ -418,9 +431,9 @@ __device__ __forceinline__ void slice_body(const UpdateArgs& a, const PageSegs& 
             u32x2 o;
             o[0] = f32_to_bf16_rne(p[u][0]) | (f32_to_bf16_rne(p[u][1]) << 16);
             o[1] = f32_to_bf16_rne(p[u][2]) | (f32_to_bf16_rne(p[u][3]) << 16);
-            __builtin_nontemporal_store(p[u], P + vi);
-            __builtin_nontemporal_store(m[u], M + vi);
-            __builtin_nontemporal_store(v[u], V + vi);
+            store_state<WT>(p[u], P + vi);
+            store_state<WT>(m[u], M + vi);
+            store_state<WT>(v[u], V + vi);
             if (EDGE_Q) scatter_q4(segs, vi << 2, o);
             else __builtin_nontemporal_store(o, P16 + vi);
         }
@@ -432,7 +445,7 @@ __device__ __forceinline__ void slice_body(const UpdateArgs& a, const PageSegs& 
 // fp32 class in flight; every wavefront-wide access is one contiguous 1 KiB (fp32) or 512 B (bf16)
 // span.  GATHER / SCATTER: read g from / write p16 to the tenant tensors instead of the page
 // classes.
-template <bool GATHER, bool SCATTER>
+template <bool GATHER, bool SCATTER, bool WT = false>
 __device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs& segs, float scale,
                                              int used8, int64_t gpage, int64_t spage, int start, int lane) {
     f32x4* __restrict__ P = reinterpret_cast<f32x4*>(a.p32 + spage * a.E);
@@ -452,12 +465,12 @@ __device__ __forceinline__ void update_slice(const UpdateArgs& a, const PageSegs
             if (GATHER) G = reinterpret_cast<const u32x2*>(segs.g[k] - segs.off[k]);
             if (SCATTER) P16 = reinterpret_cast<u32x2*>(segs.q[k] - segs.off[k]);
         } else {
-            slice_body<GATHER, SCATTER, false>(a, segs, scale, nvec, v0, P, M, V, G, P16);
+            slice_body<GATHER, SCATTER, false, WT>(a, segs, scale, nvec, v0, P, M, V, G, P16);
             return;
         }
     }
-    if (start + kUpdTile <= used8) slice_body<false, false, true>(a, segs, scale, nvec, v0, P, M, V, G, P16);
-    else slice_body<false, false, false>(a, segs, scale, nvec, v0, P, M, V, G, P16);
+    if (start + kUpdTile <= used8) slice_body<false, false, true, WT>(a, segs, scale, nvec, v0, P, M, V, G, P16);
+    else slice_body<false, false, false, WT>(a, segs, scale, nvec, v0, P, M, V, G, P16);
 }
 
 typedef long long i64x4 __attribute__((ext_vector_type(4)));
@@ -509,7 +522,7 @@ __global__ __launch_bounds__(kUpdThreads) void apm_adamw_kernel(UpdateArgs a) {
 // products), because a wavefront that lives as long as the whole transfer keeps those off its CU.
 constexpr int kStrideMaxThreads = 1024;
 
-template <bool GATHER, bool SCATTER>
+template <bool GATHER, bool SCATTER, bool WT>
 __global__ __launch_bounds__(kStrideMaxThreads) void apm_adamw_stride_kernel(UpdateArgs a, int64_t count, int nx,
                                                                              int n_workers) {
     const int lane = (int)threadIdx.x & (kWave - 1);
@@ -527,7 +540,7 @@ __global__ __launch_bounds__(kStrideMaxThreads) void apm_adamw_stride_kernel(Upd
         if (scale < 0.0f || start >= used8) continue;
         PageSegs segs{};
         if (GATHER || SCATTER) segs = a.segs[i];
-        update_slice<GATHER, SCATTER>(a, segs, scale, used8, raw[1], raw[2], start, lane);
+        update_slice<GATHER, SCATTER, WT>(a, segs, scale, used8, raw[1], raw[2], start, lane);
     }
 }
 
@@ -662,10 +675,16 @@ hipError_t launch_adamw(const AdamwLaunch& L, hipStream_t s) {
             const int workers = (int)(items < L.stride_wavefronts ? items : L.stride_wavefronts);
             const int per_wg = L.stride_waves_per_wg >= 1 && L.stride_waves_per_wg <= kStrideMaxThreads / kWave ? L.stride_waves_per_wg : 1;
             const dim3 grid((unsigned)((workers + per_wg - 1) / per_wg)), block((unsigned)(per_wg * kWave));
-            if (L.gather && L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, true>), grid, block, 0, s, a, ny, nx, workers);
-            else if (L.gather) hipLaunchKernelGGL((apm_adamw_stride_kernel<true, false>), grid, block, 0, s, a, ny, nx, workers);
-            else if (L.scatter) hipLaunchKernelGGL((apm_adamw_stride_kernel<false, true>), grid, block, 0, s, a, ny, nx, workers);
-            else hipLaunchKernelGGL((apm_adamw_stride_kernel<false, false>), grid, block, 0, s, a, ny, nx, workers);
+#define APM_LAUNCH_STRIDE(G, Q)                                                                                       \
+    do {                                                                                                             \
+        if (L.host_write_through) hipLaunchKernelGGL((apm_adamw_stride_kernel<G, Q, true>), grid, block, 0, s, a, ny, nx, workers); \
+        else hipLaunchKernelGGL((apm_adamw_stride_kernel<G, Q, false>), grid, block, 0, s, a, ny, nx, workers);       \
+    } while (0)
+            if (L.gather && L.scatter) APM_LAUNCH_STRIDE(true, true);
+            else if (L.gather) APM_LAUNCH_STRIDE(true, false);
+            else if (L.scatter) APM_LAUNCH_STRIDE(false, true);
+            else APM_LAUNCH_STRIDE(false, false);
+#undef APM_LAUNCH_STRIDE
         });
     }
     const bool may_skip = L.partials && L.skip_mode == APM_SKIP_UNTOUCHED;

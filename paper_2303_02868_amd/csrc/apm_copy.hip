@@ -5,6 +5,7 @@
 // exit at once.  Segments whose source and destination are both 16-byte aligned move 128 bits per
 // lane with contiguous wavefront accesses; any other alignment falls back to the widest unit that
 // divides both addresses and the length.
+#include <cstdlib>
 #include "apm_internal.h"
 
 namespace apm {
@@ -162,7 +163,7 @@ typedef u32x4 __attribute__((address_space(1))) * DuplexOut;
 
 // One item of each direction: all loads, then all stores, in one basic block (FULL) so that the
 // stores wait for their own loads only, in issue order.
-template <bool FULL>
+template <bool FULL, bool WT>
 __device__ __forceinline__ void duplex_item(const DuplexCopy& a, int64_t base_in, int64_t base_out, int lane_off,
                                             int lim_in, int lim_out) {
     u32x4 vin[3][kDuplexU], vout[3][kDuplexU];
@@ -182,7 +183,18 @@ __device__ __forceinline__ void duplex_item(const DuplexCopy& a, int64_t base_in
     for (int k = 0; k < 3; ++k)
 #pragma unroll
         for (int u = 0; u < kDuplexU; ++u)
-            if (FULL || lane_off + u * 1024 < lim_out) __builtin_nontemporal_store(vout[k][u], (DuplexOut)(a.out_dst[k] + base_out + u * 1024));
+            if (FULL || lane_off + u * 1024 < lim_out) {
+                // WT: written through at system scope.  A non-temporal store to host memory may rest
+                // in the L2 as a dirty line, and the write-back that ends every kernel of any other
+                // stream then pushes it across PCIe: those kernels pay for this kernel's writes.
+                DuplexOut q = (DuplexOut)(a.out_dst[k] + base_out + u * 1024);
+                // (hand-written because no builtin takes a cache policy for a 128-bit global store.
+                // The compiler does not know that this is a store whose data registers are read a
+                // little after issue -- for its own stores of more than 64 bits it keeps the next
+                // instruction from overwriting them -- so the wait states go in by hand.)
+                if (WT) asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(q), "v"(vout[k][u]) : "memory");
+                else __builtin_nontemporal_store(vout[k][u], q);
+            }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k = 0; k < 3; ++k)
@@ -191,6 +203,7 @@ __device__ __forceinline__ void duplex_item(const DuplexCopy& a, int64_t base_in
             if (FULL || lane_off + u * 1024 < lim_in) __builtin_nontemporal_store(vin[k][u], (DuplexOut)(a.in_dst[k] + base_in + u * 1024));
 }
 
+template <bool WT>
 __global__ __launch_bounds__(1024) void apm_duplex_copy_kernel(DuplexCopy a, int n_workers) {
     const int lane = (int)threadIdx.x & 63;
     const int waves_per_wg = (int)blockDim.x / 64;
@@ -223,8 +236,8 @@ __global__ __launch_bounds__(1024) void apm_duplex_copy_kernel(DuplexCopy a, int
             out.in_page += (unsigned)n_workers;
             duplex_settle(rout, out);
         }
-        if (cur_in >= kDuplexItem && cur_out >= kDuplexItem) duplex_item<true>(a, base_in, base_out, lane_off, cur_in, cur_out);
-        else duplex_item<false>(a, base_in, base_out, lane_off, cur_in, cur_out);
+        if (cur_in >= kDuplexItem && cur_out >= kDuplexItem) duplex_item<true, WT>(a, base_in, base_out, lane_off, cur_in, cur_out);
+        else duplex_item<false, WT>(a, base_in, base_out, lane_off, cur_in, cur_out);
     }
 }
 
@@ -240,8 +253,9 @@ hipError_t launch_duplex_copy(const DuplexCopy& d, int wavefronts, int per_wg, h
     if (a.page_bytes <= 0 || a.page_bytes % kDuplexItem != 0) a.used = nullptr;
     a.items_per_page = a.used ? (uint32_t)(a.page_bytes / kDuplexItem) : 0u;
     if (n_items >= ((int64_t)1 << 31)) return hipErrorInvalidValue;  // 8 TiB per class and kernel
-    hipLaunchKernelGGL(apm_duplex_copy_kernel, dim3((unsigned)((workers + per_wg - 1) / per_wg)),
-                       dim3((unsigned)(per_wg * 64)), 0, s, a, workers);
+    const dim3 grid((unsigned)((workers + per_wg - 1) / per_wg)), block((unsigned)(per_wg * 64));
+    if (a.host_store_policy != 0) hipLaunchKernelGGL(apm_duplex_copy_kernel<true>, grid, block, 0, s, a, workers);
+    else hipLaunchKernelGGL(apm_duplex_copy_kernel<false>, grid, block, 0, s, a, workers);
     return hipGetLastError();
 }
 

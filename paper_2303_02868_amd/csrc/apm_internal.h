@@ -151,6 +151,7 @@ struct AdamwLaunch {
     int32_t stride_wavefronts;    // > 0: the update runs as that many wavefronts striding over all
                                   // page slices (fp32 classes in host memory); 0: one per slice
     int32_t stride_waves_per_wg;  // how many of them share a workgroup, 1..16
+    bool host_write_through;      // stride form: fp32 state stores written through at system scope
 };
 
 // Reduce pass (fills meta with clip scale / skip); or, when no reduce pass is needed, the prepare
@@ -183,6 +184,7 @@ struct DuplexCopy {
     const int32_t* used;
     int64_t in_first_page, out_first_page, page_bytes;
     uint32_t items_per_page;  // filled in by launch_duplex_copy
+    int host_store_policy;    // stores to the host pages: 0 non-temporal, 3 written through at system scope
 };
 hipError_t launch_duplex_copy(const DuplexCopy& d, int wavefronts, int per_wg, hipStream_t s);
 

@@ -24,6 +24,7 @@
 // enqueues copy-in one batch ahead of the matching update and copy-out.
 #include <algorithm>
 #include <chrono>
+#include <cstdlib>
 #include <deque>
 
 #include "apm_internal.h"
@@ -39,6 +40,7 @@ struct apm_streamer {
     int n_slots = 0;
     float* stage[3] = {nullptr, nullptr, nullptr};  // each n_slots * B * E floats
     hipStream_t s_in = nullptr, s_cmp = nullptr, s_out = nullptr;
+    bool host_wt = false;  // stores to the host pool written through at system scope (see apm.h)
     hipStream_t s_copy = nullptr;  // staged mode: the stream of the duplex copy kernels
     hipStream_t s_res = nullptr;  // direct mode: the resident pages' update, beside the host pages'
     hipEvent_t ev_res = nullptr;
@@ -340,6 +342,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
                 C.v32 = s->host_dev[2];
                 C.stride_wavefronts = s->direct_waves;
                 C.stride_waves_per_wg = s->direct_per_wg;
+                C.host_write_through = s->host_wt;
             }
             C.meta = L.meta + first;
             if (need_reduce) {
@@ -462,6 +465,7 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
             };
             d.used = dev->d_used;  // only the used extents cross the link
             d.page_bytes = (int64_t)pb;
+            d.host_store_policy = s->host_wt ? 3 : 0;
             if (b_in >= 0 && (what & kDoH2D)) fill(b_in, true);
             if (b_out >= 0 && (what & kDoD2H)) fill(b_out, false);
             APM_HIP(launch_duplex_copy(d, s->direct_waves, s->direct_per_wg, s->s_copy));
@@ -697,6 +701,14 @@ extern "C" int apm_streamer_set_page_count(apm_streamer* s, int64_t n_pages) {
     return apm::guarded([&]() -> int {
         if (!s) return fail(APM_EINVAL, "NULL streamer");
         s->page_limit = n_pages < 0 ? -1 : n_pages;
+        return APM_OK;
+    });
+}
+
+extern "C" int apm_streamer_set_host_write_through(apm_streamer* s, int on) {
+    return apm::guarded([&]() -> int {
+        if (!s) return fail(APM_EINVAL, "NULL streamer");
+        s->host_wt = on != 0;
         return APM_OK;
     });
 }
@@ -943,6 +955,7 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                     DuplexCopy d{};
                     d.used = dev->d_used;
                     d.page_bytes = (int64_t)pb;
+                    d.host_store_policy = s->host_wt ? 3 : 0;
                     if (left_i > 0) {
                         const int64_t p0 = in[xi].p0 + used_i, s0 = in[xi].s0 + used_i;
                         for (int c = 0; c < 3; ++c) {

@@ -27,6 +27,9 @@ def host_view(pool, state, n_pages, E):
 def set_mode(streamer, mode):
     """"staged" | "direct" | "direct:<wavefronts>[:<per workgroup>]" (a small odd count makes every
     wavefront stride over many pages and slices)."""
+    if mode.endswith("+wt"):        # stores to the host pool written through at system scope
+        apm.apm_streamer_set_host_write_through(streamer, True)
+        mode = mode[:-3]
     if mode.startswith("direct"):
         parts = mode.split(":")
         n = int(parts[1]) if len(parts) > 1 else 0
@@ -69,6 +72,7 @@ def test_page_copy_roundtrip_bit_exact():
 
 @pytest.mark.parametrize("batch,slots,clip,mode", [(4, 2, 0.0, "staged"), (7, 3, 1.0, "staged"), (64, 2, 1.0, "staged"),
                                                    (5, 4, 1.0, "staged:7"), (200, 3, 0.0, "staged"),
+                                                   (5, 3, 1.0, "staged:9+wt"), (4, 2, 1.0, "direct:37:16+wt"),
                                                    (4, 2, 0.0, "staged_dma"), (7, 3, 1.0, "staged_dma"),
                                                    (4, 2, 0.0, "direct"), (4, 2, 1.0, "direct:7"), (4, 2, 1.0, "direct:37:16"),
                                                    (4, 2, 0.0, "direct:128:8")])
@@ -418,7 +422,7 @@ def test_copy_kernel_movers_on_small_and_odd_page_sizes(E, waves):
     apm.apm_pool_set_layout(dev.pool, model.tensors(model.p_flat), n_t)
     apm.apm_page_copy_async(host, 0, res.pool, 0, n_pages, apm.APM_P32)
     st = apm.apm_streamer_create(host, dev.pool, 5, 3)
-    set_mode(st, f"staged:{waves}")
+    set_mode(st, f"staged:{waves}" + ("+wt" if waves == 200 else ""))
     per = 4
     bounds = list(range(0, n_pages, per)) + [n_pages]
     layers = [(range(a, b), 0) for a, b in zip(bounds, bounds[1:])]
