@@ -93,18 +93,45 @@ void free_streamer(apm_streamer* s) {
 // streams of different groups overlap (49 GB/s each way).  So the pair is chosen by measurement:
 // a few candidate streams (the default stream among them) are timed on short concurrent copies
 // through the staging memory, and the best pair becomes (copy-in, copy-out).
-int pick_copy_streams(apm_streamer* s) {
-    constexpr int kNew = 4;
+// beside (with use_beside): a stream whose work must not be held up by the pair -- the producer's,
+// for the one-step-stale form.  Then the default stream is no candidate, and neither is a stream
+// that shares a hardware queue with `beside` (measured with a pair of short kernels): an event
+// wait enqueued on such a stream would hold up the kernels `beside` carries.
+int pick_copy_streams(apm_streamer* s, hipStream_t beside = nullptr, bool use_beside = false) {
+    constexpr int kNew = 5;
     constexpr size_t kProbe = (size_t)32 << 20;
     hipStream_t cand[kNew + 1] = {nullptr};  // cand[0] = the default stream
+    bool usable[kNew + 1];
     for (int k = 1; k <= kNew; ++k) APM_HIP(hipStreamCreateWithFlags(&cand[k], hipStreamNonBlocking));
+    for (int k = 0; k <= kNew; ++k) usable[k] = true;
+    if (use_beside) {
+        usable[0] = false;
+        int n_ok = 0;
+        bool ok[kNew + 1] = {false};
+        for (int k = 1; k <= kNew; ++k) {
+            int rc0 = streams_overlap(beside, cand[k], &ok[k]);
+            if (rc0 != APM_OK) {
+                for (int j = 1; j <= kNew; ++j) (void)hipStreamDestroy(cand[j]);
+                return rc0;
+            }
+            n_ok += ok[k] ? 1 : 0;
+        }
+        if (n_ok >= 2)  // otherwise: nothing to choose from, keep them all
+            for (int k = 1; k <= kNew; ++k) usable[k] = ok[k];
+    }
+    int first_ok = 0, second_ok = 0;
+    for (int k = kNew; k >= 1; --k)
+        if (usable[k]) { second_ok = first_ok; first_ok = k; }
+    if (first_ok == 0 || second_ok == 0) { first_ok = 1; second_ok = 2; }
     char* h = nullptr;
     if (hipHostMalloc((void**)&h, 2 * kProbe, hipHostMallocDefault) != hipSuccess) {
         // no pinned memory left for the probe (the host pool may have taken it all): go without
         (void)hipGetLastError();
-        s->s_in = cand[1];
-        s->s_out = cand[2];
-        for (int k = 3; k <= kNew; ++k) (void)hipStreamDestroy(cand[k]);
+        s->s_in = cand[first_ok];
+        s->s_out = cand[second_ok];
+        s->in_is_null = s->out_is_null = false;
+        for (int k = 1; k <= kNew; ++k)
+            if (k != first_ok && k != second_ok) (void)hipStreamDestroy(cand[k]);
         return APM_OK;
     }
     const size_t slot_bytes = (size_t)s->B * (size_t)s->dev->desc.page_elems * sizeof(float);
@@ -124,14 +151,14 @@ int pick_copy_streams(apm_streamer* s) {
         return APM_OK;
     };
     double warm;
-    int rc = timed(cand[1], cand[2], true, true, &warm);
-    if (rc == APM_OK) rc = timed(cand[1], cand[2], true, false, &s->probe_h2d);
-    if (rc == APM_OK) rc = timed(cand[1], cand[2], false, true, &s->probe_d2h);
-    int bi = 1, bj = 2;
+    int rc = timed(cand[first_ok], cand[second_ok], true, true, &warm);
+    if (rc == APM_OK) rc = timed(cand[first_ok], cand[second_ok], true, false, &s->probe_h2d);
+    if (rc == APM_OK) rc = timed(cand[first_ok], cand[second_ok], false, true, &s->probe_d2h);
+    int bi = first_ok, bj = second_ok;
     double best = 0.0;
     for (int i = 0; i <= kNew && rc == APM_OK; ++i)
         for (int j = 0; j <= kNew && rc == APM_OK; ++j) {
-            if (i == j) continue;
+            if (i == j || !usable[i] || !usable[j]) continue;
             double g;
             rc = timed(cand[i], cand[j], true, true, &g);
             if (rc == APM_OK && g > best) { best = g; bi = i; bj = j; }
@@ -500,9 +527,9 @@ int run_pipeline(apm_streamer* s, int what, int64_t step, const apm_hyper* hyper
         APM_HIP(hipStreamWaitEvent(caller, s->ev_done, 0));
         return APM_OK;
     }
-    // Copy-in is enqueued one batch ahead of the update that consumes it: on this runtime the
-    // device-to-host copy is a kernel whose enqueue blocks the host until the event it waits for
-    // has fired, and without the look-ahead the copy-in stream idles during each update.  (A
+    // Copy-in is enqueued one batch ahead of the update that consumes it: when this was written the
+    // runtime's device-to-host copy was a kernel whose enqueue blocked the host until the event it
+    // waits for had fired, and without the look-ahead the copy-in stream idled during each update.  (A
     // look-ahead of two batches was measured to make the runtime run the two copy directions one
     // after the other, 28 instead of 48 GB/s each way, so one it is.)
     auto copy_in = [&](int64_t b) -> int {
@@ -566,6 +593,21 @@ int pair_with_producer(apm_streamer* s, hipStream_t producer) {
     if (s->paired && s->paired_with == producer && s->paired_mode == s->mode) return APM_OK;
     APM_HIP(hipDeviceSynchronize());
     bool all = true;
+    if (s->mode == APM_STREAM_STAGED_DMA && s->s_in) {
+        // the calibrated pair may contain the default stream or share a hardware queue with the
+        // producer's stream: pick it again among streams that stay clear of the producer
+        if (!s->in_is_null) (void)hipStreamDestroy(s->s_in);
+        if (!s->out_is_null) (void)hipStreamDestroy(s->s_out);
+        s->s_in = s->s_out = nullptr;
+        s->in_is_null = s->out_is_null = false;
+        int rc = pick_copy_streams(s, producer, true);
+        if (rc != APM_OK) return rc;
+        bool a = false, b = false;
+        rc = streams_overlap(producer, s->s_in, &a);
+        if (rc == APM_OK) rc = streams_overlap(producer, s->s_out, &b);
+        if (rc != APM_OK) return rc;
+        all = a && b;
+    }
     hipStream_t* pipeline[2] = {&s->s_cmp, s->mode == APM_STREAM_STAGED ? &s->s_copy : nullptr};
     for (hipStream_t* st : pipeline) {
         if (!st || !*st) continue;
