@@ -321,6 +321,11 @@ def pcie_raw(host, devp, n_pages, E, state):
             "duplex_each_GBps": nbytes / tb / 1e9, "copy_bytes": run * E * 4}
 
 
+def note(msg):
+    """Progress on stderr (stdout carries the one JSON line): long legs say where they are."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 PCIE_GEN5_X16_RAW_GBPS = 64.0   # 32 GT/s x 16 lanes, 128b/130b: raw rate per direction
 
 
@@ -364,6 +369,7 @@ def time_streamer(args, streamer, hyper, first_step, n_pages, E, raw, total_para
     for name, mode in (("direct", apm.APM_STREAM_DIRECT), ("staged", apm.APM_STREAM_STAGED),
                        ("staged_dma", apm.APM_STREAM_STAGED_DMA)):
         apm.apm_streamer_set_mode(streamer, mode, args.direct_wavefronts)
+        note(f"streamed step, mode {name}")
         full()                                      # warm-up
         walls, boths = [], []
         for _ in range(args.stream_steps):
@@ -463,6 +469,7 @@ def scheduled_leg(args, wl, host, dev_pool, hyper, n_pages, first_step):
     t_plan = time.perf_counter() - t0
     streamer = apm.apm_streamer_create(host, dev_pool, (budget + 1) // 2, 2)
     stream = torch.cuda.current_stream()
+    note("schedule-driven step")
     apm.apm_streamer_step_scheduled(streamer, tasks, bounds, first_step, hyper, None, None, stream)
     ts = []
     for k in range(args.stream_steps):
@@ -515,6 +522,7 @@ def one_way_traffic_beside_a_producer(streamer, iters):
 
     t_p = timed(prod)
     out = {"producer": f"{reps} gelu calls over 2^28 bf16 values", "producer_alone_ms": t_p * 1e3}
+    note("elementwise producer beside one-way page traffic")
     for d, name, wt in ((1, "host_to_device_only", False), (2, "device_to_host_only", False), (3, "both_directions", False),
                         (2, "device_to_host_only_written_through", True), (3, "both_directions_written_through", True)):
         apm.apm_streamer_set_host_write_through(streamer, wt)
@@ -634,6 +642,7 @@ def lockfree_leg(args, streamer, dev_pool, hyper, update_ms):
         for name, mode, waves, per_wg in ways:
             apm.apm_streamer_set_mode(streamer, mode, waves, per_wg)
             apm.apm_streamer_set_host_write_through(streamer, name.endswith("written_through"))
+            note(f"one-step-stale beside {kind}: {name}")
             update_only()
             t_update = timed(update_only)
             t_sync = timed(sync_iter)
@@ -922,6 +931,7 @@ def configs_leg(args):
     torch.cuda.empty_cache()
 
     # ---- cfg 4: 13 B shape, fp32 state in pinned host memory ----------------------------------
+    note("13 B shape, state in host memory")
     out["cfg4_gpt_13b"] = cfg4_leg(args)
     return out
 
@@ -1157,13 +1167,16 @@ def main():
             out["active_page_list"] = moe_active_list_leg(args, wl, pool, hyper, plan, r["next_step"] + 100)
         if not args.no_streamed:
             apm.apm_pack_tensors(pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
+            note("streamed legs")
             out["streamed"] = streamed_leg(args, wl, pool, hyper, n_pages, r["next_step"])
         pool.destroy()
         torch.cuda.empty_cache()
         default_run = args.workload == "gpt_1p3b" and not (args.update_only or args.unfused or args.no_configs or
                                                             args.no_streamed)
         if default_run:
+            note("full-page reference")
             out["flat_1024pages"] = flat_reference_leg(args)
+            note("the other configurations")
             out["configs"] = configs_leg(args)
     else:
         # fp32 state never resident: the GPU pool holds G16/P16 only.  If the box cannot pin the
@@ -1187,6 +1200,7 @@ def main():
         dev_pool = apm.apm_pool_create(apm.APM_DEV_GPU, E, n_pages, state_mask=apm.B16_STATES)
         apm.apm_pack_tensors(dev_pool, apm.APM_G16, wl.tensors(wl.gen(1001, True, 1e-3)), wl.n_t)
         torch.cuda.synchronize()
+        note("streamed legs (state initialised in host memory)")
         s = streamed_leg_host_init(args, wl, dev_pool, hyper, n_pages)
         out["streamed"] = s
         out["value"] = s["params_per_s"]
@@ -1199,6 +1213,7 @@ def main():
         dev_pool.destroy()
 
     if not args.no_cpu_baseline:
+        note("oracle on the host cores")
         out["cpu_baseline"] = cpu_baseline(args, E, n_pages, clip, skip)
     print(json.dumps(out))
 
