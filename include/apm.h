@@ -463,8 +463,11 @@ int apm_schedule_plan(const int64_t* layer_offsets, const int64_t* layer_pages,
  * when the movements of its pages have completed; a write-back when its compute has.  A movement
  * may be issued later than its trigger allows: with the library's copy kernel as the mover, a
  * movement that is due waits for the next write-back and crosses the link in the same kernel (the
- * two directions in one kernel are a fifth faster than in two), at the latest two layers ahead of
- * the compute that needs its page, or right before that compute if it was not due earlier.
+ * two directions in one kernel are a fifth faster than in two), at the latest two units ahead of
+ * the compute that needs its page, or right before that compute if it was not due earlier; and a
+ * compute task is then carried out in units of at most 16 pages, each written back as soon as it
+ * has computed (the pages of the optimizer pass are independent), so a slot may become free
+ * earlier than the schedule says, never later.
  * The schedule is replayed on the host first and nothing is enqueued if it is unsound:
  * APM_ENOMEM (a movement task finds no free slot), APM_ESTATE (a layer computes before all its
  * pages were moved; a resident cache is set), APM_EINVAL (layers out of order, a page moved twice,

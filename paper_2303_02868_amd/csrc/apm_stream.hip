@@ -907,10 +907,8 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
         // (event-driven dispatch, Sec. 5 "Unified Scheduler") besides the slots it moves into.
         std::vector<hipEvent_t> reached((size_t)n_layers + 1, nullptr);
         hipEvent_t last_computed = nullptr;
-        // one layer's reduce + update on the compute stream, once its pages have arrived; records
-        // logical time i + 1, which is also what the write-back of the pages released here waits for
-        auto compute_layer = [&](int64_t i, hipEvent_t* computed) -> int {
-            const int64_t first = layer_first_page[i], n = layer_first_page[i + 1] - first;
+        // reduce + update of pages [first, first + n) on the compute stream, once they have arrived
+        auto compute_pages = [&](int64_t first, int64_t n, hipEvent_t* computed) -> int {
             if (n > 0) {
                 hipEvent_t last_wait = nullptr;
                 for (int64_t j = 0; j < n; ++j) {
@@ -933,9 +931,15 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
             int rc2 = new_event(computed);
             if (rc2 != APM_OK) return rc2;
             APM_HIP(hipEventRecord(*computed, s->s_cmp));
-            reached[(size_t)i + 1] = *computed;
             last_computed = *computed;
             return APM_OK;
+        };
+        // one layer's compute; records logical time i + 1, which is also what the write-back of the
+        // pages released here waits for
+        auto compute_layer = [&](int64_t i, hipEvent_t* computed) -> int {
+            int rc2 = compute_pages(layer_first_page[i], layer_first_page[i + 1] - layer_first_page[i], computed);
+            if (rc2 == APM_OK) reached[(size_t)i + 1] = *computed;
+            return rc2;
         };
 
         if (kcopy) {
@@ -948,10 +952,44 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
             // between two copy kernels), or, at the latest, right before that compute.  Slots need
             // no events here: the write-back that frees a slot precedes, in this one stream, the
             // movement that reuses it, because it precedes it in the task list.
-            struct Run { int64_t p0, s0, n; int32_t trig; };
+            //
+            // The optimizer's pages are independent, so a layer's compute task is carried out in
+            // units of at most kUnit pages, each written back as soon as it has computed: the
+            // first layer (the embedding, a seventh of a GPT-shaped model's pages) then need not
+            // arrive whole before anything flows back, nor the last one leave alone at the end.
+            // Slots are freed no later than the schedule says, and movements keep their place in
+            // the list, so the replay above still covers what is enqueued here.
+            constexpr int64_t kUnit = 16;  // measured on the 1.3 B shape: 8 / 16 / 32 pages -> 351 / 341 / 363 ms per step
+            std::vector<int64_t> unit_first;                       // first page of unit u (+ one end entry)
+            std::vector<int64_t> first_unit((size_t)n_layers + 1);  // layer i's first unit
+            for (int64_t i = 0; i < n_layers; ++i) {
+                first_unit[(size_t)i] = (int64_t)unit_first.size();
+                int64_t q = layer_first_page[i];
+                do {  // a layer without pages is one empty unit
+                    unit_first.push_back(q);
+                    q += kUnit;
+                } while (q < layer_first_page[i + 1]);
+            }
+            const int64_t n_units = (int64_t)unit_first.size();
+            first_unit[(size_t)n_layers] = n_units;
+            unit_first.push_back(N);
+            // what unit u releases: its own pages whose last access is their own layer, and, for a
+            // layer's last unit, the pages of earlier layers that the trace kept until this layer
+            std::vector<std::vector<int64_t>> unit_release((size_t)n_units);
+            for (int64_t i = 0; i < n_layers; ++i)
+                for (int64_t q : release_at[(size_t)i]) {
+                    int64_t u = first_unit[(size_t)i + 1] - 1;
+                    if (own[(size_t)q] == i) u = first_unit[(size_t)i] + (q - layer_first_page[i]) / kUnit;
+                    unit_release[(size_t)u].push_back(q);
+                }
+            for (auto& v : unit_release) std::sort(v.begin(), v.end());
+            // logical time in units: reached_u[u] = unit u - 1 has computed; trigger id t (a layer)
+            // is reached when the last unit of layer t - 1 has
+            std::vector<hipEvent_t> reached_u((size_t)n_units + 1, nullptr);
+            struct Run { int64_t p0, s0, n; int64_t trig; };       // trig: in units
             std::deque<Run> pend;                         // movement tasks not yet issued, in list order
             std::vector<uint8_t> pending((size_t)N, 0);
-            int64_t copy_at = 0;                          // logical time the copy stream is known to have passed
+            int64_t copy_at = 0;                          // logical time (units) the copy stream is known to have passed
             auto take = [&](int64_t want, std::vector<Run>* out) {
                 while (want > 0 && !pend.empty()) {
                     Run& r = pend.front();
@@ -965,11 +1003,12 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                     if (r.n == 0) pend.pop_front();
                 }
             };
-            // pages at the front of pend up to and including the last pending page of layers [a, b]
+            // pages at the front of pend up to and including the last pending page of units [a, b]
             auto pages_through = [&](int64_t a, int64_t b) -> int64_t {
-                if (b >= n_layers) b = n_layers - 1;
+                if (b >= n_units) b = n_units - 1;
+                if (a > b) return 0;
                 int64_t last = -1;
-                for (int64_t q = layer_first_page[a]; q < layer_first_page[b + 1]; ++q)
+                for (int64_t q = unit_first[(size_t)a]; q < unit_first[(size_t)b + 1]; ++q)
                     if (pending[(size_t)q]) last = q;
                 if (last < 0) return 0;
                 int64_t n = 0;
@@ -980,10 +1019,10 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                 return n;
             };
             auto exchange = [&](const std::vector<Run>& in, const std::vector<Run>& out) -> int {
-                int32_t trig = 0;
+                int64_t trig = 0;
                 for (const Run& r : in) trig = r.trig > trig ? r.trig : trig;
                 if (trig > copy_at) {
-                    APM_HIP(hipStreamWaitEvent(s_in, reached[(size_t)trig], 0));
+                    APM_HIP(hipStreamWaitEvent(s_in, reached_u[(size_t)trig], 0));
                     copy_at = trig;
                 }
                 // pieces of equal page counts in the two directions, cut where either list's run ends,
@@ -1041,38 +1080,50 @@ extern "C" int apm_streamer_step_scheduled(apm_streamer* s, const apm_task* task
                     while (k + n < n_tasks && tasks[k + n].op == APM_TASK_MOVE_TO_GPU && tasks[k + n].target == p0 + n &&
                            slot_seq[(size_t)(p0 + n)] == s0 + n && tasks[k + n].trigger_id == trig)
                         ++n;
-                    pend.push_back(Run{p0, s0, n, trig});
+                    pend.push_back(Run{p0, s0, n, first_unit[(size_t)trig]});
                     for (int64_t q = 0; q < n; ++q) pending[(size_t)(p0 + q)] = 1;
                     k += n;
                     continue;
                 }
                 const int64_t i = tasks[k].target;
                 ++k;
-                {   // what this layer still waits for goes now, alone
-                    std::vector<Run> in;
-                    take(pages_through(i, i), &in);
-                    rc = exchange(in, {});
+                for (int64_t u = first_unit[(size_t)i]; u < first_unit[(size_t)i + 1]; ++u) {
+                    {   // what this unit still waits for goes now, alone
+                        std::vector<Run> in;
+                        take(pages_through(u, u), &in);
+                        rc = exchange(in, {});
+                        if (rc != APM_OK) return rc;
+                    }
+                    hipEvent_t computed;
+                    rc = compute_pages(unit_first[(size_t)u], unit_first[(size_t)u + 1] - unit_first[(size_t)u], &computed);
+                    if (rc != APM_OK) return rc;
+                    reached_u[(size_t)u + 1] = computed;
+                    const std::vector<int64_t>& rel = unit_release[(size_t)u];
+                    if (rel.empty()) continue;
+                    std::vector<Run> out, in;
+                    for (size_t j = 0; j < rel.size();) {  // runs of consecutive pages and slots
+                        const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
+                        size_t m = 1;
+                        while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
+                        out.push_back(Run{q0, s0, (int64_t)m, 0});
+                        j += m;
+                    }
+                    // as many used elements in as go out (an exchange lasts as long as its longer
+                    // direction), but at least what the next two units need
+                    int64_t out_used = 0, in_used = 0, want = 0;
+                    for (int64_t q : rel) out_used += dev->plan.pages[(size_t)q].used;
+                    for (const Run& r : pend) {
+                        for (int64_t q = 0; q < r.n && in_used < out_used; ++q, ++want)
+                            in_used += dev->plan.pages[(size_t)(r.p0 + q)].used;
+                        if (in_used >= out_used) break;
+                    }
+                    const int64_t ahead = pages_through(u + 1, u + 2);
+                    take(ahead > want ? ahead : want, &in);
+                    APM_HIP(hipStreamWaitEvent(s_in, computed, 0));
+                    copy_at = u + 1;
+                    rc = exchange(in, out);
                     if (rc != APM_OK) return rc;
                 }
-                hipEvent_t computed;
-                rc = compute_layer(i, &computed);
-                if (rc != APM_OK) return rc;
-                const std::vector<int64_t>& rel = release_at[(size_t)i];
-                if (rel.empty()) continue;
-                std::vector<Run> out, in;
-                for (size_t j = 0; j < rel.size();) {  // runs of consecutive pages and slots
-                    const int64_t q0 = rel[j], s0 = slot_seq[(size_t)q0];
-                    size_t m = 1;
-                    while (j + m < rel.size() && rel[j + m] == q0 + (int64_t)m && slot_seq[(size_t)rel[j + m]] == s0 + (int64_t)m) ++m;
-                    out.push_back(Run{q0, s0, (int64_t)m, 0});
-                    j += m;
-                }
-                const int64_t ahead = pages_through(i + 1, i + 2);
-                take(ahead > (int64_t)rel.size() ? ahead : (int64_t)rel.size(), &in);
-                APM_HIP(hipStreamWaitEvent(s_in, computed, 0));
-                copy_at = i + 1;
-                rc = exchange(in, out);
-                if (rc != APM_OK) return rc;
             }
             if (!pend.empty()) return fail(APM_ESTATE, "internal: movement tasks left over after the last compute");
         } else {
