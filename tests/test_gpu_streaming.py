@@ -425,6 +425,7 @@ def test_copy_kernel_movers_on_small_and_odd_page_sizes(E, waves):
     set_mode(st, f"staged:{waves}" + ("+wt" if waves == 200 else ""))
     per = 4
     bounds = list(range(0, n_pages, per)) + [n_pages]
+    bounds = sorted(bounds + [bounds[1], bounds[3], n_pages])       # three layers without pages, one of them last
     layers = [(range(a, b), 0) for a, b in zip(bounds, bounds[1:])]
     tasks, _ = apm.apm_schedule_plan(layers, None, 12 * E, 11 * 12 * E)     # 11 of the 15 slots
     norm_r = torch.zeros(n_pages, dtype=torch.float32, device=DEV)
